@@ -1,0 +1,163 @@
+/*
+ * isp.h -- C ABI of the MI355X (gfx950) sparse GNN hot path.
+ *
+ * Operations (iSpLib, arXiv 2403.14853):
+ *   SpMM   Y = A X, sum reduction, A in CSR, X dense row-major fp32      (abstract; Sections 1, 3.4, 3.5)
+ *   SpMM backward dX = A^T dY through a CSR transpose that is built once
+ *          and kept in A's handle                                        (Section 3.3, cache-enabled backprop)
+ *   SDDMM  one dot product per stored entry of A (gives dA of SpMM)       (Section 1)
+ *   FusedMM SDDMM -> edge function -> SpMM in one pass, edge matrix never
+ *          written; sigmoid instance, forward and backward               (Section 1(a))
+ *
+ * General conventions
+ *   - Every array pointer is a DEVICE pointer on the current HIP device unless its name starts
+ *     with h_.  The caller allocates and owns every buffer, including workspaces, and must keep
+ *     them alive and unmodified while a handle that refers to them lives.  The library never
+ *     allocates or frees device memory.
+ *   - CSR: indptr int64[n_rows+1], indices int32[nnz], values fp32[nnz] or NULL (all ones).
+ *     Columns inside a row may be unsorted and may repeat; a repeated column is a separate
+ *     stored entry (SpMM adds them, SDDMM emits one output per stored entry).
+ *   - Dense matrices are fp32 row-major; ld* is the distance between rows in elements (>= d).
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Compute calls are
+ *     asynchronous on it.  isp_csr_build and a cache-missing isp_csr_transpose_cached
+ *     synchronise the stream once, to read a few counters back.
+ *   - Outputs are overwritten (Y = A X, not +=).  n_rows = 0 and nnz = 0 are valid.
+ *   - Every function returns a status; nothing throws or aborts across this boundary.  After a
+ *     failure isp_last_error() returns a thread-local message.
+ *   - Calls that use the same handle (or a handle and its cached transpose) on different streams
+ *     at the same time race on the handle's scratch (hub-row partial sums); serialise them.
+ *   - Results are run-to-run bitwise deterministic: no floating-point atomics are used.
+ */
+#ifndef ISP_H
+#define ISP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct isp_csr isp_csr_t; /* opaque; host-side struct owned by the library */
+
+typedef enum {
+  ISP_OK = 0,
+  ISP_EINVAL = 1,       /* NULL pointer, negative size, d <= 0, ld < d, workspace too small or misaligned */
+  ISP_EBADCSR = 2,      /* indptr not monotone / indptr[0] != 0 / indptr[n] != nnz / column out of range */
+  ISP_ENOMEM = 3,       /* host allocation failed */
+  ISP_EHIP = 4,         /* a HIP runtime call failed; text in isp_last_error() */
+  ISP_EUNSUPPORTED = 5  /* size beyond what the index types hold, or an unknown op / flag */
+} isp_status;
+
+/* flags of isp_csr_build */
+#define ISP_TRUSTED 1u /* skip the structural validation pass (the caller vouches for the CSR) */
+/* flags of isp_sddmm */
+#define ISP_SCALE_BY_A 1u /* multiply each dot product by the entry's value */
+/* op of isp_fusedmm / isp_fusedmm_backward */
+#define ISP_OP_SIGMOID 0
+
+/* Summary of a handle's row classes and work partition (all counts are rows unless named). */
+typedef struct {
+  int64_t n_rows, n_cols, nnz;
+  int64_t max_degree;
+  int64_t bin_rows[5]; /* degree 0 | 1..4 | 5..32 | 33..hub_threshold | > hub_threshold (hub) */
+  int64_t bin_nnz[5];
+  int32_t hub_threshold;  /* rows longer than this are split by nnz                */
+  int32_t segment_len;    /* nonzeros per hub segment                              */
+  int32_t block_cost;     /* target (nnz + rows) per wavefront work item            */
+  int32_t n_row_blocks;   /* wavefront work items made of whole short rows          */
+  int32_t n_hub_rows;
+  int32_t n_segments;     /* wavefront work items made of hub-row segments          */
+  int32_t is_transpose;   /* 1 for a handle returned by isp_csr_transpose_cached    */
+  int32_t has_cached_transpose;
+} isp_csr_info_t;
+
+/* Bytes of device workspace isp_csr_build needs for a matrix of this shape (upper bound). */
+isp_status isp_csr_build_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz, size_t* bytes);
+
+/*
+ * Wrap the caller's CSR arrays in a handle and prepare the work partition: rows are classed by
+ * degree; short rows are grouped into contiguous row blocks of about equal (nnz + rows); hub rows
+ * (degree > hub threshold) are cut into fixed-length nonzero segments (Section 1(b): balanced
+ * scheduling; Section 3.5: CSR operand).  Integer work only.
+ *   indptr/indices/values: borrowed device arrays (values may be NULL).
+ *   workspace: device memory, 256-byte aligned, >= isp_csr_build_workspace() bytes; borrowed
+ *              until isp_csr_destroy.
+ *   flags: 0 or ISP_TRUSTED.  Without ISP_TRUSTED a malformed CSR yields ISP_EBADCSR and no handle.
+ * Synchronises `stream` once.  n_rows, n_cols < 2^31 - 1 and nnz < 2^31 - 1, else ISP_EUNSUPPORTED.
+ */
+isp_status isp_csr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
+                         const int32_t* indices, const float* values, void* workspace,
+                         size_t workspace_bytes, unsigned flags, void* stream, isp_csr_t** out);
+
+/* Bytes of device workspace the first isp_csr_transpose_cached call on A needs. */
+isp_status isp_csr_transpose_workspace(const isp_csr_t* A, size_t* bytes);
+
+/*
+ * A^T as a CSR handle, built on the first call and kept inside A (Section 3.3): later calls
+ * return the stored handle, do no device work and ignore workspace.  The transpose is the
+ * stable one: entries of a column keep their order of appearance in A, so the result is unique:
+ *   t_indptr  int64[n_cols+1], t_indices int32[nnz] (source rows), perm int32[nnz] (position in
+ *   A of each transposed entry), t_values[q] = values[perm[q]] (absent when A has no values).
+ * These arrays live in `workspace` (256-byte aligned, borrowed until isp_csr_destroy(A)).
+ *   *At: handle owned by A (never destroy it yourself).  *was_cached: 1 on a cache hit (may be NULL).
+ * A cache miss synchronises `stream` once.
+ */
+isp_status isp_csr_transpose_cached(isp_csr_t* A, void* workspace, size_t workspace_bytes,
+                                    void* stream, const isp_csr_t** At, int* was_cached);
+
+/* Device pointers of a handle's CSR arrays (perm is NULL for a handle that is not a transpose;
+ * values is NULL when absent).  Any out pointer may be NULL.  For inspection and tests. */
+isp_status isp_csr_export(const isp_csr_t* A, const int64_t** indptr, const int32_t** indices,
+                          const float** values, const int32_t** perm);
+
+/* Fill *info (host struct) with the handle's shape, degree classes and partition sizes. */
+isp_status isp_csr_info(const isp_csr_t* A, isp_csr_info_t* info);
+
+/*
+ * SpMM, sum reduction: Y[i, 0:d] = sum over stored entries p of row i of values[p] * X[indices[p], 0:d]
+ * (abstract; Sections 1, 3.4).  X has A.n_cols rows, Y has A.n_rows rows.  Backward dX = A^T dY is the
+ * same call on the handle from isp_csr_transpose_cached (Section 3.3).  X and Y must not overlap.
+ */
+isp_status isp_spmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
+                    void* stream);
+
+/*
+ * SDDMM (Section 1): out[p] = <U[i, 0:d], V[indices[p], 0:d]> for every stored entry p of every
+ * row i, in A's CSR order; with ISP_SCALE_BY_A multiplied by values[p].  U has n_rows rows, V has
+ * n_cols rows, out has nnz elements.  With U = dY and V = X this is dA of Y = A X.
+ */
+isp_status isp_sddmm(const isp_csr_t* A, const float* U, int64_t ldu, const float* V, int64_t ldv,
+                     int32_t d, unsigned flags, float* out, void* stream);
+
+/*
+ * FusedMM forward (Section 1(a)), op = ISP_OP_SIGMOID, A square:
+ *   s_p = 1 / (1 + exp(-<X[i], X[j]>)), j = indices[p];  Y[i] = sum_p values[p] * s_p * X[j].
+ * The per-edge scores are never written to memory.  d <= 1024, else ISP_EUNSUPPORTED.
+ */
+isp_status isp_fusedmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,
+                       int64_t ldy, void* stream);
+
+/*
+ * FusedMM backward: dX for upstream gradient dY of the forward above.  With g = dY and
+ * dz_p = values[p] <g_i, x_j> s_p (1 - s_p):
+ *   dX[i] = sum_{p in row i} dz_p x_j  +  sum_{p: indices[p] = i} (values[p] s_p g_r + dz_p x_r),
+ * r = row of p.  The second sum runs over row i of the cached transpose, so
+ * isp_csr_transpose_cached(A) must have succeeded before; otherwise ISP_EINVAL.
+ */
+isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const float* dY, int64_t lddy,
+                                int32_t d, int op, float* dX, int64_t lddx, void* stream);
+
+/* Free the host-side handle and its cached transpose handle.  Never touches caller buffers.  NULL ok. */
+void isp_csr_destroy(isp_csr_t* A);
+
+/* Message of the calling thread's most recent failure ("" if none).  Static storage. */
+const char* isp_last_error(void);
+
+/* Library version string, e.g. "isp-gfx950 0.1". */
+const char* isp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ISP_H */

@@ -1,0 +1,285 @@
+// CSR ingest: structural validation, degree classes and the wavefront work partition.
+//
+// Rows are classed by degree (0 | 1..4 | 5..32 | 33..hub_t | hub).  Short rows are grouped
+// into contiguous row blocks of about block_cost units, one unit per nonzero plus one per row
+// (a row's output write costs about as much as one gathered input row).  Hub rows
+// (degree > hub_t) never share a block; each is cut into segments of seg_len nonzeros whose
+// partial sums are combined later in a fixed order.  Everything here is integer work and runs
+// once per graph (balanced scheduling: paper Section 1(b); CSR operand: Section 3.5).
+#include <stdlib.h>
+#include <new>
+#include "isp_internal.h"
+
+namespace {
+
+struct build_counters {
+  unsigned long long bin_rows[5];
+  unsigned long long bin_nnz[5];
+  unsigned long long max_degree;
+  int err;            // bit 0: indptr malformed, bit 1: column index out of range
+  int n_blocks, n_hub, n_seg;
+};
+
+struct partition_params {
+  int block_cost, hub_t, seg_len;
+};
+
+int env_int(const char* name, int dflt, int lo, int hi) {
+  const char* s = getenv(name);
+  if (!s || !*s) return dflt;
+  long v = strtol(s, nullptr, 10);
+  if (v < lo) v = lo;
+  if (v > hi) v = hi;
+  return (int)v;
+}
+
+partition_params get_params() {
+  partition_params p;
+  p.block_cost = env_int("ISP_BLOCK_COST", 256, 16, 1 << 20);
+  p.hub_t = env_int("ISP_HUB_THRESHOLD", 512, 8, 1 << 24);
+  p.seg_len = env_int("ISP_SEGMENT_LEN", 512, 8, 1 << 24);
+  return p;
+}
+
+__global__ void k_zero_counters(build_counters* c) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *c = build_counters{};
+}
+
+__device__ inline int degree_bin(long long deg, int hub_t) {
+  if (deg <= 0) return 0;
+  if (deg > hub_t) return 4;
+  if (deg <= 4) return 1;
+  if (deg <= 32) return 2;
+  return 3;
+}
+
+// One thread per row: degree, class, cost, segment count; indptr checks; class histogram.
+__global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ indptr, int64_t n_rows, int64_t nnz,
+                                                  partition_params pp, int32_t* __restrict__ cost,
+                                                  int32_t* __restrict__ hubflag, int32_t* __restrict__ nseg,
+                                                  build_counters* __restrict__ ctr) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  long long deg = 0;
+  bool bad = false;
+  const bool live = i < n_rows;
+  if (live) {
+    const int64_t a = indptr[i], b = indptr[i + 1];
+    deg = b - a;
+    bad = deg < 0 || a < 0 || b > nnz || (i == 0 && a != 0) || (i == n_rows - 1 && b != nnz);
+    if (bad) deg = 0;
+    const bool hub = deg > pp.hub_t;
+    cost[i] = hub ? 0 : (int32_t)deg + 1;
+    hubflag[i] = hub ? 1 : 0;
+    nseg[i] = hub ? (int32_t)((deg + pp.seg_len - 1) / pp.seg_len) : 0;
+  }
+  if (__any(bad) && lane == 0) atomicOr(&ctr->err, 1);
+  const int bin = live ? degree_bin(deg, pp.hub_t) : -1;
+#pragma unroll
+  for (int b = 0; b < 5; ++b) {
+    const unsigned long long m = __ballot(bin == b);
+    long long s = (bin == b) ? deg : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0 && m) {
+      atomicAdd(&ctr->bin_rows[b], (unsigned long long)__popcll(m));
+      if (s) atomicAdd(&ctr->bin_nnz[b], (unsigned long long)s);
+    }
+  }
+  long long mx = deg;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    long long t = __shfl_xor(mx, o);
+    mx = t > mx ? t : mx;
+  }
+  if (lane == 0 && mx > 0) atomicMax(&ctr->max_degree, (unsigned long long)mx);
+  int tot = live ? (int)((deg > pp.hub_t) ? (deg + pp.seg_len - 1) / pp.seg_len : 0) : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o);
+  if (lane == 0 && tot) atomicAdd(&ctr->n_seg, tot);
+}
+
+// Column indices must lie in [0, n_cols).
+__global__ void __launch_bounds__(256) k_check_indices(const int32_t* __restrict__ indices, int64_t nnz, int64_t n_cols,
+                                                       build_counters* __restrict__ ctr) {
+  bool bad = false;
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * blockDim.x) {
+    const int32_t c = indices[p];
+    bad |= (c < 0 || c >= n_cols);
+  }
+  if (__any(bad) && (threadIdx.x & (ISP_WAVE - 1)) == 0) atomicOr(&ctr->err, 2);
+}
+
+// Block boundaries forced by hub rows: a hub row starts a block and so does the row after it.
+__global__ void __launch_bounds__(256) k_mark_rows(const int32_t* __restrict__ hubflag, int64_t n_rows,
+                                                   int32_t* __restrict__ mark) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_rows) return;
+  mark[i] = (i == 0 || hubflag[i] || hubflag[i - 1]) ? 1 : 0;
+}
+
+// Balanced boundaries: block b starts at the first row whose cumulative short-row cost reaches b * block_cost.
+__global__ void __launch_bounds__(256) k_mark_balanced(const int64_t* __restrict__ cum_cost, int64_t n_rows,
+                                                       int64_t n_bal, int block_cost, int32_t* __restrict__ mark) {
+  const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= n_bal) return;
+  const int64_t target = b * (int64_t)block_cost;
+  int64_t lo = 0, hi = n_rows;  // first i in [0, n_rows] with cum_cost[i] >= target
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (cum_cost[mid] >= target) hi = mid; else lo = mid + 1;
+  }
+  if (lo < n_rows) mark[lo] = 1;
+}
+
+__global__ void __launch_bounds__(256) k_compact(const int32_t* __restrict__ mark, const int32_t* __restrict__ mpos,
+                                                 const int32_t* __restrict__ hubflag, const int32_t* __restrict__ hpos,
+                                                 const int32_t* __restrict__ nseg, const int32_t* __restrict__ segbase,
+                                                 int64_t n_rows, int32_t* __restrict__ blk_row,
+                                                 int32_t* __restrict__ hub_rows, int32_t* __restrict__ hub_seg_ptr,
+                                                 int32_t* __restrict__ seg_hub, build_counters* __restrict__ ctr,
+                                                 int64_t max_blocks, int64_t max_hub, int64_t max_seg) {
+  // The bounds only bite for a malformed indptr (the host then reports ISP_EBADCSR); they keep
+  // every write inside the workspace in that case too.
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) {
+    const int nb = mpos[n_rows], nh = hpos[n_rows];
+    if (nb <= max_blocks) blk_row[nb] = (int32_t)n_rows;
+    if (nh <= max_hub) hub_seg_ptr[nh] = segbase[n_rows];
+    ctr->n_blocks = nb;
+    ctr->n_hub = nh;
+  }
+  if (i >= n_rows) return;
+  if (mark[i] && mpos[i] < max_blocks) blk_row[mpos[i]] = (int32_t)i;
+  if (hubflag[i]) {
+    const int h = hpos[i], s0 = segbase[i], ns = nseg[i];
+    if (h < max_hub) {
+      hub_rows[h] = (int32_t)i;
+      hub_seg_ptr[h] = s0;
+    }
+    for (int s = 0; s < ns && s0 + s < max_seg; ++s) seg_hub[s0 + s] = h;
+  }
+}
+
+struct ws_layout {
+  size_t counters, cost, hubflag, nseg, cum_cost, mark, mpos, hpos, segbase, scan_tmp;
+  size_t blk_row, hub_rows, hub_seg_ptr, seg_hub, partials, total;
+  int64_t max_blocks, max_hub, max_seg;
+};
+
+ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
+  ws_layout L;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += isp_align(bytes); return o; };
+  const int64_t n_bal = (nnz + n_rows) / pp.block_cost + 2;
+  int64_t max_hub = nnz / ((int64_t)pp.hub_t + 1);
+  if (max_hub > n_rows) max_hub = n_rows;
+  int64_t max_blocks = n_bal + 2 * max_hub + 2;
+  if (max_blocks > n_rows + 1) max_blocks = n_rows + 1;
+  const int64_t max_seg = nnz / pp.seg_len + max_hub + 1;
+  L.max_blocks = max_blocks; L.max_hub = max_hub; L.max_seg = max_seg;
+  L.counters = take(sizeof(build_counters));
+  L.cost = take((size_t)(n_rows + 1) * 4);
+  L.hubflag = take((size_t)(n_rows + 1) * 4);
+  L.nseg = take((size_t)(n_rows + 1) * 4);
+  L.cum_cost = take((size_t)(n_rows + 1) * 8);
+  L.mark = take((size_t)(n_rows + 1) * 4);
+  L.mpos = take((size_t)(n_rows + 1) * 4);
+  L.hpos = take((size_t)(n_rows + 1) * 4);
+  L.segbase = take((size_t)(n_rows + 1) * 4);
+  L.scan_tmp = take(isp_scan_tmp_bytes(n_rows + 1));
+  L.blk_row = take((size_t)(max_blocks + 1) * 4);
+  L.hub_rows = take((size_t)(max_hub + 1) * 4);
+  L.hub_seg_ptr = take((size_t)(max_hub + 2) * 4);
+  L.seg_hub = take((size_t)(max_seg + 1) * 4);
+  L.partials = take((size_t)(max_seg + 1) * ISP_PARTIAL_TILE * sizeof(float));
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
+size_t isp_partition_workspace(int64_t n_rows, int64_t nnz) { return make_layout(n_rows, nnz, get_params()).total; }
+
+isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
+                            const int32_t* indices, const float* values, void* ws, size_t ws_bytes, bool validate,
+                            hipStream_t s, isp_csr** out) {
+  const partition_params pp = get_params();
+  const ws_layout L = make_layout(n_rows, nnz, pp);
+  if (ws_bytes < L.total) return isp_fail(ISP_EINVAL, "workspace too small: %zu < %zu bytes", ws_bytes, L.total);
+  if (((uintptr_t)ws & 255) != 0) return isp_fail(ISP_EINVAL, "workspace must be 256-byte aligned");
+  char* base = (char*)ws;
+  build_counters* ctr = (build_counters*)(base + L.counters);
+  int32_t* cost = (int32_t*)(base + L.cost);
+  int32_t* hubflag = (int32_t*)(base + L.hubflag);
+  int32_t* nseg = (int32_t*)(base + L.nseg);
+  int64_t* cum_cost = (int64_t*)(base + L.cum_cost);
+  int32_t* mark = (int32_t*)(base + L.mark);
+  int32_t* mpos = (int32_t*)(base + L.mpos);
+  int32_t* hpos = (int32_t*)(base + L.hpos);
+  int32_t* segbase = (int32_t*)(base + L.segbase);
+  void* scan_tmp = base + L.scan_tmp;
+  int32_t* blk_row = (int32_t*)(base + L.blk_row);
+  int32_t* hub_rows = (int32_t*)(base + L.hub_rows);
+  int32_t* hub_seg_ptr = (int32_t*)(base + L.hub_seg_ptr);
+  int32_t* seg_hub = (int32_t*)(base + L.seg_hub);
+
+  k_zero_counters<<<1, 64, 0, s>>>(ctr);
+  ISP_LAUNCH_CHECK();
+  const unsigned row_grid = (unsigned)((n_rows + 255) / 256);
+  if (n_rows > 0) {
+    k_row_pass<<<row_grid, 256, 0, s>>>(indptr, n_rows, nnz, pp, cost, hubflag, nseg, ctr);
+    ISP_LAUNCH_CHECK();
+  }
+  if (validate && nnz > 0) {
+    k_check_indices<<<2048, 256, 0, s>>>(indices, nnz, n_cols, ctr);
+    ISP_LAUNCH_CHECK();
+  }
+  isp_status st;
+  if ((st = isp_scan_i32_to_i64(cost, cum_cost, n_rows, scan_tmp, s)) != ISP_OK) return st;
+  if (n_rows > 0) {
+    k_mark_rows<<<row_grid, 256, 0, s>>>(hubflag, n_rows, mark);
+    ISP_LAUNCH_CHECK();
+    // total short-row cost <= nnz + n_rows, so this many targets cover it
+    const int64_t n_bal = (nnz + n_rows) / pp.block_cost + 1;
+    k_mark_balanced<<<(unsigned)((n_bal + 255) / 256), 256, 0, s>>>(cum_cost, n_rows, n_bal, pp.block_cost, mark);
+    ISP_LAUNCH_CHECK();
+  }
+  if ((st = isp_scan_i32_to_i32(mark, mpos, n_rows, scan_tmp, s)) != ISP_OK) return st;
+  if ((st = isp_scan_i32_to_i32(hubflag, hpos, n_rows, scan_tmp, s)) != ISP_OK) return st;
+  if ((st = isp_scan_i32_to_i32(nseg, segbase, n_rows, scan_tmp, s)) != ISP_OK) return st;
+  k_compact<<<row_grid > 0 ? row_grid : 1, 256, 0, s>>>(mark, mpos, hubflag, hpos, nseg, segbase, n_rows, blk_row,
+                                                       hub_rows, hub_seg_ptr, seg_hub, ctr, L.max_blocks,
+                                                       L.max_hub, L.max_seg);
+  ISP_LAUNCH_CHECK();
+  build_counters h;
+  ISP_HIP(hipMemcpyAsync(&h, ctr, sizeof(h), hipMemcpyDeviceToHost, s));
+  ISP_HIP(hipStreamSynchronize(s));
+  if (h.err & 1) return isp_fail(ISP_EBADCSR, "indptr is not a monotone offset array from 0 to nnz");
+  if (h.err & 2) return isp_fail(ISP_EBADCSR, "a column index lies outside [0, n_cols)");
+  if (h.n_blocks > L.max_blocks || h.n_hub > L.max_hub || h.n_seg > L.max_seg)
+    return isp_fail(ISP_EINVAL, "internal: partition exceeds its bounds (%d/%lld blocks, %d/%lld hubs, %d/%lld segs)",
+                    h.n_blocks, (long long)L.max_blocks, h.n_hub, (long long)L.max_hub, h.n_seg, (long long)L.max_seg);
+
+  int device = 0;
+  ISP_HIP(hipGetDevice(&device));
+  isp_csr* A = new (std::nothrow) isp_csr();
+  if (!A) return isp_fail(ISP_ENOMEM, "host allocation of the handle failed");
+  A->device = device;
+  A->v.n_rows = n_rows; A->v.n_cols = n_cols; A->v.nnz = nnz;
+  A->v.indptr = indptr; A->v.indices = indices; A->v.values = values;
+  A->v.blk_row = blk_row; A->v.n_blocks = h.n_blocks;
+  A->v.hub_rows = hub_rows; A->v.hub_seg_ptr = hub_seg_ptr; A->v.seg_hub = seg_hub;
+  A->v.n_hub = h.n_hub; A->v.n_seg = h.n_seg;
+  A->v.hub_t = pp.hub_t; A->v.seg_len = pp.seg_len;
+  A->v.partials = (float*)(base + L.partials);
+  A->perm = nullptr; A->At = nullptr; A->is_transpose = false;
+  isp_csr_info_t& I = A->info;
+  I.n_rows = n_rows; I.n_cols = n_cols; I.nnz = nnz; I.max_degree = (int64_t)h.max_degree;
+  for (int b = 0; b < 5; ++b) { I.bin_rows[b] = (int64_t)h.bin_rows[b]; I.bin_nnz[b] = (int64_t)h.bin_nnz[b]; }
+  I.hub_threshold = pp.hub_t; I.segment_len = pp.seg_len; I.block_cost = pp.block_cost;
+  I.n_row_blocks = h.n_blocks; I.n_hub_rows = h.n_hub; I.n_segments = h.n_seg;
+  I.is_transpose = 0; I.has_cached_transpose = 0;
+  *out = A;
+  return ISP_OK;
+}

@@ -1,0 +1,206 @@
+// FusedMM, sigmoid instance (paper Section 1(a): SDDMM and SpMM combined into one operation):
+//   forward   s_p = sigmoid(<x_i, x_j>),  y_i = sum_p a_p s_p x_j            (j = column of p)
+//   backward  dz_p = a_p <g_i, x_j> s_p (1 - s_p)
+//             dX_i = sum_{p in row i} dz_p x_j + sum_{p in column i} (a_p s_p g_r + dz_p x_r)
+// The per-edge scores exist only in registers: each gathered row x_j is used for the dot product
+// and for the accumulation in the same pass, and the backward recomputes the scores instead of
+// reading them back.  The column sum of the backward runs over the rows of the cached transpose.
+#include "row_stream.h"
+
+namespace {
+using namespace isp_dev;
+
+__device__ inline float sigmoidf_fast(float z) { return 1.f / (1.f + __expf(-z)); }
+
+template <int VEC, int T>
+__device__ inline float dot_lanes(const float (&a)[T][VEC], const float (&b)[T][VEC]) {
+  float s = 0.f;
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) s = fmaf(a[tt][v], b[tt][v], s);
+  return s;
+}
+
+template <int VEC, int T>
+__device__ inline void load_row(const float* __restrict__ M, int64_t ld, int row, const int (&col)[T],
+                                const bool (&on)[T], float (&o)[T][VEC]) {
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) o[tt][v] = 0.f;
+    if (on[tt]) load_vec<VEC>(M + (int64_t)row * ld + col[tt], o[tt]);
+  }
+}
+
+constexpr int pick_u(int regs_per_edge) { return regs_per_edge >= 8 ? 2 : (regs_per_edge >= 4 ? 4 : 8); }
+
+// ---- forward ---------------------------------------------------------------------------------
+template <int VEC_, int T_, bool HAS_VAL_>
+struct fwd_policy {
+  static constexpr int VEC = VEC_, T = T_, NG = 1, U = pick_u(VEC_ * T_);
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false;
+  struct args { const float* src[1]; int64_t ld[1]; };
+  struct row_state { float xi[T][VEC]; };
+  __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
+                                          const bool (&on)[T]) {
+    load_row<VEC, T>(pa.src[0], pa.ld[0], row, col, on, rs.xi);
+  }
+  __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[1][T][VEC],
+                                     float (&acc)[T][VEC], const bool (&)[T]) {
+    const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xi, x[0]));
+    const float w = a * sigmoidf_fast(z);
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[tt][v] = fmaf(w, x[0][tt][v], acc[tt][v]);
+  }
+};
+
+// ---- backward, row pass over A: dX_i = sum_p dz_p x_j ----------------------------------------
+template <int VEC_, int T_, bool HAS_VAL_>
+struct bwd_row_policy {
+  static constexpr int VEC = VEC_, T = T_, NG = 1, U = pick_u(VEC_ * T_);
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false;
+  struct args { const float* src[1]; int64_t ld[1]; const float* G; int64_t ldg; };
+  struct row_state { float xi[T][VEC]; float gi[T][VEC]; };
+  __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
+                                          const bool (&on)[T]) {
+    load_row<VEC, T>(pa.src[0], pa.ld[0], row, col, on, rs.xi);
+    load_row<VEC, T>(pa.G, pa.ldg, row, col, on, rs.gi);
+  }
+  __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[1][T][VEC],
+                                     float (&acc)[T][VEC], const bool (&)[T]) {
+    const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xi, x[0]));
+    const float gd = wave_allreduce(dot_lanes<VEC, T>(rs.gi, x[0]));
+    const float sg = sigmoidf_fast(z);
+    const float dz = a * gd * sg * (1.f - sg);
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[tt][v] = fmaf(dz, x[0][tt][v], acc[tt][v]);
+  }
+};
+
+// ---- backward, row pass over A^T: dX_j += sum_p (a_p s_p g_i + dz_p x_i) ---------------------
+// Row j of A^T lists the source rows i of the entries in column j; x_i and g_i are gathered.
+template <int VEC_, int T_, bool HAS_VAL_>
+struct bwd_col_policy {
+  static constexpr int VEC = VEC_, T = T_, NG = 2, U = pick_u(2 * VEC_ * T_);
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = true;
+  struct args { const float* src[2]; int64_t ld[2]; };  // src[0] = X, src[1] = dY
+  struct row_state { float xj[T][VEC]; };
+  __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
+                                          const bool (&on)[T]) {
+    load_row<VEC, T>(pa.src[0], pa.ld[0], row, col, on, rs.xj);
+  }
+  __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[2][T][VEC],
+                                     float (&acc)[T][VEC], const bool (&)[T]) {
+    const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xj, x[0]));
+    const float gd = wave_allreduce(dot_lanes<VEC, T>(rs.xj, x[1]));
+    const float sg = sigmoidf_fast(z);
+    const float w = a * sg;
+    const float dz = a * gd * sg * (1.f - sg);
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[tt][v] = fmaf(w, x[1][tt][v], fmaf(dz, x[0][tt][v], acc[tt][v]));
+  }
+};
+
+template <class P>
+__global__ void __launch_bounds__(ISP_WG) k_fused(isp_view A, const int64_t* __restrict__ indptr,
+                                                  const int32_t* __restrict__ indices,
+                                                  const float* __restrict__ values, typename P::args pa, int d,
+                                                  float* __restrict__ Y, int64_t ldy) {
+  stream_item<P>(A, indptr, indices, values, pa, d, 0, Y, ldy);
+}
+
+template <int VEC, int T, bool ACC>
+__global__ void __launch_bounds__(ISP_WG) k_fused_fixup(isp_view A, int d, float* __restrict__ Y, int64_t ldy) {
+  hub_fixup<VEC, T, ACC>(A, d, 0, Y, ldy);
+}
+
+template <class P>
+isp_status run_pass(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s) {
+  const isp_view& v = A->v;
+  const int n_items = v.n_blocks + v.n_seg;
+  if (n_items > 0) {
+    const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
+    k_fused<P><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
+    ISP_LAUNCH_CHECK();
+  }
+  if (v.n_hub > 0) {
+    const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
+    k_fused_fixup<P::VEC, P::T, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, Y, ldy);
+    ISP_LAUNCH_CHECK();
+  }
+  return ISP_OK;
+}
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// 0: float4 lanes, 1: float2 lanes, 2..4: scalar lanes with 1, 2, 4 column groups
+int pick_shape(int d, bool ok4, bool ok2) {
+  if (d > 2 * ISP_WAVE && d % 4 == 0 && ok4) return 0;
+  if (d > ISP_WAVE && d <= 2 * ISP_WAVE && d % 2 == 0 && ok2) return 1;
+  if (d <= ISP_WAVE) return 2;
+  if (d <= 2 * ISP_WAVE) return 3;
+  return 4;
+}
+
+#define ISP_SHAPE_SWITCH(shape, has_val, CALL)                                   \
+  switch (shape) {                                                              \
+    case 0: if (has_val) { CALL(4, 1, true); } else { CALL(4, 1, false); } break; \
+    case 1: if (has_val) { CALL(2, 1, true); } else { CALL(2, 1, false); } break; \
+    case 2: if (has_val) { CALL(1, 1, true); } else { CALL(1, 1, false); } break; \
+    case 3: if (has_val) { CALL(1, 2, true); } else { CALL(1, 2, false); } break; \
+    default: if (has_val) { CALL(1, 4, true); } else { CALL(1, 4, false); } break; \
+  }
+
+}  // namespace
+
+isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
+                              hipStream_t s) {
+  const bool ok4 = ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16);
+  const bool ok2 = ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8);
+  const int shape = pick_shape(d, ok4, ok2);
+  const bool hv = A->v.values != nullptr;
+  isp_status st = ISP_OK;
+#define ISP_FWD(V, T, HV)                         \
+  {                                               \
+    using P = fwd_policy<V, T, HV>;               \
+    P::args pa;                                   \
+    pa.src[0] = X;                                \
+    pa.ld[0] = ldx;                               \
+    st = run_pass<P>(A, pa, d, Y, ldy, s);        \
+  }
+  ISP_SHAPE_SWITCH(shape, hv, ISP_FWD)
+#undef ISP_FWD
+  return st;
+}
+
+isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx, const float* G, int64_t ldg,
+                                  int32_t d, float* dX, int64_t lddx, hipStream_t s) {
+  const bool ok4 = ldx % 4 == 0 && ldg % 4 == 0 && lddx % 4 == 0 && aligned(X, 16) && aligned(G, 16) && aligned(dX, 16);
+  const bool ok2 = ldx % 2 == 0 && ldg % 2 == 0 && lddx % 2 == 0 && aligned(X, 8) && aligned(G, 8) && aligned(dX, 8);
+  const int shape = pick_shape(d, ok4, ok2);
+  const bool hv = A->v.values != nullptr;
+  isp_status st = ISP_OK;
+#define ISP_BWD(V, T, HV)                                  \
+  {                                                        \
+    using P1 = bwd_row_policy<V, T, HV>;                   \
+    P1::args p1;                                           \
+    p1.src[0] = X; p1.ld[0] = ldx; p1.G = G; p1.ldg = ldg; \
+    st = run_pass<P1>(A, p1, d, dX, lddx, s);              \
+    if (st == ISP_OK) {                                    \
+      using P2 = bwd_col_policy<V, T, HV>;                 \
+      P2::args p2;                                         \
+      p2.src[0] = X; p2.ld[0] = ldx; p2.src[1] = G; p2.ld[1] = ldg; \
+      st = run_pass<P2>(A->At, p2, d, dX, lddx, s);        \
+    }                                                      \
+  }
+  ISP_SHAPE_SWITCH(shape, hv, ISP_BWD)
+#undef ISP_BWD
+  return st;
+}

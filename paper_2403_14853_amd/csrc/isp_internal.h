@@ -1,0 +1,77 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "isp.h"
+
+#define ISP_WAVE 64
+#define ISP_WG 256                 // threads per workgroup in the row-streaming kernels
+#define ISP_WAVES_PER_WG (ISP_WG / ISP_WAVE)
+#define ISP_PARTIAL_TILE 256       // floats per hub-segment partial row (one column tile)
+
+// Device-side view of a CSR with its work partition.  Passed to kernels by value.
+struct isp_view {
+  int64_t n_rows, n_cols, nnz;
+  const int64_t* indptr;
+  const int32_t* indices;
+  const float* values;     // may be NULL
+  // work items: [0, n_blocks) are row blocks [blk_row[b], blk_row[b+1]) made of whole short rows;
+  // [n_blocks, n_blocks + n_seg) are segments of hub rows.
+  const int32_t* blk_row;  // n_blocks + 1
+  int32_t n_blocks;
+  const int32_t* hub_rows; // n_hub row ids, ascending
+  const int32_t* hub_seg_ptr;  // n_hub + 1: first segment of each hub row
+  const int32_t* seg_hub;  // n_seg: index into hub_rows of each segment
+  int32_t n_hub, n_seg;
+  int32_t hub_t, seg_len;
+  float* partials;         // n_seg * ISP_PARTIAL_TILE floats
+};
+
+struct isp_csr {
+  isp_view v;
+  const int32_t* perm;     // transposes only
+  isp_csr_info_t info;
+  int device;
+  isp_csr* At;             // cached transpose (owned), or NULL
+  bool is_transpose;
+};
+
+// ---- error plumbing --------------------------------------------------------------------------
+isp_status isp_fail(isp_status st, const char* fmt, ...);
+#define ISP_HIP(call)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return isp_fail(ISP_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+#define ISP_LAUNCH_CHECK() ISP_HIP(hipGetLastError())
+
+static inline size_t isp_align(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- device scans (scan.hip) -----------------------------------------------------------------
+// Exclusive prefix sums; out has n + 1 entries (out[n] = total).  tmp must hold
+// isp_scan_tmp_bytes(n) bytes.  in and out may not alias.
+size_t isp_scan_tmp_bytes(int64_t n);
+isp_status isp_scan_i32_to_i64(const int32_t* in, int64_t* out, int64_t n, void* tmp, hipStream_t s);
+isp_status isp_scan_i32_to_i32(const int32_t* in, int32_t* out, int64_t n, void* tmp, hipStream_t s);
+
+// ---- partition (csr_build.hip) ---------------------------------------------------------------
+size_t isp_partition_workspace(int64_t n_rows, int64_t nnz);
+isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
+                            const int32_t* indices, const float* values, void* ws, size_t ws_bytes,
+                            bool validate, hipStream_t s, isp_csr** out);
+
+// ---- transpose (transpose.hip) ---------------------------------------------------------------
+size_t isp_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_values);
+isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_t s);
+
+// ---- compute (spmm.hip, sddmm.hip, fusedmm.hip) ------------------------------------------------
+isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
+                           hipStream_t s);
+isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv,
+                            int32_t d, bool scale, float* out, hipStream_t s);
+isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
+                              hipStream_t s);
+isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx, const float* G, int64_t ldg,
+                                  int32_t d, float* dX, int64_t lddx, hipStream_t s);

@@ -1,0 +1,245 @@
+// Row-streaming skeleton shared by SpMM and the FusedMM kernels (gfx950, wave64).
+//
+// One wavefront owns one work item: either a block of whole short rows or one segment of a hub
+// row.  The item's nonzeros form one contiguous range of the CSR arrays; the wave reads them 64
+// at a time (lane l holds entry p + l), broadcasts each (column, value) pair through
+// v_readlane into scalar registers, and gathers the addressed dense row with all 64 lanes
+// spread across the feature dimension (VEC consecutive floats per lane, T column groups of
+// 64*VEC).  U gathers are issued back to back before the first is consumed so that each wave
+// keeps several 64*VEC*4-byte requests in flight.  A row's result is written when its last
+// nonzero has been added; a hub segment's result goes to the handle's partial-sum scratch and is
+// combined by a second, fixed-order kernel (no floating-point atomics anywhere).
+#pragma once
+#include "isp_internal.h"
+
+namespace isp_dev {
+
+template <int VEC> struct vec_of;
+template <> struct vec_of<1> { using type = float; };
+template <> struct vec_of<2> { using type = float2; };
+template <> struct vec_of<4> { using type = float4; };
+
+template <int VEC>
+__device__ inline void load_vec(const float* __restrict__ p, float (&o)[VEC]) {
+  using V = typename vec_of<VEC>::type;
+  const V v = *reinterpret_cast<const V*>(p);
+  if constexpr (VEC == 1) { o[0] = v; }
+  else if constexpr (VEC == 2) { o[0] = v.x; o[1] = v.y; }
+  else { o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
+}
+
+template <int VEC>
+__device__ inline void store_vec(float* __restrict__ p, const float (&o)[VEC]) {
+  using V = typename vec_of<VEC>::type;
+  V v;
+  if constexpr (VEC == 1) { v = o[0]; }
+  else if constexpr (VEC == 2) { v.x = o[0]; v.y = o[1]; }
+  else { v.x = o[0]; v.y = o[1]; v.z = o[2]; v.w = o[3]; }
+  *reinterpret_cast<V*>(p) = v;
+}
+
+__device__ inline int bcast_i(int v, int src_lane) { return __builtin_amdgcn_readlane(v, src_lane); }
+__device__ inline float bcast_f(float v, int src_lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+// Sum over the 64 lanes, result in every lane (xor butterfly).
+__device__ inline float wave_allreduce(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// What a work item covers.
+struct item_range {
+  int64_t p, p_end;      // nonzero range
+  int row, row_last;     // block items: rows [row, row_last); segment items: [seg, seg + 1)
+  int src_row;           // matrix row the nonzeros belong to at the start (segment: the hub row)
+  bool is_seg, skip;
+};
+
+__device__ inline item_range locate_item(const isp_view& A, const int64_t* __restrict__ indptr, int item) {
+  item_range r;
+  r.is_seg = item >= A.n_blocks;
+  r.skip = false;
+  if (!r.is_seg) {
+    r.row = A.blk_row[item];
+    r.row_last = A.blk_row[item + 1];
+    r.src_row = r.row;
+    r.p = indptr[r.row];
+    r.p_end = indptr[r.row_last];
+    // a block made of one hub row is empty here: its nonzeros are covered by segment items
+    r.skip = (r.row_last == r.row + 1) && (r.p_end - r.p > A.hub_t);
+  } else {
+    const int s = item - A.n_blocks;
+    const int h = A.seg_hub[s];
+    const int hr = A.hub_rows[h];
+    const int64_t rs = indptr[hr], re = indptr[hr + 1];
+    r.p = rs + (int64_t)(s - A.hub_seg_ptr[h]) * A.seg_len;
+    r.p_end = (r.p + A.seg_len < re) ? r.p + A.seg_len : re;
+    r.row = s;
+    r.row_last = s + 1;
+    r.src_row = hr;
+  }
+  return r;
+}
+
+// Policy P supplies:
+//   static constexpr int VEC, T, NG, U;  static constexpr bool HAS_VAL, ACCUMULATE;
+//   struct args { const float* src[NG]; int64_t ld[NG]; ... };
+//   struct row_state;  static void row_begin(args, row_state&, int row, cols...)
+//   static void edge(args, row_state&, float a, x[NG][T][VEC], acc[T][VEC], on[T])
+template <class P>
+__device__ inline void stream_item(const isp_view& A, const int64_t* __restrict__ indptr,
+                                   const int32_t* __restrict__ indices, const float* __restrict__ values,
+                                   const typename P::args& pa, int d, int k0, float* __restrict__ Y, int64_t ldy) {
+  constexpr int VEC = P::VEC, T = P::T, NG = P::NG, U = P::U;
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6)));
+  if (item >= A.n_blocks + A.n_seg) return;
+  item_range it = locate_item(A, indptr, item);
+  if (it.skip) return;
+
+  int col[T];      // first feature column of this lane in each group, relative to the matrix
+  bool on[T];
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+    col[tt] = k0 + (tt * ISP_WAVE + lane) * VEC;
+    on[tt] = col[tt] < d;
+  }
+  // where results go: Y rows for block items, partial rows for segments
+  float* __restrict__ out = it.is_seg ? A.partials : Y;
+  const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
+  const int out_k0 = it.is_seg ? k0 : 0;  // partial rows hold only the current column tile
+
+  int row = it.row;
+  const int row_last = it.row_last;
+  int64_t p = it.p;
+  const int64_t p_end = it.p_end;
+  const int64_t never = INT64_MAX;
+  int64_t row_end, row_end_next;
+  if (it.is_seg) { row_end = p_end; row_end_next = never; }
+  else {
+    row_end = indptr[row + 1];
+    row_end_next = (row + 1 < row_last) ? indptr[row + 2] : never;
+  }
+
+  float acc[T][VEC];
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[tt][v] = 0.f;
+
+  typename P::row_state rs;
+  int src_row = it.src_row;
+
+  auto write_row = [&]() {
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt) {
+      if (on[tt]) {
+        float* o = out + (int64_t)row * ldo + (col[tt] - out_k0);
+        if (P::ACCUMULATE && !it.is_seg) {
+          float old[VEC];
+          load_vec<VEC>(o, old);
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[tt][v] += old[v];
+        }
+        store_vec<VEC>(o, acc[tt]);
+      }
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[tt][v] = 0.f;
+    }
+  };
+  auto next_row = [&]() {
+    ++row;
+    ++src_row;
+    row_end = row_end_next;
+    row_end_next = (row + 1 < row_last) ? indptr[row + 2] : never;
+  };
+
+  // leading empty rows
+  while (row < row_last && row_end == p) { write_row(); next_row(); }
+  if (row < row_last) P::row_begin(pa, rs, src_row, col, on);
+
+  while (p < p_end) {
+    const int64_t left = p_end - p;
+    const int cnt = left < ISP_WAVE ? (int)left : ISP_WAVE;
+    int c = 0;
+    float a = 1.f;
+    if (lane < cnt) {
+      c = __builtin_nontemporal_load(indices + p + lane);
+      if (P::HAS_VAL) a = __builtin_nontemporal_load(values + p + lane);
+    }
+    for (int t = 0; t < cnt; t += U) {
+      float x[U][NG][T][VEC];
+      const bool full = t + U <= cnt;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (full || t + u < cnt) {
+          const int cj = bcast_i(c, t + u);
+#pragma unroll
+          for (int g = 0; g < NG; ++g) {
+            const float* __restrict__ src = pa.src[g] + (int64_t)cj * pa.ld[g];
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt) {
+              if (on[tt]) load_vec<VEC>(src + col[tt], x[u][g][tt]);
+              else {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) x[u][g][tt][v] = 0.f;
+              }
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (full || t + u < cnt) {
+          const float av = P::HAS_VAL ? bcast_f(a, t + u) : 1.f;
+          P::edge(pa, rs, av, x[u], acc, on);
+          if (p + t + u + 1 == row_end) {
+            write_row();
+            next_row();
+            while (row < row_last && row_end == p + t + u + 1) { write_row(); next_row(); }
+            if (row < row_last) P::row_begin(pa, rs, src_row, col, on);
+          }
+        }
+      }
+    }
+    p += cnt;
+  }
+}
+
+// Fixed-order combination of hub-segment partial sums: one wave per hub row adds its segments'
+// partial rows in segment order and writes (or, with ACCUMULATE, adds to) the output row.
+template <int VEC, int T, bool ACCUMULATE>
+__device__ inline void hub_fixup(const isp_view& A, int d, int k0, float* __restrict__ Y, int64_t ldy) {
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int h = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6)));
+  if (h >= A.n_hub) return;
+  const int s0 = A.hub_seg_ptr[h], s1 = A.hub_seg_ptr[h + 1];
+  const int row = A.hub_rows[h];
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+    const int rel = (tt * ISP_WAVE + lane) * VEC;
+    if (k0 + rel >= d) continue;
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    for (int s = s0; s < s1; ++s) {
+      float t[VEC];
+      load_vec<VEC>(A.partials + (int64_t)s * ISP_PARTIAL_TILE + rel, t);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[v] += t[v];
+    }
+    float* o = Y + (int64_t)row * ldy + k0 + rel;
+    if (ACCUMULATE) {
+      float old[VEC];
+      load_vec<VEC>(o, old);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[v] += old[v];
+    }
+    store_vec<VEC>(o, acc);
+  }
+}
+
+}  // namespace isp_dev

@@ -1,0 +1,247 @@
+// Stable CSR transpose, built once per graph and cached in the source handle (paper Section 3.3:
+// cache-enabled backpropagation; the cached expression is read as A^T in CSR form).
+//
+// "Stable" = entries of one column keep their order of appearance in A, which makes the result
+// unique and lets it be compared bit for bit.  It is computed as a least-significant-digit radix
+// sort of the column indices (8-bit digits) that carries the source position as payload; every
+// pass is a stable counting sort: per-tile digit histograms -> exclusive scan over
+// (digit, tile) -> scatter with ranks taken in source order.  Integer work only, no atomics on
+// anything order-dependent.
+#include "isp_internal.h"
+
+namespace {
+
+constexpr int RS_THREADS = 256;
+constexpr int RS_WAVES = RS_THREADS / ISP_WAVE;
+constexpr int RS_ROUNDS = 16;                       // keys per lane
+constexpr int RS_WAVE_KEYS = RS_ROUNDS * ISP_WAVE;  // contiguous keys owned by one wave
+constexpr int RS_TILE = RS_WAVE_KEYS * RS_WAVES;    // keys per workgroup
+constexpr int RS_RADIX = 256;
+
+// Source row of every stored entry, written by the same work items the compute kernels use.
+__global__ void __launch_bounds__(ISP_WG) k_row_of(isp_view A, int32_t* __restrict__ row_of) {
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int item = blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6);
+  if (item >= A.n_blocks + A.n_seg) return;
+  if (item < A.n_blocks) {
+    const int r0 = A.blk_row[item], r1 = A.blk_row[item + 1];
+    if (r1 == r0 + 1 && A.indptr[r1] - A.indptr[r0] > A.hub_t) return;  // hub row: written by its segments
+    for (int r = r0; r < r1; ++r) {
+      const int64_t e = A.indptr[r + 1];
+      for (int64_t p = A.indptr[r] + lane; p < e; p += ISP_WAVE) row_of[p] = r;
+    }
+  } else {
+    const int s = item - A.n_blocks;
+    const int h = A.seg_hub[s];
+    const int hr = A.hub_rows[h];
+    const int64_t re = A.indptr[hr + 1];
+    const int64_t b = A.indptr[hr] + (int64_t)(s - A.hub_seg_ptr[h]) * A.seg_len;
+    const int64_t e = (b + A.seg_len < re) ? b + A.seg_len : re;
+    for (int64_t p = b + lane; p < e; p += ISP_WAVE) row_of[p] = hr;
+  }
+}
+
+// Per-tile digit histogram; table is digit-major: table[digit * n_tiles + tile].
+__global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t* __restrict__ keys, int64_t n, int shift,
+                                                           int n_tiles, int32_t* __restrict__ table) {
+  __shared__ int hist[RS_RADIX];
+  hist[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * RS_TILE;
+  for (int i = threadIdx.x; i < RS_TILE; i += RS_THREADS) {
+    const int64_t q = base + i;
+    if (q < n) atomicAdd(&hist[(keys[q] >> shift) & (RS_RADIX - 1)], 1);
+  }
+  __syncthreads();
+  table[(int64_t)threadIdx.x * n_tiles + blockIdx.x] = hist[threadIdx.x];
+}
+
+// Stable scatter of one pass.  Wave w of a workgroup owns the contiguous keys
+// [tile + w * RS_WAVE_KEYS, +RS_WAVE_KEYS) and walks them 64 at a time in source order, so a
+// key's rank among equal digits = (equal digits in earlier tiles: scanned table) + (in earlier
+// waves of the tile) + (earlier rounds of this wave) + (lower lanes of this round).
+template <bool FIRST>
+__global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(const int32_t* __restrict__ keys_in,
+                                                              const int32_t* __restrict__ pay_in, int64_t n, int shift,
+                                                              int n_tiles, const int32_t* __restrict__ table_scanned,
+                                                              int32_t* __restrict__ keys_out,
+                                                              int32_t* __restrict__ pay_out) {
+  __shared__ volatile int wave_cnt[RS_WAVES][RS_RADIX];
+  __shared__ int wave_base[RS_WAVES][RS_RADIX];
+  const int lane = threadIdx.x & (ISP_WAVE - 1), w = threadIdx.x / ISP_WAVE;
+  for (int i = threadIdx.x; i < RS_WAVES * RS_RADIX; i += RS_THREADS) (&wave_cnt[0][0])[i] = 0;
+  __syncthreads();
+  const int64_t wbase = (int64_t)blockIdx.x * RS_TILE + (int64_t)w * RS_WAVE_KEYS;
+  const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int key[RS_ROUNDS], pay[RS_ROUNDS], rank[RS_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < RS_ROUNDS; ++r) {
+    const int64_t q = wbase + r * ISP_WAVE + lane;
+    const bool valid = q < n;
+    key[r] = valid ? keys_in[q] : 0;
+    pay[r] = valid ? (FIRST ? (int32_t)q : pay_in[q]) : 0;
+    const int dg = (key[r] >> shift) & (RS_RADIX - 1);
+    unsigned long long m = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const unsigned long long bal = __ballot((dg >> b) & 1);
+      m &= ((dg >> b) & 1) ? bal : ~bal;
+    }
+    // m = valid lanes of this round holding the same digit as this lane
+    const int before = valid ? wave_cnt[w][dg] : 0;
+    rank[r] = before + __popcll(m & lt_mask);
+    if (valid && (m & lt_mask) == 0) wave_cnt[w][dg] = before + __popcll(m);  // lowest lane of the group
+  }
+  __syncthreads();
+  {  // thread t owns digit t: where each wave's keys of that digit start in the output
+    const int dg = threadIdx.x;
+    int run = table_scanned[(int64_t)dg * n_tiles + blockIdx.x];
+#pragma unroll
+    for (int ww = 0; ww < RS_WAVES; ++ww) {
+      wave_base[ww][dg] = run;
+      run += wave_cnt[ww][dg];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < RS_ROUNDS; ++r) {
+    const int64_t q = wbase + r * ISP_WAVE + lane;
+    if (q < n) {
+      const int dg = (key[r] >> shift) & (RS_RADIX - 1);
+      const int dst = wave_base[w][dg] + rank[r];
+      keys_out[dst] = key[r];
+      pay_out[dst] = pay[r];
+    }
+  }
+}
+
+// From the sorted (column, source position) pairs: perm, source rows, values and the row offsets
+// of A^T (found where the sorted column changes; empty columns get the next offset).
+__global__ void __launch_bounds__(256) k_transpose_finish(const int32_t* __restrict__ skey,
+                                                          const int32_t* __restrict__ spay, int64_t nnz,
+                                                          int64_t n_cols, const int32_t* __restrict__ row_of,
+                                                          const float* __restrict__ values,
+                                                          int64_t* __restrict__ t_indptr,
+                                                          int32_t* __restrict__ t_indices, int32_t* __restrict__ perm,
+                                                          float* __restrict__ t_values) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= nnz) return;
+  const int32_t c = skey[q];
+  const int32_t src = spay[q];
+  perm[q] = src;
+  t_indices[q] = row_of[src];
+  if (values) t_values[q] = values[src];
+  const int32_t prev = q > 0 ? skey[q - 1] : -1;
+  // (the clamp only matters for an unvalidated CSR with a column >= n_cols)
+  const int64_t c_hi = c < n_cols ? (int64_t)c : n_cols - 1;
+  for (int64_t cc = (int64_t)prev + 1; cc <= c_hi; ++cc) t_indptr[cc] = q;
+  if (q == nnz - 1)
+    for (int64_t cc = (int64_t)c + 1; cc <= n_cols; ++cc) t_indptr[cc] = nnz;
+}
+
+__global__ void __launch_bounds__(256) k_fill_i64(int64_t* __restrict__ a, int64_t n, int64_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) a[i] = v;
+}
+
+struct t_layout {
+  size_t t_indptr, t_indices, perm, t_values, row_of, key_a, key_b, pay_a, pay_b, table, table_scanned, scan_tmp,
+      part, total;
+  int64_t n_tiles;
+};
+
+t_layout make_layout(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_values) {
+  (void)n_rows;
+  t_layout L;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += isp_align(bytes); return o; };
+  L.n_tiles = (nnz + RS_TILE - 1) / RS_TILE;
+  const size_t e = (size_t)(nnz + 1) * 4;
+  L.t_indptr = take((size_t)(n_cols + 1) * 8);
+  L.t_indices = take(e);
+  L.perm = take(e);
+  L.t_values = take(has_values ? e : 0);
+  L.row_of = take(e);
+  L.key_a = take(e);
+  L.key_b = take(e);
+  L.pay_a = take(e);
+  L.pay_b = take(e);
+  const int64_t tbl = (int64_t)RS_RADIX * L.n_tiles;
+  L.table = take((size_t)(tbl + 1) * 4);
+  L.table_scanned = take((size_t)(tbl + 1) * 4);
+  L.scan_tmp = take(isp_scan_tmp_bytes(tbl + 1));
+  L.part = take(isp_partition_workspace(n_cols, nnz));
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
+size_t isp_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_values) {
+  return make_layout(n_rows, n_cols, nnz, has_values).total;
+}
+
+isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_t s) {
+  const isp_view& v = A->v;
+  const int64_t nnz = v.nnz, n_cols = v.n_cols, n_rows = v.n_rows;
+  const bool has_values = v.values != nullptr;
+  const t_layout L = make_layout(n_rows, n_cols, nnz, has_values);
+  if (!ws) return isp_fail(ISP_EINVAL, "transpose workspace is NULL");
+  if (ws_bytes < L.total) return isp_fail(ISP_EINVAL, "transpose workspace too small: %zu < %zu bytes", ws_bytes, L.total);
+  if (((uintptr_t)ws & 255) != 0) return isp_fail(ISP_EINVAL, "workspace must be 256-byte aligned");
+  char* base = (char*)ws;
+  int64_t* t_indptr = (int64_t*)(base + L.t_indptr);
+  int32_t* t_indices = (int32_t*)(base + L.t_indices);
+  int32_t* perm = (int32_t*)(base + L.perm);
+  float* t_values = has_values ? (float*)(base + L.t_values) : nullptr;
+  int32_t* row_of = (int32_t*)(base + L.row_of);
+  int32_t* key[2] = {(int32_t*)(base + L.key_a), (int32_t*)(base + L.key_b)};
+  int32_t* pay[2] = {(int32_t*)(base + L.pay_a), (int32_t*)(base + L.pay_b)};
+  int32_t* table = (int32_t*)(base + L.table);
+  int32_t* table_scanned = (int32_t*)(base + L.table_scanned);
+  void* scan_tmp = base + L.scan_tmp;
+
+  if (nnz == 0) {
+    k_fill_i64<<<(unsigned)((n_cols + 1 + 255) / 256), 256, 0, s>>>(t_indptr, n_cols + 1, 0);
+    ISP_LAUNCH_CHECK();
+  } else {
+    const int n_items = v.n_blocks + v.n_seg;
+    k_row_of<<<(unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG), ISP_WG, 0, s>>>(v, row_of);
+    ISP_LAUNCH_CHECK();
+    int bits = 1;
+    while (bits < 31 && ((int64_t)1 << bits) < n_cols) ++bits;
+    const int n_pass = (bits + 7) / 8;
+    const int n_tiles = (int)L.n_tiles;
+    const int32_t* kin = v.indices;
+    const int32_t* pin = nullptr;
+    for (int pass = 0; pass < n_pass; ++pass) {
+      const int shift = 8 * pass;
+      k_radix_hist<<<n_tiles, RS_THREADS, 0, s>>>(kin, nnz, shift, n_tiles, table);
+      ISP_LAUNCH_CHECK();
+      isp_status st = isp_scan_i32_to_i32(table, table_scanned, (int64_t)RS_RADIX * n_tiles, scan_tmp, s);
+      if (st != ISP_OK) return st;
+      int32_t* kout = key[pass & 1];
+      int32_t* pout = pay[pass & 1];
+      if (pass == 0)
+        k_radix_scatter<true><<<n_tiles, RS_THREADS, 0, s>>>(kin, pin, nnz, shift, n_tiles, table_scanned, kout, pout);
+      else
+        k_radix_scatter<false><<<n_tiles, RS_THREADS, 0, s>>>(kin, pin, nnz, shift, n_tiles, table_scanned, kout, pout);
+      ISP_LAUNCH_CHECK();
+      kin = kout;
+      pin = pout;
+    }
+    k_transpose_finish<<<(unsigned)((nnz + 255) / 256), 256, 0, s>>>(kin, pin, nnz, n_cols, row_of, v.values, t_indptr,
+                                                                    t_indices, perm, t_values);
+    ISP_LAUNCH_CHECK();
+  }
+  isp_csr* At = nullptr;
+  isp_status st = isp_build_handle(n_cols, n_rows, nnz, t_indptr, t_indices, t_values, base + L.part,
+                                   ws_bytes - L.part, false, s, &At);
+  if (st != ISP_OK) return st;
+  At->perm = perm;
+  At->is_transpose = true;
+  At->info.is_transpose = 1;
+  A->At = At;
+  A->info.has_cached_transpose = 1;
+  return ISP_OK;
+}

@@ -1,0 +1,61 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol include/isp.h declares,
+and its argument checks that need no device work behave as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2403_14853_amd as isp
+from paper_2403_14853_amd import binding
+
+
+def _header_symbols(repo_root):
+    text = open(os.path.join(repo_root, "include", "isp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(isp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    lib = isp.load_library()
+    declared = _header_symbols(repo_root)
+    assert declared, "no declarations found in include/isp.h"
+    for name in declared:
+        assert hasattr(lib, name), "libisp.so does not export %s" % name
+    assert sorted(binding.EXPORTED_SYMBOLS) == declared
+    assert lib.isp_version().decode().startswith("isp-gfx950")
+
+
+def test_binding_names_follow_the_abi():
+    for name in ("csr_build", "csr_transpose_cached", "spmm", "sddmm", "fusedmm", "fusedmm_backward"):
+        assert callable(getattr(isp, name))
+
+
+def test_argument_checks_without_device_work():
+    lib = isp.load_library()
+    need = ctypes.c_size_t()
+    assert lib.isp_csr_build_workspace(10, 10, 20, None) == 1  # ISP_EINVAL
+    assert b"NULL" in lib.isp_last_error()
+    assert lib.isp_csr_build_workspace(-1, 10, 20, ctypes.byref(need)) == 1
+    assert lib.isp_csr_build_workspace(10, 10, 2**31, ctypes.byref(need)) == 5  # ISP_EUNSUPPORTED
+    assert lib.isp_csr_build_workspace(1000, 1000, 5000, ctypes.byref(need)) == 0 and need.value > 0
+    small = need.value
+    assert lib.isp_csr_build_workspace(100000, 100000, 5000000, ctypes.byref(need)) == 0 and need.value > small
+    h = ctypes.c_void_p()
+    assert lib.isp_csr_build(4, 4, 4, None, None, None, None, 0, 0, None, ctypes.byref(h)) == 1
+    assert lib.isp_csr_build(4, 4, 4, None, None, None, None, 0, 0, None, None) == 1
+    # NULL handles
+    assert lib.isp_spmm(None, None, 4, 4, None, 4, None) == 1
+    assert lib.isp_sddmm(None, None, 4, None, 4, 4, 0, None, None) == 1
+    assert lib.isp_fusedmm(None, None, 4, 4, 0, None, 4, None) == 1
+    assert lib.isp_fusedmm_backward(None, None, 4, None, 4, 4, 0, None, 4, None) == 1
+    assert lib.isp_csr_transpose_workspace(None, ctypes.byref(need)) == 1
+    assert lib.isp_csr_info(None, None) == 1
+    lib.isp_csr_destroy(None)  # documented no-op
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libisp.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()

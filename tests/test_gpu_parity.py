@@ -1,0 +1,201 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
+Structural outputs bit-exact; floats within 1e-5 * magnitude + 1e-6 per element."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import graphgen
+import oracle
+import paper_2403_14853_amd as isp
+from gpu_util import assert_close, build, dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print("\n[case] %s" % request.node.nodeid, flush=True)
+    yield
+    torch.cuda.synchronize()
+
+
+def _partition_env(hub=None, seg=None, block=None):
+    for k, v in (("ISP_HUB_THRESHOLD", hub), ("ISP_SEGMENT_LEN", seg), ("ISP_BLOCK_COST", block)):
+        if v is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = str(v)
+
+
+@pytest.fixture
+def small_partition():
+    """Small hub threshold / segment / block sizes so that tiny graphs span many work items,
+    hub segments and ragged tails."""
+    _partition_env(hub=24, seg=16, block=32)
+    yield
+    _partition_env()
+
+
+def _check_transpose(A, w_indptr, w_indices, w_values, n_rows, n_cols):
+    At, was = isp.csr_transpose_cached(A)
+    assert not was
+    At2, was2 = isp.csr_transpose_cached(A)
+    assert was2 and At2 is At
+    ti, tj, tv, perm = At.export()
+    o_ti, o_tj, o_perm, o_tv = oracle.transpose(n_rows, n_cols, w_indptr, w_indices, w_values)
+    assert np.array_equal(ti.cpu().numpy(), o_ti)
+    assert np.array_equal(tj.cpu().numpy(), o_tj)
+    assert np.array_equal(perm.cpu().numpy(), o_perm)
+    if w_values is not None:
+        assert np.array_equal(tv.cpu().numpy(), o_tv)
+    else:
+        assert tv is None
+    return At, (o_ti, o_tj, o_tv)
+
+
+def _run_all_ops(indptr, indices, values, n_rows, n_cols, d, seed, fused=True):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n_cols, d)).astype(np.float32)
+    G = rng.standard_normal((n_rows, d)).astype(np.float32)
+    A = build(indptr, indices, values, n_cols=n_cols)
+    info = A.info()
+    assert info["nnz"] == len(indices) and sum(info["bin_rows"]) == n_rows and sum(info["bin_nnz"]) == len(indices)
+    deg = np.diff(indptr)
+    assert info["max_degree"] == (deg.max() if n_rows else 0)
+    assert info["n_hub_rows"] == int((deg > info["hub_threshold"]).sum())
+    # forward
+    Xd, Gd = dev(X), dev(G)
+    Y = torch.full((n_rows, d), float("nan"), device="cuda")
+    isp.spmm(A, Xd, Y)
+    ref, mag = oracle.spmm(indptr, indices, values, X)
+    assert_close(Y, ref, mag, "spmm")
+    # determinism
+    Y2 = torch.empty_like(Y)
+    isp.spmm(A, Xd, Y2)
+    assert torch.equal(Y, Y2)
+    # cached transpose + backward
+    At, (o_ti, o_tj, o_tv) = _check_transpose(A, indptr, indices, values, n_rows, n_cols)
+    dX = torch.full((n_cols, d), float("nan"), device="cuda")
+    isp.spmm(At, Gd, dX)
+    ref, mag = oracle.spmm(o_ti, o_tj, o_tv, G)
+    assert_close(dX, ref, mag, "spmm backward")
+    # sddmm (dA) and its scaled form
+    out = torch.full((len(indices),), float("nan"), device="cuda")
+    isp.sddmm(A, Gd, Xd, out)
+    ref, mag = oracle.sddmm(indptr, indices, values, G, X)
+    assert_close(out, ref, mag, "sddmm")
+    isp.sddmm(A, Gd, Xd, out, scale_by_a=True)
+    ref, mag = oracle.sddmm(indptr, indices, values, G, X, scale_by_a=True)
+    assert_close(out, ref, mag, "sddmm scaled")
+    if fused and n_rows == n_cols and d <= 256:
+        Xs = (0.3 * X).astype(np.float32)
+        Xsd = dev(Xs)
+        Yf = torch.full((n_rows, d), float("nan"), device="cuda")
+        isp.fusedmm(A, Xsd, Yf)
+        ref, mag = oracle.fusedmm(indptr, indices, values, Xs)
+        assert_close(Yf, ref, mag, "fusedmm")
+        dXf = torch.full((n_rows, d), float("nan"), device="cuda")
+        isp.fusedmm_backward(A, Xsd, Gd, dXf)
+        ref, mag = oracle.fusedmm_backward(indptr, indices, values, Xs, G)
+        assert_close(dXf, ref, mag, "fusedmm backward")
+        dXf2 = torch.empty_like(dXf)
+        isp.fusedmm_backward(A, Xsd, Gd, dXf2)
+        assert torch.equal(dXf, dXf2)
+    A.destroy()
+
+
+@pytest.mark.parametrize("d", [1, 3, 32, 64, 100, 128, 130, 200, 256])
+def test_all_ops_small_graph_many_items(small_partition, d):
+    w = graphgen.make_config(1, shrink=128)  # ~1.3k nodes, power law, hubs far above the small threshold
+    _run_all_ops(w.indptr, w.indices, w.values, w.n, w.n, d, seed=d)
+
+
+@pytest.mark.parametrize("d", [300, 513])
+def test_wide_features_tile_over_columns(small_partition, d):
+    w = graphgen.make_config(1, shrink=256)
+    _run_all_ops(w.indptr, w.indices, w.values, w.n, w.n, d, seed=d, fused=False)
+
+
+def test_rectangular_unsorted_duplicates_no_values(small_partition):
+    indptr, indices, values = graphgen.random_csr(700, 333, 9000, 5, sorted_cols=False, allow_dup=True)
+    _run_all_ops(indptr, indices, values, 700, 333, 48, seed=1)
+    _run_all_ops(indptr, indices, None, 700, 333, 128, seed=2)
+
+
+def test_directed_config0_default_partition():
+    w = graphgen.make_config(0)
+    _run_all_ops(w.indptr, w.indices, w.values, w.n, w.n, w.d, seed=0)
+
+
+def test_empty_rows_and_unit_values(small_partition):
+    w = graphgen.make_config(4, shrink=256)  # directed R-MAT: about half the rows are empty
+    assert (np.diff(w.indptr) == 0).sum() > w.n // 4
+    _run_all_ops(w.indptr, w.indices, None, w.n, w.n, 64, seed=3)
+
+
+def test_degenerate_shapes():
+    # nnz = 0: outputs are zero-filled
+    indptr = np.zeros(6, dtype=np.int64)
+    A = build(indptr, np.zeros(0, np.int32), None, n_cols=5)
+    Y = torch.full((5, 7), float("nan"), device="cuda")
+    isp.spmm(A, torch.ones(5, 7, device="cuda"), Y)
+    assert torch.equal(Y, torch.zeros_like(Y))
+    At, _ = isp.csr_transpose_cached(A)
+    ti, tj, tv, perm = At.export()
+    assert torch.equal(ti, torch.zeros(6, dtype=torch.int64, device="cuda")) and tj.numel() == 0
+    isp.spmm(At, torch.ones(5, 7, device="cuda"), Y)
+    assert torch.equal(Y, torch.zeros_like(Y))
+    A.destroy()
+    # n_rows = 0
+    A = build(np.zeros(1, dtype=np.int64), np.zeros(0, np.int32), None, n_cols=0)
+    assert A.info()["n_row_blocks"] == 0
+    A.destroy()
+    # 1 x 1 with a self loop
+    A = build(np.array([0, 1], dtype=np.int64), np.array([0], dtype=np.int32), np.array([2.0], dtype=np.float32))
+    Y = torch.empty(1, 1, device="cuda")
+    isp.spmm(A, torch.full((1, 1), 3.0, device="cuda"), Y)
+    assert Y.item() == 6.0
+    A.destroy()
+
+
+def test_leading_dimension_larger_than_d(small_partition):
+    w = graphgen.make_config(1, shrink=256)
+    d, ld = 96, 160
+    rng = np.random.default_rng(0)
+    Xfull = rng.standard_normal((w.n, ld)).astype(np.float32)
+    A = build(w.indptr, w.indices, w.values)
+    Xd = dev(Xfull)[:, :d]
+    Ybuf = torch.full((w.n, ld), 7.0, device="cuda")
+    isp.spmm(A, Xd, Ybuf[:, :d])
+    ref, mag = oracle.spmm(w.indptr, w.indices, w.values, Xfull[:, :d])
+    assert_close(Ybuf[:, :d].contiguous(), ref, mag, "spmm with ld > d")
+    assert torch.all(Ybuf[:, d:] == 7.0), "columns beyond d were written"
+    A.destroy()
+
+
+def test_malformed_csr_is_rejected():
+    w = graphgen.make_config(0)
+    bad_ptr = w.indptr.copy()
+    bad_ptr[10], bad_ptr[11] = bad_ptr[11], bad_ptr[10] - 1
+    with pytest.raises(isp.IspError) as e:
+        build(bad_ptr, w.indices, w.values)
+    assert e.value.status_name == "ISP_EBADCSR"
+    bad_idx = w.indices.copy()
+    bad_idx[123] = w.n
+    with pytest.raises(isp.IspError) as e:
+        build(w.indptr, bad_idx, w.values)
+    assert e.value.status_name == "ISP_EBADCSR"
+    bad_idx[123] = -1
+    with pytest.raises(isp.IspError):
+        build(w.indptr, bad_idx, w.values)
+    A = build(w.indptr, w.indices, w.values)
+    X = torch.ones(w.n, 8, device="cuda")
+    with pytest.raises(isp.IspError) as e:  # backward before the transpose exists
+        isp.fusedmm_backward(A, X, X, torch.empty_like(X))
+    assert e.value.status_name == "ISP_EINVAL"
+    with pytest.raises(isp.IspError) as e:  # FusedMM width limit
+        isp.fusedmm(A, torch.ones(w.n, 260, device="cuda"), torch.empty(w.n, 260, device="cuda"))
+    assert e.value.status_name == "ISP_EUNSUPPORTED"
+    A.destroy()
