@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse GNN hot path on one MI355X.
+
+One "step" = one pass of the hot path over the workload with all inputs resident in HBM:
+the cached-transpose lookup (a cache hit after the first call), SpMM forward Y = A X and SpMM
+backward dX = A^T dY (configs 1-3), plus SDDMM where the configuration lists it, or FusedMM
+forward + backward (config 4).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4]
+
+The default workload is configuration 3, the largest power-law graph (R-MAT, n = 2,449,029,
+~123.6 M stored entries, d = 128), which is the one the bandwidth target is quoted on.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--shrink", type=int, default=1, help="divide the graph size (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain device copies of X (known size) before the timed region, "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import graphgen
+    import paper_2403_14853_amd as isp
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    isp.load_library()  # fails loudly when the HIP library is missing
+    t0 = time.time()
+    w = graphgen.make_config(args.config, shrink=args.shrink)
+    gen_s = time.time() - t0
+    n, d, nnz = w.n, w.d, w.nnz
+    dev = lambda a: torch.from_numpy(a).cuda()
+    indptr, indices, values = dev(w.indptr), dev(w.indices), dev(w.values)
+    X, dY = dev(w.X), dev(w.dY)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+
+    def timed(fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        out = fn()
+        b.record(stream)
+        b.synchronize()
+        return out, a.elapsed_time(b)
+
+    A, build_ms = timed(lambda: isp.csr_build(indptr, indices, values))
+    (At, _), transpose_ms = timed(lambda: isp.csr_transpose_cached(A))
+    info, info_t = A.info(), At.info()
+
+    ops = list(w.ops)
+    if args.config == 1:  # two-layer GCN step: forward and backward SpMM per layer
+        ops = ["spmm", "spmm", "spmm_t", "spmm_t"]
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    dA = torch.empty(nnz, dtype=torch.float32, device="cuda") if "sddmm" in ops else None
+    flops_of = {"spmm": 2.0 * nnz * d, "spmm_t": 2.0 * nnz * d, "sddmm": 2.0 * nnz * d,
+                "fusedmm": 4.0 * nnz * d, "fusedmm_bwd": 10.0 * nnz * d}
+    run_of = {
+        "spmm": lambda: isp.spmm(A, X, Y),
+        "spmm_t": lambda: isp.spmm(isp.csr_transpose_cached(A)[0], dY, dX),  # cache hit every step
+        "sddmm": lambda: isp.sddmm(A, dY, X, dA),
+        "fusedmm": lambda: isp.fusedmm(A, X, Y),
+        "fusedmm_bwd": lambda: isp.fusedmm_backward(A, X, dY, dX),
+    }
+
+    def step(events=None):
+        for i, op in enumerate(ops):
+            if events is not None:
+                events[i][0].record(stream)
+            run_of[op]()
+            if events is not None:
+                events[i][1].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    if args.copy_calibration:
+        for _ in range(3):
+            Y.copy_(X)  # plain copy kernel: reads 4*n*d bytes, writes 4*n*d bytes
+    torch.cuda.synchronize()
+    # per-op HIP events on the launch stream, recorded inside the timed region
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    op_ms = [float(np.mean([evs[k][i][0].elapsed_time(evs[k][i][1]) for k in range(args.steps)]))
+             for i in range(len(ops))]
+    total_flops = sum(flops_of[o] for o in ops)
+    value = total_flops / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the row-streaming SpMM kernel (forward launch).  Algorithmic bytes of one
+    # launch = every operand moved once: CSR (8 B per row offset + 4 B index + 4 B value per
+    # entry) + X read once + Y written once.
+    dom = "fusedmm" if args.config == 4 else "spmm"
+    dom_ms = float(np.mean([op_ms[i] for i, o in enumerate(ops) if o == dom]))
+    val_bytes = 4 if w.values is not None else 0
+    csr_bytes = 8.0 * (n + 1) + (4.0 + val_bytes) * nnz
+    alg_bytes = csr_bytes + 2.0 * 4.0 * n * d
+    gather_bytes = csr_bytes + 4.0 * d * nnz + 4.0 * n * d  # every entry fetches its own X row
+    achieved = alg_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "k_fused<fwd>" if dom == "fusedmm" else "k_spmm",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES.get((args.config, args.shrink)),
+        "algorithmic_bytes": alg_bytes, "launch_ms": round(dom_ms, 4),
+        "gather_model_bytes": gather_bytes,
+        "gather_model_GBps": round(gather_bytes / (dom_ms * 1e-3) / 1e9, 1),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, Y, dom)
+
+    out = {
+        "metric": "SpMM fwd+bwd GFLOP/s (2*nnz*d/t)" if args.config != 4 else "FusedMM fwd+bwd GFLOP/s",
+        "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n": n, "nnz": nnz, "d": d, "ops": ops,
+                   "max_degree": info["max_degree"], "hub_rows": info["n_hub_rows"],
+                   "work_items": info["n_row_blocks"] + info["n_segments"]},
+        "op_ms": {("%d:%s" % (i, o)): round(op_ms[i], 4) for i, o in enumerate(ops)},
+        "op_gflops": {("%d:%s" % (i, o)): round(flops_of[o] / (op_ms[i] * 1e-3) / 1e9, 1) for i, o in enumerate(ops)},
+        "setup_ms": {"generate_host": round(gen_s * 1e3, 1), "csr_build": round(build_ms, 3),
+                     "transpose_first_call": round(transpose_ms, 3)},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); keyed by (config, shrink).  None = not measured for that workload.
+TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(w, Y_gpu, dom):
+    """Time the fp64 CPU oracle on a bounded row sample of the same workload (and use its result
+    as one more parity check of the GPU output on those rows)."""
+    import numpy as np
+    import oracle
+    target_nnz = 200_000_000  # whole forward of configs 0-3 (seconds of oracle work on 16 cores)
+    rows = int(np.searchsorted(w.indptr, min(target_nnz, w.nnz), side="left"))
+    rows = max(1, min(rows, w.n))
+    sp = w.indptr[: rows + 1]
+    nnz_s = int(sp[-1])
+    si, sv = w.indices[:nnz_s], (None if w.values is None else w.values[:nnz_s])
+    threads = oracle.max_threads()
+    t0 = time.perf_counter()
+    if dom == "spmm":
+        ref, mag = oracle.spmm(sp, si, sv, w.X, want_mag=True)
+        flops, kind = 2.0 * nnz_s * w.d, "spmm forward"
+    else:
+        ref, mag = oracle.fusedmm(sp, si, sv, w.X, want_mag=True)
+        flops, kind = 4.0 * nnz_s * w.d, "fusedmm forward"
+    dt = time.perf_counter() - t0
+    got = Y_gpu[:rows].cpu().numpy().astype(np.float64)
+    ratio = float(np.max(np.abs(got - ref) / (1e-5 * mag + 1e-6)))
+    return {"value": round(flops / dt / 1e9, 2), "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "%s on rows [0, %d) of the same graph (%d stored entries), fp64 accumulate, "
+                      "OpenMP over rows, %.1f s" % (kind, rows, nnz_s, dt),
+            "gpu_vs_oracle_max_err_over_tol": ratio}
+
+
+if __name__ == "__main__":
+    main()

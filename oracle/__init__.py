@@ -142,9 +142,9 @@ def fusedmm(indptr, indices, values, X, want_mag=True):
     indptr, indices, values = _csr(indptr, indices, values)
     X = _dense(X)
     n, d = indptr.shape[0] - 1, X.shape[1]
-    assert X.shape[0] == n
+    assert X.shape[0] >= n  # a row-prefix of a square matrix is accepted (rows i < n, columns < X rows)
     if indices.size:
-        assert indices.max() < n and indices.min() >= 0
+        assert indices.max() < X.shape[0] and indices.min() >= 0
     Y = np.empty((n, d), dtype=np.float64)
     mag = np.empty((n, d), dtype=np.float64) if want_mag else None
     _load().isp_oracle_fusedmm(n, _ptr(indptr), _ptr(indices), _ptr(values), _ptr(X), d, d, _ptr(Y), _ptr(mag))

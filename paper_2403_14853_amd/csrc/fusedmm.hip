@@ -5,7 +5,8 @@
 // The per-edge scores exist only in registers: each gathered row x_j is used for the dot product
 // and for the accumulation in the same pass, and the backward recomputes the scores instead of
 // reading them back.  The column sum of the backward runs over the rows of the cached transpose.
-#include "row_stream.h"
+#include <stdlib.h>
+#include "grouped_ops.h"
 
 namespace {
 using namespace isp_dev;
@@ -138,6 +139,101 @@ isp_status run_pass(const isp_csr* A, const typename P::args& pa, int d, float* 
   return ISP_OK;
 }
 
+// ---- grouped fast path (d % 4 == 0, 16-byte aligned operands) -----------------------------------
+struct g_args1 { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
+struct g_args12 { const float* src[1]; int64_t lds_[1]; const float* rowop[2]; int64_t ldr[2]; float* out_entry; };
+struct g_args21 { const float* src[2]; int64_t lds_[2]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
+
+struct g_fwd {  // gathered x_j, row operand x_i
+  static constexpr int NSRC = 1, NROW = 1;
+  static constexpr bool PER_ENTRY = false, ACCUMULATE = false;
+  using args = g_args1;
+  template <int LPG>
+  __device__ static inline void edge(float a, const float (&x)[1][4], const float (&r)[1][4], float (&acc)[4]) {
+    const float z = group_allreduce<LPG>(dot4(r[0], x[0]));
+    const float w = a * sigmoidf_fast(z);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[0][v], acc[v]);
+  }
+  template <int LPG>
+  __device__ static inline float entry(float, const float (&)[1][4], const float (&)[1][4]) { return 0.f; }
+};
+
+struct g_bwd_row {  // gathered x_j, row operands x_i and g_i:  dX_i += dz x_j
+  static constexpr int NSRC = 1, NROW = 2;
+  static constexpr bool PER_ENTRY = false, ACCUMULATE = false;
+  using args = g_args12;
+  template <int LPG>
+  __device__ static inline void edge(float a, const float (&x)[1][4], const float (&r)[2][4], float (&acc)[4]) {
+    const float z = group_allreduce<LPG>(dot4(r[0], x[0]));
+    const float gd = group_allreduce<LPG>(dot4(r[1], x[0]));
+    const float sg = sigmoidf_fast(z);
+    const float dz = a * gd * sg * (1.f - sg);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = fmaf(dz, x[0][v], acc[v]);
+  }
+  template <int LPG>
+  __device__ static inline float entry(float, const float (&)[1][4], const float (&)[2][4]) { return 0.f; }
+};
+
+struct g_bwd_col {  // over A^T: gathered x_i and g_i, row operand x_j:  dX_j += a s g_i + dz x_i
+  static constexpr int NSRC = 2, NROW = 1;
+  static constexpr bool PER_ENTRY = false, ACCUMULATE = true;
+  using args = g_args21;
+  template <int LPG>
+  __device__ static inline void edge(float a, const float (&x)[2][4], const float (&r)[1][4], float (&acc)[4]) {
+    const float z = group_allreduce<LPG>(dot4(r[0], x[0]));
+    const float gd = group_allreduce<LPG>(dot4(r[0], x[1]));
+    const float sg = sigmoidf_fast(z);
+    const float w = a * sg;
+    const float dz = a * gd * sg * (1.f - sg);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
+  }
+  template <int LPG>
+  __device__ static inline float entry(float, const float (&)[2][4], const float (&)[1][4]) { return 0.f; }
+};
+
+template <class P, int LPG, bool HAS_VAL>
+__global__ void __launch_bounds__(ISP_WG) k_fused_grouped(isp_view A, const int64_t* __restrict__ indptr,
+                                                          const int32_t* __restrict__ indices,
+                                                          const float* __restrict__ values, typename P::args pa, int d,
+                                                          float* __restrict__ Y, int64_t ldy) {
+  __shared__ gs_lds lds;
+  fused_grouped_item<P, LPG, HAS_VAL>(A, indptr, indices, values, pa, d, Y, ldy, lds);
+}
+
+template <class P, int LPG>
+isp_status run_grouped(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s) {
+  const isp_view& v = A->v;
+  const int n_items = v.n_blocks + v.n_seg;
+  if (n_items > 0) {
+    const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
+    if (v.values) k_fused_grouped<P, LPG, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
+    else k_fused_grouped<P, LPG, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
+    ISP_LAUNCH_CHECK();
+  }
+  if (v.n_hub > 0) {
+    const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
+    k_fused_fixup<4, 1, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, Y, ldy);
+    ISP_LAUNCH_CHECK();
+  }
+  return ISP_OK;
+}
+
+template <class P>
+isp_status run_grouped_d(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s) {
+  if (d <= 32) return run_grouped<P, 8>(A, pa, d, Y, ldy, s);
+  if (d <= 64) return run_grouped<P, 16>(A, pa, d, Y, ldy, s);
+  if (d <= 128) return run_grouped<P, 32>(A, pa, d, Y, ldy, s);
+  return run_grouped<P, 64>(A, pa, d, Y, ldy, s);
+}
+
+bool grouped_partition_ok(const isp_csr* A) {
+  return A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + A->v.hub_t <= GS_MAX_ENT &&
+         A->v.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
+}
+
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // 0: float4 lanes, 1: float2 lanes, 2..4: scalar lanes with 1, 2, 4 column groups
@@ -164,6 +260,10 @@ isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int
                               hipStream_t s) {
   const bool ok4 = ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16);
   const bool ok2 = ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8);
+  if (ok4 && d % 4 == 0 && grouped_partition_ok(A)) {
+    g_fwd::args pa{{X}, {ldx}, {X}, {ldx}, nullptr};
+    return run_grouped_d<g_fwd>(A, pa, d, Y, ldy, s);
+  }
   const int shape = pick_shape(d, ok4, ok2);
   const bool hv = A->v.values != nullptr;
   isp_status st = ISP_OK;
@@ -184,6 +284,13 @@ isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx,
                                   int32_t d, float* dX, int64_t lddx, hipStream_t s) {
   const bool ok4 = ldx % 4 == 0 && ldg % 4 == 0 && lddx % 4 == 0 && aligned(X, 16) && aligned(G, 16) && aligned(dX, 16);
   const bool ok2 = ldx % 2 == 0 && ldg % 2 == 0 && lddx % 2 == 0 && aligned(X, 8) && aligned(G, 8) && aligned(dX, 8);
+  if (ok4 && d % 4 == 0 && grouped_partition_ok(A) && grouped_partition_ok(A->At)) {
+    g_bwd_row::args p1{{X}, {ldx}, {X, G}, {ldx, ldg}, nullptr};
+    isp_status st1 = run_grouped_d<g_bwd_row>(A, p1, d, dX, lddx, s);
+    if (st1 != ISP_OK) return st1;
+    g_bwd_col::args p2{{X, G}, {ldx, ldg}, {X}, {ldx}, nullptr};
+    return run_grouped_d<g_bwd_col>(A->At, p2, d, dX, lddx, s);
+  }
   const int shape = pick_shape(d, ok4, ok2);
   const bool hv = A->v.values != nullptr;
   isp_status st = ISP_OK;

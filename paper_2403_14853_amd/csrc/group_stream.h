@@ -1,0 +1,149 @@
+// Grouped row-streaming skeleton (gfx950, wave64): the fast path when the feature width and the
+// operands' alignment allow 16-byte lanes.
+//
+// A wavefront owns one work item (a block of whole short rows or one hub-row segment) whose
+// nonzeros are contiguous in the CSR arrays.  The 64 lanes form G = 64 / LPG groups of LPG
+// lanes; a group gathers one dense row slice of 4 * LPG floats with one float4 per lane, so a
+// single load instruction serves G nonzeros.  The item's (column, value) pairs are staged once
+// in LDS; a per-item step table, also in LDS, says for every step which G consecutive entries
+// it covers and whether it ends a row (a step never crosses a row boundary, every row - even
+// an empty one - owns at least one step).  The main loop is therefore flat: U steps are issued
+// back to back (LDS read -> address -> gather) before the first is consumed, independent of
+// where rows begin and end, which keeps short rows from serialising on memory latency.  When
+// a step ends a row the G group accumulators are summed with lane shuffles and group 0 writes
+// the row slice.  Feature columns beyond one slice are covered by further workgroups
+// (blockIdx % n_slices), dealt round-robin to the XCDs.
+#pragma once
+#include "row_stream.h"
+
+namespace isp_dev {
+
+// Partition limits this skeleton is sized for (csr_build clamps its parameters to them).
+constexpr int GS_MAX_ENT = 768;    // nonzeros per item:  block_cost - 1 + hub_t  or  seg_len
+constexpr int GS_MAX_ROWS = 256;   // rows per item: block_cost
+constexpr int GS_MAX_STEPS = GS_MAX_ENT + GS_MAX_ROWS;  // G = 1 worst case
+
+constexpr int GS_U = 8;            // steps issued back to back; step tables are padded to a multiple
+
+typedef unsigned short gs_u16;
+struct __attribute__((aligned(16))) gs_wave_lds {
+  int2 ent[GS_MAX_ENT + 8];               // (column, value bits) of the item's nonzeros
+  gs_u16 step[GS_MAX_STEPS + GS_U];       // step descriptors, padded with null steps
+  gs_u16 rp[GS_MAX_ROWS + 8];             // row start offsets relative to the item
+  gs_u16 ss[GS_MAX_ROWS + 8];             // first step of each row
+};
+struct gs_lds { gs_wave_lds w[ISP_WAVES_PER_WG]; };
+
+// step descriptor (16 bits): bits 0..9 entry offset, 10..13 live entries (0..8), bit 14 ends a row
+constexpr unsigned GS_LAST = 0x4000u;
+__device__ inline gs_u16 gs_pack(int off, int cnt, bool last) {
+  return (gs_u16)((unsigned)off | ((unsigned)cnt << 10) | (last ? GS_LAST : 0u));
+}
+__device__ inline int gs_off(unsigned dsc) { return (int)(dsc & 0x3ffu); }
+__device__ inline int gs_cnt(unsigned dsc) { return (int)((dsc >> 10) & 15u); }
+
+// Orders this wave's earlier LDS writes before its later LDS reads (other lanes' data).  The LDS
+// unit executes one wave's operations in order, so only the compiler has to be held back.
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+__device__ inline int wave_exclusive_scan_i(int v, int lane, int* total) {
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < ISP_WAVE; o <<= 1) {
+    const int t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  *total = __shfl(inc, ISP_WAVE - 1);
+  return inc - v;
+}
+
+// Stage the item's entries and build its step table.  Returns the number of steps, rounded up to
+// a multiple of GS_U with null steps (no live entry, not a row end).
+template <int G, bool HAS_VAL>
+__device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict__ indptr,
+                                 const int32_t* __restrict__ indices, const float* __restrict__ values,
+                                 gs_wave_lds& L, int lane) {
+  int2* __restrict__ ent = L.ent;
+  gs_u16* __restrict__ step = L.step;
+  gs_u16* __restrict__ rp = L.rp;
+  gs_u16* __restrict__ ss = L.ss;
+  const int n_ent = (int)(it.p_end - it.p);
+  for (int i = lane; i < n_ent; i += ISP_WAVE) {
+    int2 e;
+    e.x = __builtin_nontemporal_load(indices + it.p + i);
+    e.y = HAS_VAL ? __float_as_int(__builtin_nontemporal_load(values + it.p + i)) : 0x3f800000;
+    ent[i] = e;
+  }
+  const int n_rows = it.row_last - it.row;
+  if (it.is_seg) {
+    if (lane == 0) { rp[0] = 0; rp[1] = (gs_u16)n_ent; }
+  } else {
+    for (int r = lane; r <= n_rows; r += ISP_WAVE) rp[r] = (gs_u16)(indptr[it.row + r] - it.p);
+  }
+  wave_lds_sync();
+  int carry = 0;
+  for (int c = 0; c < n_rows; c += ISP_WAVE) {
+    const int r = c + lane;
+    int ns = 0;
+    if (r < n_rows) {
+      const int len = (int)rp[r + 1] - (int)rp[r];
+      ns = len > 0 ? (len + G - 1) / G : 1;
+    }
+    int tot;
+    const int ex = wave_exclusive_scan_i(ns, lane, &tot);
+    if (r < n_rows) ss[r] = (gs_u16)(carry + ex);
+    carry += tot;
+  }
+  const int n_steps = carry;
+  if (lane == 0) ss[n_rows] = (gs_u16)n_steps;
+  wave_lds_sync();
+  const int n_padded = (n_steps + GS_U - 1) / GS_U * GS_U;
+  for (int s = lane; s < n_padded; s += ISP_WAVE) {
+    gs_u16 dsc = 0;  // null step
+    if (s < n_steps) {
+      int lo = 0, hi = n_rows;  // last row r with ss[r] <= s
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((int)ss[mid] <= s) lo = mid; else hi = mid;
+      }
+      const int k = s - (int)ss[lo];
+      const int len = (int)rp[lo + 1] - (int)rp[lo];
+      const int left = len - k * G;
+      dsc = gs_pack((int)rp[lo] + k * G, left >= G ? G : (left > 0 ? left : 0), s + 1 == (int)ss[lo + 1]);
+    }
+    step[s] = dsc;
+  }
+  wave_lds_sync();
+  return n_padded;
+}
+
+// Sum over the LPG consecutive lanes of a group, result in every lane of the group.  Lane
+// exchanges inside 16 lanes are DPP modifiers (no LDS traffic); xor 16 is a ds_swizzle, xor 32 a
+// bpermute.
+template <int LPG>
+__device__ inline float group_allreduce(float v) {
+  // quad_perm [1,0,3,2] and [2,3,0,1]: xor 1, xor 2
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));
+  // row_half_mirror (reverse within 8 lanes): pairs the two quads of an 8-lane half
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));
+  if constexpr (LPG >= 16)  // row_mirror (reverse within 16 lanes)
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));
+  if constexpr (LPG >= 32)  // swap halves of 32 lanes: swizzle bit mode, xor mask 0x10
+    v += __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));
+  if constexpr (LPG >= 64) v += __shfl_xor(v, 32);
+  return v;
+}
+
+// Sum a value over the G groups (lanes with equal lane % LPG); result valid in group 0.
+template <int LPG>
+__device__ inline float group_sum(float v) {
+#pragma unroll
+  for (int o = LPG; o < ISP_WAVE; o <<= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+}  // namespace isp_dev

@@ -1,0 +1,134 @@
+// Grouped kernels for the operations that need a whole dot product per nonzero (SDDMM and the
+// FusedMM passes).  Same work items, LDS staging and step tables as the grouped SpMM; here a
+// group of LPG lanes spans the full feature width (4 * LPG >= d), so G = 64 / LPG dot products
+// are reduced side by side with the same DPP instructions.  The row operand (U's row for SDDMM,
+// x_i / g_i for FusedMM) is re-read with every step instead of being kept across steps: it is an
+// L1 hit after a row's first step and keeps the main loop free of row-change stalls.
+#pragma once
+#include "group_stream.h"
+
+namespace isp_dev {
+
+// Policy P:  NSRC gathered operands (rows picked by column index), NROW row operands (rows picked
+// by the step's matrix row); args { src[NSRC], lds_[NSRC], rowop[NROW], ldr[NROW], out_entry };
+// either edge<LPG>(a, src, rowop, acc) accumulating into the row's result, or (PER_ENTRY)
+// entry<LPG>(a, src, rowop) returning the value stored for the entry.
+template <class P, int LPG, bool HAS_VAL>
+__device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __restrict__ indptr,
+                                          const int32_t* __restrict__ indices, const float* __restrict__ values,
+                                          const typename P::args& pa, int d, float* __restrict__ Y, int64_t ldy,
+                                          gs_lds& lds) {
+  constexpr int G = ISP_WAVE / LPG;
+  constexpr int NSRC = P::NSRC, NROW = P::NROW;
+  constexpr int U = 4;  // steps in flight per buffer; two buffers
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int w = threadIdx.x >> 6;
+  const int item = __builtin_amdgcn_readfirstlane((int)blockIdx.x * ISP_WAVES_PER_WG + w);
+  if (item >= A.n_blocks + A.n_seg) return;
+  const item_range it = locate_item(A, indptr, item);
+  if (it.skip) return;
+  gs_wave_lds& L = lds.w[w];
+  const int n_steps = gs_prepare<G, HAS_VAL>(it, indptr, indices, values, L, lane);
+
+  const int g = lane / LPG, q = lane % LPG;
+  const int col = q * 4;
+  const bool lane_on = col < d;
+  const int coff = lane_on ? col : 0;
+  float* __restrict__ out = it.is_seg ? A.partials + col : Y + col;
+  const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
+  int row = it.row;          // output row (segment index for hub segments), advanced by consume
+  int irow = it.src_row;     // matrix row of the next step to issue
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+
+  auto finish_row = [&]() {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = group_sum<LPG>(acc[v]);
+    if (g == 0 && lane_on) {
+      float* o = out + (int64_t)row * ldo;
+      if (P::ACCUMULATE && !it.is_seg) {
+        float old[4];
+        load_vec<4>(o, old);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[v] += old[v];
+      }
+      store_vec<4>(o, acc);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = 0.f;
+    ++row;
+  };
+  auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][NSRC][4], float (&r)[U][NROW][4], float (&a)[U]) {
+    int2 e[U];
+    int srow[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      dsc[u] = L.step[s0 + u];
+      e[u] = L.ent[gs_off(dsc[u]) + g];
+      srow[u] = irow;
+      irow += (int)((dsc[u] >> 14) & 1u);  // a row end moves the following steps to the next row
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool act = g < gs_cnt(dsc[u]) && lane_on;
+      a[u] = act ? __int_as_float(e[u].y) : 0.f;
+      const int64_t cj = act ? e[u].x : 0;
+#pragma unroll
+      for (int k = 0; k < NSRC; ++k) load_vec<4>(pa.src[k] + cj * pa.lds_[k] + coff, x[u][k]);
+      const int64_t ri = srow[u] < A.n_rows ? srow[u] : 0;  // null steps after the last row
+#pragma unroll
+      for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + ri * pa.ldr[k] + coff, r[u][k]);
+    }
+  };
+  auto consume = [&](const unsigned (&dsc)[U], float (&x)[U][NSRC][4], float (&r)[U][NROW][4], const float (&a)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool act = g < gs_cnt(dsc[u]) && lane_on;
+#pragma unroll
+      for (int k = 0; k < NSRC; ++k)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[u][k][v] = act ? x[u][k][v] : 0.f;
+#pragma unroll
+      for (int k = 0; k < NROW; ++k)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) r[u][k][v] = lane_on ? r[u][k][v] : 0.f;
+      if constexpr (P::PER_ENTRY) {
+        // one output per stored entry: lane 0 of every live group writes its entry's value
+        const float val = P::template entry<LPG>(a[u], x[u], r[u]);
+        if (g < gs_cnt(dsc[u]) && q == 0) {
+          float* o = pa.out_entry + it.p + gs_off(dsc[u]) + g;
+          *o = val;
+        }
+      } else {
+        P::template edge<LPG>(a[u], x[u], r[u], acc);
+        if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
+      }
+    }
+  };
+
+  const int n_groups = n_steps / U;
+  if (n_groups == 0) return;
+  unsigned dA[U], dB[U];
+  float xA[U][NSRC][4], xB[U][NSRC][4], rA[U][NROW][4], rB[U][NROW][4], aA[U], aB[U];
+  issue(0, dA, xA, rA, aA);
+  int gi = 0;
+  while (gi + 2 < n_groups) {
+    issue((gi + 1) * U, dB, xB, rB, aB);
+    consume(dA, xA, rA, aA);
+    issue((gi + 2) * U, dA, xA, rA, aA);
+    consume(dB, xB, rB, aB);
+    gi += 2;
+  }
+  if (gi + 1 < n_groups) {
+    issue((gi + 1) * U, dB, xB, rB, aB);
+    consume(dA, xA, rA, aA);
+    consume(dB, xB, rB, aB);
+  } else {
+    consume(dA, xA, rA, aA);
+  }
+}
+
+__device__ inline float dot4(const float (&a)[4], const float (&b)[4]) {
+  return fmaf(a[3], b[3], fmaf(a[2], b[2], fmaf(a[1], b[1], a[0] * b[0])));
+}
+
+}  // namespace isp_dev

@@ -5,7 +5,8 @@
 // Same work items as SpMM.  The wave keeps U's row in registers, gathers V's rows with the 64
 // lanes spread over the feature dimension, and reduces each product across the wave.  Results
 // of up to 64 consecutive entries are collected one per lane and stored coalesced.
-#include "row_stream.h"
+#include <stdlib.h>
+#include "grouped_ops.h"
 
 namespace {
 using namespace isp_dev;
@@ -89,6 +90,48 @@ __global__ void __launch_bounds__(ISP_WG) k_sddmm(isp_view A, const int64_t* __r
   }
 }
 
+// ---- grouped fast path (d <= 256, 16-byte aligned operands) -------------------------------------
+template <bool SCALE>
+struct sddmm_policy {
+  static constexpr int NSRC = 1, NROW = 1;
+  static constexpr bool PER_ENTRY = true, ACCUMULATE = false;
+  struct args { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
+  template <int LPG>
+  __device__ static inline float entry(float a, const float (&x)[1][4], const float (&r)[1][4]) {
+    const float dot = group_allreduce<LPG>(dot4(r[0], x[0]));
+    return SCALE ? a * dot : dot;
+  }
+  template <int LPG>
+  __device__ static inline void edge(float, const float (&)[1][4], const float (&)[1][4], float (&)[4]) {}
+};
+
+template <int LPG, bool SCALE>
+__global__ void __launch_bounds__(ISP_WG) k_sddmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
+                                                          const int32_t* __restrict__ indices,
+                                                          const float* __restrict__ values,
+                                                          typename sddmm_policy<SCALE>::args pa, int d) {
+  __shared__ gs_lds lds;
+  fused_grouped_item<sddmm_policy<SCALE>, LPG, SCALE>(A, indptr, indices, values, pa, d, nullptr, 0, lds);
+}
+
+template <int LPG>
+isp_status launch_grouped(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv, int d,
+                          bool scale, float* out, hipStream_t s) {
+  const isp_view& v = A->v;
+  const int n_items = v.n_blocks + v.n_seg;
+  if (n_items == 0 || v.nnz == 0) return ISP_OK;
+  const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
+  if (scale && v.values) {
+    sddmm_policy<true>::args pa{{V}, {ldv}, {U}, {ldu}, out};
+    k_sddmm_grouped<LPG, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d);
+  } else {
+    sddmm_policy<false>::args pa{{V}, {ldv}, {U}, {ldu}, out};
+    k_sddmm_grouped<LPG, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d);
+  }
+  ISP_LAUNCH_CHECK();
+  return ISP_OK;
+}
+
 template <int VEC>
 isp_status launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv, int d, int k0,
                   bool scale, bool add, float* out, hipStream_t s) {
@@ -112,6 +155,17 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv, int32_t d,
                             bool scale, float* out, hipStream_t s) {
+  const isp_view& av = A->v;
+  const bool grouped_ok = d <= ISP_PARTIAL_TILE && d % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 && aligned(U, 16) &&
+                          aligned(V, 16) && A->info.block_cost <= GS_MAX_ROWS &&
+                          A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT &&
+                          !getenv("ISP_NO_GROUPED");
+  if (grouped_ok) {
+    if (d <= 32) return launch_grouped<8>(A, U, ldu, V, ldv, d, scale, out, s);
+    if (d <= 64) return launch_grouped<16>(A, U, ldu, V, ldv, d, scale, out, s);
+    if (d <= 128) return launch_grouped<32>(A, U, ldu, V, ldv, d, scale, out, s);
+    return launch_grouped<64>(A, U, ldu, V, ldv, d, scale, out, s);
+  }
   int vec = 1;
   if (d > 2 * ISP_WAVE && d % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 && aligned(U, 16) && aligned(V, 16)) vec = 4;
   else if (d > ISP_WAVE && d % 2 == 0 && ldu % 2 == 0 && ldv % 2 == 0 && aligned(U, 8) && aligned(V, 8)) vec = 2;

@@ -2,7 +2,8 @@
 // 3.4, 3.5).  The backward dX = A^T dY is this same code run on the cached transpose's handle
 // (Section 3.3).  Gather-bound: per nonzero one 4*d-byte row of X is fetched and d FMAs are done,
 // so the kernels are built around coalesced row gathers, not around matrix cores.
-#include "row_stream.h"
+#include <stdlib.h>
+#include "group_stream.h"
 
 namespace {
 using namespace isp_dev;
@@ -28,12 +29,13 @@ template <int VEC, int T, bool HAS_VAL>
 __global__ void __launch_bounds__(ISP_WG) k_spmm(isp_view A, const int64_t* __restrict__ indptr,
                                                  const int32_t* __restrict__ indices,
                                                  const float* __restrict__ values, const float* __restrict__ X,
-                                                 int64_t ldx, int d, int k0, float* __restrict__ Y, int64_t ldy) {
+                                                 int64_t ldx, int d, int k0, float* __restrict__ Y, int64_t ldy,
+                                                 int n_slices) {
   using P = spmm_policy<VEC, T, HAS_VAL>;
   typename P::args pa;
   pa.src[0] = X;
   pa.ld[0] = ldx;
-  stream_item<P>(A, indptr, indices, values, pa, d, k0, Y, ldy);
+  stream_item<P>(A, indptr, indices, values, pa, d, k0, Y, ldy, n_slices);
 }
 
 template <int VEC, int T>
@@ -41,22 +43,134 @@ __global__ void __launch_bounds__(ISP_WG) k_spmm_fixup(isp_view A, int d, int k0
   hub_fixup<VEC, T, false>(A, d, k0, Y, ldy);
 }
 
-template <int VEC, int T>
+template <int VEC, int T, int FV = VEC, int FT = T>
 isp_status launch_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int k0, float* Y, int64_t ldy,
-                       hipStream_t s) {
+                       hipStream_t s, int n_slices = 1) {
   const isp_view& v = A->v;
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
-    const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
+    const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * n_slices;
     if (v.values)
-      k_spmm<VEC, T, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy);
+      k_spmm<VEC, T, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy, n_slices);
     else
-      k_spmm<VEC, T, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy);
+      k_spmm<VEC, T, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy, n_slices);
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
     const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    k_spmm_fixup<VEC, T><<<grid, ISP_WG, 0, s>>>(v, d, k0, Y, ldy);
+    k_spmm_fixup<FV, FT><<<grid, ISP_WG, 0, s>>>(v, d, k0, Y, ldy);
+    ISP_LAUNCH_CHECK();
+  }
+  return ISP_OK;
+}
+
+
+// ---- grouped fast path -------------------------------------------------------------------------
+// LPG lanes x float4 cover one slice of 4 * LPG feature columns; G = 64 / LPG nonzeros per gather
+// instruction.  Slice s of tile k_base covers columns [k_base + s * 4 * LPG, +4 * LPG).
+template <int LPG, bool HAS_VAL>
+__global__ void __launch_bounds__(ISP_WG) k_spmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
+                                                         const int32_t* __restrict__ indices,
+                                                         const float* __restrict__ values,
+                                                         const float* __restrict__ X, int64_t ldx, int d, int k_base,
+                                                         int n_slices, float* __restrict__ Y, int64_t ldy) {
+  constexpr int G = ISP_WAVE / LPG;
+  constexpr int U = GS_U;
+  __shared__ gs_lds lds;
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int w = threadIdx.x >> 6;
+  const int slice = __builtin_amdgcn_readfirstlane((int)(blockIdx.x % n_slices));
+  const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / n_slices) * ISP_WAVES_PER_WG + w);
+  if (item >= A.n_blocks + A.n_seg) return;
+  const item_range it = locate_item(A, indptr, item);
+  if (it.skip) return;
+  gs_wave_lds& L = lds.w[w];
+  const int n_steps = gs_prepare<G, HAS_VAL>(it, indptr, indices, values, L, lane);  // multiple of U
+
+  const int g = lane / LPG, q = lane % LPG;
+  const int col = k_base + (slice * LPG + q) * 4;
+  const bool lane_on = col < d;
+  // lanes without a live entry (row tails, null steps, columns past d) read row 0 of X and have
+  // their data replaced by zeros, so every step issues exactly one gather per lane
+  const float* __restrict__ xcol = lane_on ? X + col : X;
+  float* __restrict__ out = it.is_seg ? A.partials + (col - k_base) : Y + col;
+  const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
+  int row = it.row;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+
+  auto finish_row = [&]() {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = group_sum<LPG>(acc[v]);
+    if (g == 0 && lane_on) store_vec<4>(out + (int64_t)row * ldo, acc);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = 0.f;
+    ++row;
+  };
+  // descriptors of U consecutive steps = one 16-byte LDS read
+  auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][4], float (&a)[U]) {
+    const uint4 pk = *reinterpret_cast<const uint4*>(L.step + s0);
+    const unsigned raw[4] = {pk.x, pk.y, pk.z, pk.w};
+    int2 e[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      dsc[u] = (raw[u >> 1] >> ((u & 1) * 16)) & 0xffffu;
+      e[u] = L.ent[gs_off(dsc[u]) + g];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool act = g < gs_cnt(dsc[u]) && lane_on;
+      a[u] = act ? __int_as_float(e[u].y) : 0.f;
+      load_vec<4>(xcol + (int64_t)(act ? e[u].x : 0) * ldx, x[u]);
+    }
+  };
+  auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][4], const float (&a)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool act = g < gs_cnt(dsc[u]) && lane_on;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[v] = fmaf(a[u], act ? x[u][v] : 0.f, acc[v]);
+      if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
+    }
+  };
+
+  const int n_groups = n_steps / U;
+  if (n_groups == 0) return;
+  unsigned dA[U], dB[U];
+  float xA[U][4], xB[U][4], aA[U], aB[U];
+  issue(0, dA, xA, aA);
+  int gi = 0;
+  while (gi + 2 < n_groups) {  // steady state: the next group's gathers are in flight while one is consumed
+    issue((gi + 1) * U, dB, xB, aB);
+    consume(dA, xA, aA);
+    issue((gi + 2) * U, dA, xA, aA);
+    consume(dB, xB, aB);
+    gi += 2;
+  }
+  if (gi + 1 < n_groups) {
+    issue((gi + 1) * U, dB, xB, aB);
+    consume(dA, xA, aA);
+    consume(dB, xB, aB);
+  } else {
+    consume(dA, xA, aA);
+  }
+}
+
+template <int LPG>
+isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, int k_base, int n_slices, float* Y,
+                          int64_t ldy, hipStream_t s) {
+  const isp_view& v = A->v;
+  const int n_items = v.n_blocks + v.n_seg;
+  if (n_items > 0) {
+    const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * (unsigned)n_slices;
+    if (v.values)
+      k_spmm_grouped<LPG, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy);
+    else
+      k_spmm_grouped<LPG, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy);
+    ISP_LAUNCH_CHECK();
+  }
+  if (v.n_hub > 0) {
+    const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
+    k_spmm_fixup<4, 1><<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   return ISP_OK;
@@ -72,6 +186,41 @@ isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_
   int vec = 1;
   if (d > 2 * ISP_WAVE && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16)) vec = 4;
   else if (d > ISP_WAVE && d % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8)) vec = 2;
+  const isp_view& av = A->v;
+  const bool grouped_ok = d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16) &&
+                          A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + av.hub_t <= GS_MAX_ENT &&
+                          av.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
+  if (grouped_ok) {
+    // lanes per group: 8 / 16 / 32 / 64 <-> slices of 32 / 64 / 128 / 256 columns
+    int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : (d <= 128 ? 32 : 64));
+    if (const char* e = getenv("ISP_SPMM_LPG")) lpg = atoi(e);
+    isp_status st = ISP_OK;
+    for (int k_base = 0; k_base < d && st == ISP_OK; k_base += ISP_PARTIAL_TILE) {
+      const int w = (d - k_base < ISP_PARTIAL_TILE) ? d - k_base : ISP_PARTIAL_TILE;
+      const int ns = (w + 4 * lpg - 1) / (4 * lpg);
+      switch (lpg) {
+        case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
+        case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
+        case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
+        default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
+      }
+    }
+    return st;
+  }
+  if (const char* e = getenv("ISP_EXP_SLICES")) {  // experiment: column slices spread over XCDs
+    const int ns = atoi(e);
+    if (ns == -1 && vec == 2 && d <= 2 * ISP_WAVE) {
+      const isp_view& v = A->v;
+      const unsigned grid = (unsigned)((v.n_blocks + v.n_seg + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
+      k_spmm<2, 1, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, 0, Y, ldy, -1);
+      k_spmm_fixup<2, 1><<<(unsigned)((v.n_hub + 3) / 4 + 1), ISP_WG, 0, s>>>(v, d, 0, Y, ldy);
+      return ISP_OK;
+    }
+    if (ns > 1 && d <= ISP_PARTIAL_TILE && d % ns == 0) {
+      const int w = d / ns;
+      return launch_tile<1, 1, 1, 4>(A, X, ldx, d, 0, Y, ldy, s, ns);
+    }
+  }
   isp_status st = ISP_OK;
   int k0 = 0;
   while (k0 < d && st == ISP_OK) {  // column tiles of at most ISP_PARTIAL_TILE floats
