@@ -35,9 +35,12 @@ int env_int(const char* name, int dflt, int lo, int hi) {
 
 partition_params get_params() {
   partition_params p;
-  p.block_cost = env_int("ISP_BLOCK_COST", 256, 16, 1 << 20);
-  p.hub_t = env_int("ISP_HUB_THRESHOLD", 512, 8, 1 << 24);
-  p.seg_len = env_int("ISP_SEGMENT_LEN", 512, 8, 1 << 24);
+  // Upper limits = what the grouped kernels' per-wave LDS tables hold (block_cost + hub_t <= 768
+  // entries, block_cost <= 256 rows, seg_len <= 768 entries).  The environment overrides exist for
+  // tuning and for tests that want many small work items.
+  p.block_cost = env_int("ISP_BLOCK_COST", 256, 16, 256);
+  p.hub_t = env_int("ISP_HUB_THRESHOLD", 512, 8, 512);
+  p.seg_len = env_int("ISP_SEGMENT_LEN", 512, 8, 768);
   return p;
 }
 
@@ -53,50 +56,55 @@ __device__ inline int degree_bin(long long deg, int hub_t) {
   return 3;
 }
 
-// One thread per row: degree, class, cost, segment count; indptr checks; class histogram.
+// Per row: degree, class, cost, segment count; indptr checks.  Grid-stride; the class histogram,
+// maximum degree and segment total are reduced per workgroup before a handful of integer atomics.
 __global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ indptr, int64_t n_rows, int64_t nnz,
                                                   partition_params pp, int32_t* __restrict__ cost,
                                                   int32_t* __restrict__ hubflag, int32_t* __restrict__ nseg,
                                                   build_counters* __restrict__ ctr) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int lane = threadIdx.x & (ISP_WAVE - 1);
-  long long deg = 0;
-  bool bad = false;
-  const bool live = i < n_rows;
-  if (live) {
+  __shared__ unsigned long long s_rows[5], s_nnz[5], s_max;
+  __shared__ int s_err, s_seg;
+  if (threadIdx.x < 5) { s_rows[threadIdx.x] = 0; s_nnz[threadIdx.x] = 0; }
+  if (threadIdx.x == 0) { s_max = 0; s_err = 0; s_seg = 0; }
+  __syncthreads();
+  unsigned long long my_rows[5] = {0, 0, 0, 0, 0}, my_nnz[5] = {0, 0, 0, 0, 0}, my_max = 0;
+  int my_err = 0, my_seg = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_rows; i += (int64_t)gridDim.x * blockDim.x) {
     const int64_t a = indptr[i], b = indptr[i + 1];
-    deg = b - a;
-    bad = deg < 0 || a < 0 || b > nnz || (i == 0 && a != 0) || (i == n_rows - 1 && b != nnz);
-    if (bad) deg = 0;
+    long long deg = b - a;
+    if (deg < 0 || a < 0 || b > nnz || (i == 0 && a != 0) || (i == n_rows - 1 && b != nnz)) { my_err = 1; deg = 0; }
     const bool hub = deg > pp.hub_t;
+    const int ns = hub ? (int)((deg + pp.seg_len - 1) / pp.seg_len) : 0;
     cost[i] = hub ? 0 : (int32_t)deg + 1;
     hubflag[i] = hub ? 1 : 0;
-    nseg[i] = hub ? (int32_t)((deg + pp.seg_len - 1) / pp.seg_len) : 0;
-  }
-  if (__any(bad) && lane == 0) atomicOr(&ctr->err, 1);
-  const int bin = live ? degree_bin(deg, pp.hub_t) : -1;
+    nseg[i] = ns;
+    const int bin = degree_bin(deg, pp.hub_t);
 #pragma unroll
-  for (int b = 0; b < 5; ++b) {
-    const unsigned long long m = __ballot(bin == b);
-    long long s = (bin == b) ? deg : 0;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-    if (lane == 0 && m) {
-      atomicAdd(&ctr->bin_rows[b], (unsigned long long)__popcll(m));
-      if (s) atomicAdd(&ctr->bin_nnz[b], (unsigned long long)s);
+    for (int k = 0; k < 5; ++k) {
+      my_rows[k] += (bin == k);
+      my_nnz[k] += (bin == k) ? (unsigned long long)deg : 0ull;
     }
+    my_max = (unsigned long long)deg > my_max ? (unsigned long long)deg : my_max;
+    my_seg += ns;
   }
-  long long mx = deg;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    long long t = __shfl_xor(mx, o);
-    mx = t > mx ? t : mx;
+  for (int k = 0; k < 5; ++k) {
+    if (my_rows[k]) atomicAdd(&s_rows[k], my_rows[k]);
+    if (my_nnz[k]) atomicAdd(&s_nnz[k], my_nnz[k]);
   }
-  if (lane == 0 && mx > 0) atomicMax(&ctr->max_degree, (unsigned long long)mx);
-  int tot = live ? (int)((deg > pp.hub_t) ? (deg + pp.seg_len - 1) / pp.seg_len : 0) : 0;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o);
-  if (lane == 0 && tot) atomicAdd(&ctr->n_seg, tot);
+  if (my_max) atomicMax(&s_max, my_max);
+  if (my_err) atomicOr(&s_err, 1);
+  if (my_seg) atomicAdd(&s_seg, my_seg);
+  __syncthreads();
+  if (threadIdx.x < 5) {
+    if (s_rows[threadIdx.x]) atomicAdd(&ctr->bin_rows[threadIdx.x], s_rows[threadIdx.x]);
+    if (s_nnz[threadIdx.x]) atomicAdd(&ctr->bin_nnz[threadIdx.x], s_nnz[threadIdx.x]);
+  }
+  if (threadIdx.x == 0) {
+    if (s_max) atomicMax(&ctr->max_degree, s_max);
+    if (s_err) atomicOr(&ctr->err, 1);
+    if (s_seg) atomicAdd(&ctr->n_seg, s_seg);
+  }
 }
 
 // Column indices must lie in [0, n_cols).
@@ -228,7 +236,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   ISP_LAUNCH_CHECK();
   const unsigned row_grid = (unsigned)((n_rows + 255) / 256);
   if (n_rows > 0) {
-    k_row_pass<<<row_grid, 256, 0, s>>>(indptr, n_rows, nnz, pp, cost, hubflag, nseg, ctr);
+    k_row_pass<<<row_grid < 2048 ? row_grid : 2048, 256, 0, s>>>(indptr, n_rows, nnz, pp, cost, hubflag, nseg, ctr);
     ISP_LAUNCH_CHECK();
   }
   if (validate && nnz > 0) {

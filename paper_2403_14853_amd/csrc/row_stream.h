@@ -28,22 +28,6 @@ __device__ inline void load_vec(const float* __restrict__ p, float (&o)[VEC]) {
   else { o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
 }
 
-typedef float isp_f2 __attribute__((ext_vector_type(2)));
-typedef float isp_f4 __attribute__((ext_vector_type(4)));
-
-// Same as load_vec with the non-temporal (streaming) cache hint.
-template <int VEC>
-__device__ inline void load_vec_nt(const float* __restrict__ p, float (&o)[VEC]) {
-  if constexpr (VEC == 1) { o[0] = __builtin_nontemporal_load(p); }
-  else if constexpr (VEC == 2) {
-    const isp_f2 v = __builtin_nontemporal_load(reinterpret_cast<const isp_f2*>(p));
-    o[0] = v.x; o[1] = v.y;
-  } else {
-    const isp_f4 v = __builtin_nontemporal_load(reinterpret_cast<const isp_f4*>(p));
-    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
-  }
-}
-
 template <int VEC>
 __device__ inline void store_vec(float* __restrict__ p, const float (&o)[VEC]) {
   using V = typename vec_of<VEC>::type;
@@ -108,21 +92,10 @@ __device__ inline item_range locate_item(const isp_view& A, const int64_t* __res
 template <class P>
 __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                    const int32_t* __restrict__ indices, const float* __restrict__ values,
-                                   const typename P::args& pa, int d, int k0, float* __restrict__ Y, int64_t ldy,
-                                   int n_slices_in = 1) {
+                                   const typename P::args& pa, int d, int k0, float* __restrict__ Y, int64_t ldy) {
   constexpr int VEC = P::VEC, T = P::T, NG = P::NG, U = P::U;
   const int lane = threadIdx.x & (ISP_WAVE - 1);
-  // With n_slices > 1 consecutive workgroups (which the dispatcher deals round-robin to the
-  // XCDs) take different column slices of the same items, so each XCD's L2 only ever holds one
-  // slice of the gathered rows.
-  const int n_slices = n_slices_in < 0 ? 1 : n_slices_in;  // negative: experiment, non-temporal gathers
-  const int wg = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / n_slices));
-  const int slice = __builtin_amdgcn_readfirstlane((int)(blockIdx.x % n_slices));
-  const int item = wg * ISP_WAVES_PER_WG + (int)(threadIdx.x >> 6);
-  const int slice_w = (n_slices > 1) ? (d + n_slices - 1) / n_slices : d;
-  const int k_lo = (n_slices > 1) ? slice * slice_w : k0;
-  const int k_hi = (n_slices > 1) ? ((k_lo + slice_w < d) ? k_lo + slice_w : d) : d;
-  const int part_k0 = (n_slices > 1) ? 0 : k0;
+  const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6)));
   if (item >= A.n_blocks + A.n_seg) return;
   item_range it = locate_item(A, indptr, item);
   if (it.skip) return;
@@ -131,13 +104,13 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
   bool on[T];
 #pragma unroll
   for (int tt = 0; tt < T; ++tt) {
-    col[tt] = k_lo + (tt * ISP_WAVE + lane) * VEC;
-    on[tt] = col[tt] < k_hi;
+    col[tt] = k0 + (tt * ISP_WAVE + lane) * VEC;
+    on[tt] = col[tt] < d;
   }
   // where results go: Y rows for block items, partial rows for segments
   float* __restrict__ out = it.is_seg ? A.partials : Y;
   const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
-  const int out_k0 = it.is_seg ? part_k0 : 0;  // partial rows hold only the current column tile
+  const int out_k0 = it.is_seg ? k0 : 0;  // partial rows hold only the current column tile
 
   int row = it.row;
   const int row_last = it.row_last;
@@ -209,7 +182,7 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
             const float* __restrict__ src = pa.src[g] + (int64_t)cj * pa.ld[g];
 #pragma unroll
             for (int tt = 0; tt < T; ++tt) {
-              if (on[tt]) { if (n_slices_in < 0) load_vec_nt<VEC>(src + col[tt], x[u][g][tt]); else load_vec<VEC>(src + col[tt], x[u][g][tt]); }
+              if (on[tt]) load_vec<VEC>(src + col[tt], x[u][g][tt]);
               else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) x[u][g][tt][v] = 0.f;

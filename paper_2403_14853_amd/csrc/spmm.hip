@@ -29,13 +29,12 @@ template <int VEC, int T, bool HAS_VAL>
 __global__ void __launch_bounds__(ISP_WG) k_spmm(isp_view A, const int64_t* __restrict__ indptr,
                                                  const int32_t* __restrict__ indices,
                                                  const float* __restrict__ values, const float* __restrict__ X,
-                                                 int64_t ldx, int d, int k0, float* __restrict__ Y, int64_t ldy,
-                                                 int n_slices) {
+                                                 int64_t ldx, int d, int k0, float* __restrict__ Y, int64_t ldy) {
   using P = spmm_policy<VEC, T, HAS_VAL>;
   typename P::args pa;
   pa.src[0] = X;
   pa.ld[0] = ldx;
-  stream_item<P>(A, indptr, indices, values, pa, d, k0, Y, ldy, n_slices);
+  stream_item<P>(A, indptr, indices, values, pa, d, k0, Y, ldy);
 }
 
 template <int VEC, int T>
@@ -43,22 +42,22 @@ __global__ void __launch_bounds__(ISP_WG) k_spmm_fixup(isp_view A, int d, int k0
   hub_fixup<VEC, T, false>(A, d, k0, Y, ldy);
 }
 
-template <int VEC, int T, int FV = VEC, int FT = T>
+template <int VEC, int T>
 isp_status launch_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int k0, float* Y, int64_t ldy,
-                       hipStream_t s, int n_slices = 1) {
+                       hipStream_t s) {
   const isp_view& v = A->v;
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
-    const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * n_slices;
+    const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
     if (v.values)
-      k_spmm<VEC, T, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy, n_slices);
+      k_spmm<VEC, T, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy);
     else
-      k_spmm<VEC, T, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy, n_slices);
+      k_spmm<VEC, T, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
     const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    k_spmm_fixup<FV, FT><<<grid, ISP_WG, 0, s>>>(v, d, k0, Y, ldy);
+    k_spmm_fixup<VEC, T><<<grid, ISP_WG, 0, s>>>(v, d, k0, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   return ISP_OK;
@@ -206,20 +205,6 @@ isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_
       }
     }
     return st;
-  }
-  if (const char* e = getenv("ISP_EXP_SLICES")) {  // experiment: column slices spread over XCDs
-    const int ns = atoi(e);
-    if (ns == -1 && vec == 2 && d <= 2 * ISP_WAVE) {
-      const isp_view& v = A->v;
-      const unsigned grid = (unsigned)((v.n_blocks + v.n_seg + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-      k_spmm<2, 1, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, 0, Y, ldy, -1);
-      k_spmm_fixup<2, 1><<<(unsigned)((v.n_hub + 3) / 4 + 1), ISP_WG, 0, s>>>(v, d, 0, Y, ldy);
-      return ISP_OK;
-    }
-    if (ns > 1 && d <= ISP_PARTIAL_TILE && d % ns == 0) {
-      const int w = d / ns;
-      return launch_tile<1, 1, 1, 4>(A, X, ldx, d, 0, Y, ldy, s, ns);
-    }
   }
   isp_status st = ISP_OK;
   int k0 = 0;

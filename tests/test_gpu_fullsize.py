@@ -1,0 +1,108 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(default partition parameters).  The oracle's OpenMP row loops finish these in seconds on the
+box's host cores, so outputs are compared in full, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import graphgen
+import oracle
+import paper_2403_14853_amd as isp
+from gpu_util import assert_close, build, dev
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def _say(msg):
+    print("[fullsize] " + msg, flush=True)
+
+
+def _transpose_exact(A, w):
+    At, _ = isp.csr_transpose_cached(A)
+    ti, tj, tv, perm = At.export()
+    o_ti, o_tj, o_perm, o_tv = oracle.transpose(w.n, w.n, w.indptr, w.indices, w.values)
+    assert np.array_equal(ti.cpu().numpy(), o_ti), "t_indptr differs"
+    assert np.array_equal(tj.cpu().numpy(), o_tj), "t_indices differs"
+    assert np.array_equal(perm.cpu().numpy(), o_perm), "perm differs"
+    if w.values is not None:
+        assert np.array_equal(tv.cpu().numpy(), o_tv), "t_values differs"
+    del ti, tj, tv, perm
+    return At, (o_ti, o_tj, o_tv)
+
+
+@pytest.mark.parametrize("k", [1, 3])
+def test_spmm_forward_backward_full(k):
+    _say("config %d: generating" % k)
+    w = graphgen.make_config(k)
+    A = build(w.indptr, w.indices, w.values)
+    info = A.info()
+    _say("n=%d nnz=%d max_degree=%d hub_rows=%d items=%d" % (w.n, w.nnz, info["max_degree"], info["n_hub_rows"],
+                                                             info["n_row_blocks"] + info["n_segments"]))
+    if k == 3:
+        assert info["max_degree"] > 10_000 and info["n_hub_rows"] > 0  # the nnz-split hub path is exercised
+    X, dY = dev(w.X), dev(w.dY)
+    Y = torch.empty_like(X)
+    isp.spmm(A, X, Y)
+    _say("forward: oracle")
+    ref, mag = oracle.spmm(w.indptr, w.indices, w.values, w.X)
+    assert_close(Y, ref, mag, "spmm forward")
+    del ref, mag
+    _say("transpose: oracle")
+    At, (o_ti, o_tj, o_tv) = _transpose_exact(A, w)
+    isp.spmm(At, dY, Y)
+    _say("backward: oracle")
+    ref, mag = oracle.spmm(o_ti, o_tj, o_tv, w.dY)
+    assert_close(Y, ref, mag, "spmm backward")
+    A.destroy()
+
+
+def test_dense_degree_config2_spmm_and_sddmm_full():
+    _say("config 2: generating")
+    w = graphgen.make_config(2)
+    A = build(w.indptr, w.indices, w.values)
+    X, dY = dev(w.X), dev(w.dY)
+    Y = torch.empty_like(X)
+    isp.spmm(A, X, Y)
+    _say("forward: oracle")
+    ref, mag = oracle.spmm(w.indptr, w.indices, w.values, w.X)
+    assert_close(Y, ref, mag, "spmm forward")
+    del ref, mag
+    # row-mean values: A 1 = 1 on non-empty rows (closed form, independent of the oracle)
+    ones = torch.ones(w.n, 4, device="cuda")
+    Y1 = torch.empty_like(ones)
+    isp.spmm(A, ones, Y1)
+    nonempty = torch.from_numpy(np.diff(w.indptr) > 0).cuda()
+    assert torch.allclose(Y1[nonempty], torch.ones_like(Y1[nonempty]), rtol=0, atol=2e-5)
+    assert torch.all(Y1[~nonempty] == 0)
+    _say("transpose: oracle")
+    At, (o_ti, o_tj, o_tv) = _transpose_exact(A, w)
+    isp.spmm(At, dY, Y)
+    ref, mag = oracle.spmm(o_ti, o_tj, o_tv, w.dY)
+    assert_close(Y, ref, mag, "spmm backward")
+    del ref, mag, o_ti, o_tj, o_tv
+    dA = torch.empty(w.nnz, device="cuda")
+    isp.sddmm(A, dY, X, dA)
+    _say("sddmm: oracle")
+    ref, mag = oracle.sddmm(w.indptr, w.indices, w.values, w.dY, w.X)
+    assert_close(dA, ref, mag, "sddmm")
+    A.destroy()
+
+
+def test_fusedmm_config4_full():
+    _say("config 4: generating")
+    w = graphgen.make_config(4)
+    A = build(w.indptr, w.indices, None)  # unit edge values: no value array is read
+    X, dY = dev(w.X), dev(w.dY)
+    Y = torch.empty_like(X)
+    isp.fusedmm(A, X, Y)
+    _say("forward: oracle")
+    ref, mag = oracle.fusedmm(w.indptr, w.indices, None, w.X)
+    assert_close(Y, ref, mag, "fusedmm forward")
+    del ref, mag
+    At, _ = isp.csr_transpose_cached(A)
+    dX = torch.empty_like(X)
+    isp.fusedmm_backward(A, X, dY, dX)
+    _say("backward: oracle (sequential scatter form)")
+    ref, mag = oracle.fusedmm_backward(w.indptr, w.indices, None, w.X, w.dY)
+    assert_close(dX, ref, mag, "fusedmm backward")
+    A.destroy()
