@@ -125,7 +125,7 @@ def main():
     gather_bytes = csr_bytes + 4.0 * d * nnz + 4.0 * n * d  # every entry fetches its own X row
     achieved = alg_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": "k_fused<fwd>" if dom == "fusedmm" else "k_spmm",
+        "bound": "hbm", "kernel": "k_fused_grouped<g_fwd>" if dom == "fusedmm" else "k_spmm_grouped",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES.get((args.config, args.shrink)),
         "algorithmic_bytes": alg_bytes, "launch_ms": round(dom_ms, 4),
@@ -157,7 +157,9 @@ def main():
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); keyed by (config, shrink).  None = not measured for that workload.
-TRAFFIC_BYTES = {}
+TRAFFIC_BYTES = {
+    (3, 1): 51.32e9,  # profiles/spmm_c3-rmat2.4m-d128.txt: 2 x FETCH_SIZE (calibrated) + WRITE_SIZE of k_spmm_grouped
+}
 
 
 def cpu_baseline(w, Y_gpu, dom):

@@ -31,6 +31,14 @@ def build(verbose: bool = False) -> str:
     if verbose and out.strip():
         print(out)
     os.replace(tmp, LIB)
+    # stand-alone bandwidth probe (measurement companion, not linked into the library)
+    probe = os.path.join(HERE, "bw_probe")
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
+                          "-packed-fp32-ops", os.path.join(CSRC, "bw_probe.hip"), "-o", probe + ".tmp"],
+                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on bw_probe.hip:\n" + res.stdout)
+    os.replace(probe + ".tmp", probe)
     return LIB
 
 

@@ -225,7 +225,17 @@ __device__ inline void hub_fixup(const isp_view& A, int d, int k0, float* __rest
     float acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-    for (int s = s0; s < s1; ++s) {
+    int s = s0;
+    for (; s + 8 <= s1; s += 8) {  // eight partial rows in flight, added in segment order
+      float t[8][VEC];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) load_vec<VEC>(A.partials + (int64_t)(s + u) * ISP_PARTIAL_TILE + rel, t[u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += t[u][v];
+    }
+    for (; s < s1; ++s) {
       float t[VEC];
       load_vec<VEC>(A.partials + (int64_t)s * ISP_PARTIAL_TILE + rel, t);
 #pragma unroll

@@ -190,9 +190,16 @@ isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_
                           A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + av.hub_t <= GS_MAX_ENT &&
                           av.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
   if (grouped_ok) {
-    // lanes per group: 8 / 16 / 32 / 64 <-> slices of 32 / 64 / 128 / 256 columns
-    int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : (d <= 128 ? 32 : 64));
-    if (const char* e = getenv("ISP_SPMM_LPG")) lpg = atoi(e);
+    // Lanes per group 8 / 16 / 32 / 64 <-> column slices of 32 / 64 / 128 / 256 floats.  One slice
+    // per row is the default; on large graphs two slices per row (dealt to alternating XCDs, so
+    // each L2 keeps half-rows of twice as many hot columns) measured faster despite reading the
+    // CSR arrays twice.  ISP_SPMM_LPG overrides the choice for tuning.
+    const bool large = av.nnz >= (int64_t)8 << 20;
+    int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : (d <= 128 ? (large ? 16 : 32) : (large ? 32 : 64)));
+    if (const char* e = getenv("ISP_SPMM_LPG")) {
+      const int v = atoi(e);
+      if (v == 8 || v == 16 || v == 32 || v == 64) lpg = v;
+    }
     isp_status st = ISP_OK;
     for (int k_base = 0; k_base < d && st == ISP_OK; k_base += ISP_PARTIAL_TILE) {
       const int w = (d - k_base < ISP_PARTIAL_TILE) ? d - k_base : ISP_PARTIAL_TILE;
