@@ -32,6 +32,11 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--shrink", type=int, default=1, help="divide the graph size (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--epoch-ablation", type=int, default=0, metavar="E",
+                    help="instead of the benchmark line: time E training epochs (forward + backward SpMM) with "
+                         "the cached transpose and with the transpose rebuilt every epoch")
+    ap.add_argument("--sweep-d", action="store_true",
+                    help="instead of the benchmark line: SpMM forward time over feature widths 8..1024")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain device copies of X (known size) before the timed region, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -53,7 +58,8 @@ def main():
     gen_s = time.time() - t0
     n, d, nnz = w.n, w.d, w.nnz
     dev = lambda a: torch.from_numpy(a).cuda()
-    indptr, indices, values = dev(w.indptr), dev(w.indices), dev(w.values)
+    indptr, indices = dev(w.indptr), dev(w.indices)
+    values = None if w.values is None else dev(w.values)
     X, dY = dev(w.X), dev(w.dY)
     torch.cuda.synchronize()
     stream = torch.cuda.current_stream()
@@ -69,6 +75,13 @@ def main():
     A, build_ms = timed(lambda: isp.csr_build(indptr, indices, values))
     (At, _), transpose_ms = timed(lambda: isp.csr_transpose_cached(A))
     info, info_t = A.info(), At.info()
+
+    if args.epoch_ablation > 0:
+        print(json.dumps(epoch_ablation(isp, w, indptr, indices, values, X, dY, args.epoch_ablation)))
+        return
+    if args.sweep_d:
+        print(json.dumps(sweep_d(isp, w, A)))
+        return
 
     ops = list(w.ops)
     if args.config == 1:  # two-layer GCN step: forward and backward SpMM per layer
@@ -160,6 +173,63 @@ def main():
 TRAFFIC_BYTES = {
     (3, 1): 51.32e9,  # profiles/spmm_c3-rmat2.4m-d128.txt: 2 x FETCH_SIZE (calibrated) + WRITE_SIZE of k_spmm_grouped
 }
+
+
+def _time_ms(fn, reps):
+    import torch
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    b.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def epoch_ablation(isp, w, indptr, indices, values, X, dY, epochs):
+    """The paper's caching claim at kernel level (Section 3.3): per-epoch time of forward + backward
+    SpMM when the transpose is built once and cached vs rebuilt in every epoch."""
+    import torch
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    A = isp.csr_build(indptr, indices, values)
+
+    def epoch_cached():
+        isp.spmm(A, X, Y)
+        At, _ = isp.csr_transpose_cached(A)  # built in the first epoch only
+        isp.spmm(At, dY, dX)
+
+    first = _time_ms(epoch_cached, 1)
+    cached = _time_ms(epoch_cached, epochs)
+
+    def epoch_uncached():
+        B = isp.csr_build(indptr, indices, values)  # fresh handle: nothing cached
+        isp.spmm(B, X, Y)
+        Bt, _ = isp.csr_transpose_cached(B)
+        isp.spmm(Bt, dY, dX)
+        torch.cuda.synchronize()
+        B.destroy()
+
+    epoch_uncached()
+    uncached = _time_ms(epoch_uncached, epochs)
+    return {"what": "epoch ablation: SpMM forward + backward per epoch", "workload": w.name, "epochs": epochs,
+            "first_epoch_ms_with_cache": round(first, 3), "epoch_ms_cached_transpose": round(cached, 3),
+            "epoch_ms_transpose_rebuilt": round(uncached, 3), "speedup_from_cache": round(uncached / cached, 3)}
+
+
+def sweep_d(isp, w, A):
+    """SpMM forward over feature widths (the GPU counterpart of the paper's tuning graph, Section 3.2)."""
+    import torch
+    out = []
+    for d in (8, 16, 32, 64, 100, 128, 256, 512, 1024):
+        X = torch.randn(w.n, d, device="cuda")
+        Y = torch.empty_like(X)
+        isp.spmm(A, X, Y)
+        ms = _time_ms(lambda: isp.spmm(A, X, Y), 5)
+        out.append({"d": d, "ms": round(ms, 4), "gflops": round(2.0 * w.nnz * d / ms / 1e6, 1),
+                    "gather_GBps": round(w.nnz * (8.0 + 4.0 * d) / ms / 1e6, 1)})
+        del X, Y
+    return {"what": "SpMM forward vs feature width", "workload": w.name, "nnz": w.nnz, "sweep": out}
 
 
 def cpu_baseline(w, Y_gpu, dom):

@@ -193,7 +193,8 @@ def make_config(k: int, *, shrink: int = 1, graph_seed: int = 0, x_seed: int = 1
     else:
         indptr, indices = rmat_graph(n, r["m"], graph_seed, symmetrise=r["symmetrise"],
                                      self_loops=r["self_loops"])
-    vals = edge_values(indptr, indices, r["values"])
+    # unit edge values are represented by "no value array" (the kernels then read no values)
+    vals = None if r["values"] == "unit" else edge_values(indptr, indices, r["values"])
     dd = d if d is not None else r["d"]
     if r["feat"] == "uniform":
         X = uniform((n, dd), x_seed)

@@ -34,13 +34,13 @@ struct __attribute__((aligned(16))) gs_wave_lds {
 };
 struct gs_lds { gs_wave_lds w[ISP_WAVES_PER_WG]; };
 
-// step descriptor (16 bits): bits 0..9 entry offset, 10..13 live entries (0..8), bit 14 ends a row
-constexpr unsigned GS_LAST = 0x4000u;
+// step descriptor (16 bits): bits 0..9 entry offset, 10..14 live entries (0..16), bit 15 ends a row
+constexpr unsigned GS_LAST = 0x8000u;
 __device__ inline gs_u16 gs_pack(int off, int cnt, bool last) {
   return (gs_u16)((unsigned)off | ((unsigned)cnt << 10) | (last ? GS_LAST : 0u));
 }
 __device__ inline int gs_off(unsigned dsc) { return (int)(dsc & 0x3ffu); }
-__device__ inline int gs_cnt(unsigned dsc) { return (int)((dsc >> 10) & 15u); }
+__device__ inline int gs_cnt(unsigned dsc) { return (int)((dsc >> 10) & 31u); }
 
 // Orders this wave's earlier LDS writes before its later LDS reads (other lanes' data).  The LDS
 // unit executes one wave's operations in order, so only the compiler has to be held back.

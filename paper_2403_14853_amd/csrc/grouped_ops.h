@@ -65,7 +65,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
       dsc[u] = L.step[s0 + u];
       e[u] = L.ent[gs_off(dsc[u]) + g];
       srow[u] = irow;
-      irow += (int)((dsc[u] >> 14) & 1u);  // a row end moves the following steps to the next row
+      irow += (int)((dsc[u] >> 15) & 1u);  // a row end moves the following steps to the next row
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {

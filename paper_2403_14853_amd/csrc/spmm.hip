@@ -190,21 +190,25 @@ isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_
                           A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + av.hub_t <= GS_MAX_ENT &&
                           av.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
   if (grouped_ok) {
-    // Lanes per group 8 / 16 / 32 / 64 <-> column slices of 32 / 64 / 128 / 256 floats.  One slice
-    // per row is the default; on large graphs two slices per row (dealt to alternating XCDs, so
-    // each L2 keeps half-rows of twice as many hot columns) measured faster despite reading the
-    // CSR arrays twice.  ISP_SPMM_LPG overrides the choice for tuning.
+    // Lanes per group 4 / 8 / 16 / 32 / 64 <-> column slices of 16 / 32 / 64 / 128 / 256 floats.
+    // Measured on R-MAT graphs (2.4 M and 124 M nonzeros, d = 8..256): the slice that just covers
+    // the row wins up to d = 128; on large graphs two 64-float slices per 128-float row win
+    // (dealt to alternating XCDs, each L2 then keeps half-rows of twice as many hot columns,
+    // which outweighs reading the CSR arrays twice) provided both halves are whole 128-byte lines;
+    // wider rows run as 128-float slices.  ISP_SPMM_LPG overrides the choice for tuning.
     const bool large = av.nnz >= (int64_t)8 << 20;
-    int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : (d <= 128 ? (large ? 16 : 32) : (large ? 32 : 64)));
+    int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : 32);
+    if (large && d > 64 && d <= 128 && d % 64 == 0) lpg = 16;
     if (const char* e = getenv("ISP_SPMM_LPG")) {
       const int v = atoi(e);
-      if (v == 8 || v == 16 || v == 32 || v == 64) lpg = v;
+      if (v == 4 || v == 8 || v == 16 || v == 32 || v == 64) lpg = v;
     }
     isp_status st = ISP_OK;
     for (int k_base = 0; k_base < d && st == ISP_OK; k_base += ISP_PARTIAL_TILE) {
       const int w = (d - k_base < ISP_PARTIAL_TILE) ? d - k_base : ISP_PARTIAL_TILE;
       const int ns = (w + 4 * lpg - 1) / (4 * lpg);
       switch (lpg) {
+        case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
         case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
         case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
         case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;

@@ -91,7 +91,8 @@ def test_dense_degree_config2_spmm_and_sddmm_full():
 def test_fusedmm_config4_full():
     _say("config 4: generating")
     w = graphgen.make_config(4)
-    A = build(w.indptr, w.indices, None)  # unit edge values: no value array is read
+    assert w.values is None  # unit edge values: no value array is read
+    A = build(w.indptr, w.indices, None)
     X, dY = dev(w.X), dev(w.dY)
     Y = torch.empty_like(X)
     isp.fusedmm(A, X, Y)
