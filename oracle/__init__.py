@@ -49,6 +49,10 @@ def _load():
     lib.isp_oracle_fusedmm.restype = None
     lib.isp_oracle_fusedmm_backward.argtypes = [i64, vp, vp, vp, vp, i64, vp, i64, i32, vp, vp]
     lib.isp_oracle_fusedmm_backward.restype = None
+    lib.isp_oracle_spmm_reduce.argtypes = [i64, vp, vp, vp, vp, i64, i32, ctypes.c_int, vp, vp, vp]
+    lib.isp_oracle_spmm_reduce.restype = None
+    lib.isp_oracle_spmm_reduce_backward.argtypes = [i64, i64, vp, vp, vp, vp, i64, i32, ctypes.c_int, vp, vp, vp]
+    lib.isp_oracle_spmm_reduce_backward.restype = None
     _lib = lib
     return lib
 
@@ -163,4 +167,43 @@ def fusedmm_backward(indptr, indices, values, X, dY, want_mag=True):
     mag = np.empty((n, d), dtype=np.float64) if want_mag else None
     _load().isp_oracle_fusedmm_backward(n, _ptr(indptr), _ptr(indices), _ptr(values), _ptr(X), d, _ptr(dY), d, d,
                                         _ptr(dX), _ptr(mag))
+    return dX, mag
+
+
+REDUCE = {"sum": 0, "mean": 1, "min": 2, "max": 3}
+
+
+def spmm_reduce(indptr, indices, values, X, reduce, want_mag=True):
+    """Y = reduce over each row's stored entries of a_p * X[col_p] for reduce in 'mean', 'min', 'max'.
+    Returns (Y fp64, arg int32 | None, mag | None); min / max products are formed in fp32."""
+    indptr, indices, values = _csr(indptr, indices, values)
+    X = _dense(X)
+    n, d = indptr.shape[0] - 1, X.shape[1]
+    if indices.size:
+        assert indices.max() < X.shape[0] and indices.min() >= 0
+    r = REDUCE[reduce]
+    assert r in (1, 2, 3)
+    Y = np.empty((n, d), dtype=np.float64)
+    arg = np.empty((n, d), dtype=np.int32) if r >= 2 else None
+    mag = np.empty((n, d), dtype=np.float64) if (want_mag and r == 1) else None
+    _load().isp_oracle_spmm_reduce(n, _ptr(indptr), _ptr(indices), _ptr(values), _ptr(X), d, d, r, _ptr(Y),
+                                   _ptr(arg), _ptr(mag))
+    return Y, arg, mag
+
+
+def spmm_reduce_backward(n_cols, indptr, indices, values, dY, reduce, arg=None, want_mag=True):
+    """dX (n_cols x d, fp64) of spmm_reduce for upstream gradient dY; min / max need the forward's arg."""
+    indptr, indices, values = _csr(indptr, indices, values)
+    dY = _dense(dY)
+    n, d = indptr.shape[0] - 1, dY.shape[1]
+    assert dY.shape[0] == n
+    r = REDUCE[reduce]
+    assert r in (1, 2, 3)
+    if r >= 2:
+        arg = np.ascontiguousarray(arg, dtype=np.int32)
+        assert arg.shape == (n, d)
+    dX = np.empty((n_cols, d), dtype=np.float64)
+    mag = np.empty((n_cols, d), dtype=np.float64) if want_mag else None
+    _load().isp_oracle_spmm_reduce_backward(n, n_cols, _ptr(indptr), _ptr(indices), _ptr(values), _ptr(dY), d, d, r,
+                                            _ptr(arg), _ptr(dX), _ptr(mag))
     return dX, mag

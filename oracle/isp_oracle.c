@@ -232,3 +232,84 @@ void isp_oracle_fusedmm_backward(int64_t n, const int64_t* indptr, const int32_t
     }
   }
 }
+
+/* ---- other reductions of the sparse-dense product (Section 3.4, Section 3.5: reduce = 'sum',
+ * 'mean', 'min', 'max') ----------------------------------------------------------------------
+ * The paper names the reductions and gives no formula; the reading taken is the one of the
+ * scatter-style reduce it refers to:
+ *   mean: Y[i,k] = (sum_p a_p x_jk) / len_i, len_i = stored entries of row i; empty row -> 0.
+ *   min / max: Y[i,k] = min / max over the stored entries p of row i of a_p * x_jk; arg[i,k] = the
+ *     position p (index into the CSR arrays) of the first entry attaining it; empty row -> 0, arg -1.
+ * For min / max the product is formed and compared in fp32 (one rounded multiply), the precision
+ * the GPU kernel decides in, so values and arg positions can be compared bit for bit.
+ * reduce: 1 mean, 2 min, 3 max.  arg may be NULL for mean.  mag (mean only, may be NULL) is the sum
+ * of |a_p x_jk| / len_i. */
+void isp_oracle_spmm_reduce(int64_t n_rows, const int64_t* indptr, const int32_t* indices, const float* values,
+                            const float* X, int64_t ldx, int32_t d, int reduce, double* Y, int32_t* arg,
+                            double* mag) {
+#pragma omp parallel for schedule(dynamic, 256)
+  for (int64_t i = 0; i < n_rows; ++i) {
+    double* y = Y + i * (int64_t)d;
+    const int64_t s = indptr[i], e = indptr[i + 1];
+    if (reduce == 1) {
+      double* m = mag ? mag + i * (int64_t)d : NULL;
+      for (int32_t k = 0; k < d; ++k) {
+        double acc = 0.0, am = 0.0;
+        for (int64_t p = s; p < e; ++p) {
+          const double t = (values ? (double)values[p] : 1.0) * (double)X[(int64_t)indices[p] * ldx + k];
+          acc += t;
+          am += fabs(t);
+        }
+        y[k] = e > s ? acc / (double)(e - s) : 0.0;
+        if (m) m[k] = e > s ? am / (double)(e - s) : 0.0;
+      }
+    } else {
+      int32_t* a = arg + i * (int64_t)d;
+      for (int32_t k = 0; k < d; ++k) {
+        float best = 0.0f;
+        int32_t where = -1;
+        for (int64_t p = s; p < e; ++p) {
+          const float av = values ? values[p] : 1.0f;
+          const volatile float t = av * X[(int64_t)indices[p] * ldx + k];  /* fp32 product */
+          const float tv = t;
+          if (where < 0 || (reduce == 2 ? tv < best : tv > best)) { best = tv; where = (int32_t)p; }
+        }
+        y[k] = (double)best;
+        a[k] = where;
+      }
+    }
+  }
+}
+
+/* Backward of the reductions above, scatter form (sequential), dX is n_cols x d, zeroed here:
+ *   mean:      dX[j,:] += (a_p / len_i) dY[i,:]                for every entry p = (i, j)
+ *   min / max: dX[col(p),k] += a_p dY[i,k]  with p = arg[i,k]  (nothing for arg = -1)        */
+void isp_oracle_spmm_reduce_backward(int64_t n_rows, int64_t n_cols, const int64_t* indptr, const int32_t* indices,
+                                     const float* values, const float* dY, int64_t ldg, int32_t d, int reduce,
+                                     const int32_t* arg, double* dX, double* mag) {
+  memset(dX, 0, (size_t)n_cols * (size_t)d * sizeof(double));
+  if (mag) memset(mag, 0, (size_t)n_cols * (size_t)d * sizeof(double));
+  for (int64_t i = 0; i < n_rows; ++i) {
+    const int64_t s = indptr[i], e = indptr[i + 1];
+    const float* g = dY + i * ldg;
+    if (reduce == 1) {
+      for (int64_t p = s; p < e; ++p) {
+        const double w = (values ? (double)values[p] : 1.0) / (double)(e - s);
+        double* o = dX + (int64_t)indices[p] * d;
+        double* m = mag ? mag + (int64_t)indices[p] * d : NULL;
+        for (int32_t k = 0; k < d; ++k) {
+          o[k] += w * (double)g[k];
+          if (m) m[k] += fabs(w * (double)g[k]);
+        }
+      }
+    } else {
+      for (int32_t k = 0; k < d; ++k) {
+        const int32_t p = arg[i * (int64_t)d + k];
+        if (p < 0) continue;
+        const double t = (values ? (double)values[p] : 1.0) * (double)g[k];
+        dX[(int64_t)indices[p] * d + k] += t;
+        if (mag) mag[(int64_t)indices[p] * d + k] += fabs(t);
+      }
+    }
+  }
+}
