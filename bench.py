@@ -37,6 +37,8 @@ def main():
                          "the cached transpose and with the transpose rebuilt every epoch")
     ap.add_argument("--sweep-d", action="store_true",
                     help="instead of the benchmark line: SpMM forward time over feature widths 8..1024")
+    ap.add_argument("--reductions", action="store_true",
+                    help="instead of the benchmark line: forward and backward time of the mean / min / max reductions")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain device copies of X (known size) before the timed region, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -81,6 +83,9 @@ def main():
         return
     if args.sweep_d:
         print(json.dumps(sweep_d(isp, w, A)))
+        return
+    if args.reductions:
+        print(json.dumps(reductions(isp, w, A, X, dY)))
         return
 
     ops = list(w.ops)
@@ -230,6 +235,24 @@ def sweep_d(isp, w, A):
                     "gather_GBps": round(w.nnz * (8.0 + 4.0 * d) / ms / 1e6, 1)})
         del X, Y
     return {"what": "SpMM forward vs feature width", "workload": w.name, "nnz": w.nnz, "sweep": out}
+
+
+def reductions(isp, w, A, X, dY):
+    """mean / min / max SpMM (generic path) forward and backward, next to the tuned sum."""
+    import torch
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    arg = torch.empty(w.n, w.d, dtype=torch.int32, device="cuda")
+    out = {}
+    for r in ("sum", "mean", "min", "max"):
+        a = arg if r in ("min", "max") else None
+        isp.spmm_reduce(A, X, Y, r, a)
+        f = _time_ms(lambda: isp.spmm_reduce(A, X, Y, r, a), 5)
+        isp.spmm_reduce_backward(A, dY, dX, r, a)
+        b = _time_ms(lambda: isp.spmm_reduce_backward(A, dY, dX, r, a), 5)
+        out[r] = {"forward_ms": round(f, 4), "backward_ms": round(b, 4),
+                  "forward_gflops": round(2.0 * w.nnz * w.d / f / 1e6, 1)}
+    return {"what": "SpMM reductions, forward and backward through the cached transpose", "workload": w.name,
+            "reductions": out}
 
 
 def cpu_baseline(w, Y_gpu, dom):

@@ -148,6 +148,35 @@ isp_status isp_fusedmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t 
 isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const float* dY, int64_t lddy,
                                 int32_t d, int op, float* dX, int64_t lddx, void* stream);
 
+/* reduce of isp_spmm_reduce / isp_spmm_reduce_backward */
+#define ISP_REDUCE_SUM 0
+#define ISP_REDUCE_MEAN 1
+#define ISP_REDUCE_MIN 2
+#define ISP_REDUCE_MAX 3
+
+/*
+ * SpMM with the other reductions of the paper's matmul (Sections 3.4, 3.5: 'sum', 'mean', 'min', 'max').
+ *   sum : same as isp_spmm.
+ *   mean: Y[i] = (sum_p values[p] X[indices[p]]) / (stored entries of row i); empty row -> 0.
+ *   min / max: Y[i,k] = min / max over the stored entries p of row i of values[p] * X[indices[p], k], product
+ *         and comparison in fp32; arg[i,k] = position p (index into indices / values) of the first entry that
+ *         attains it; empty row -> Y = 0, arg = -1.  arg is int32, n_rows x d, row-major, dense (leading
+ *         dimension d), required for min / max, ignored otherwise.
+ * As in the paper, only the sum reduction has the tuned kernels; the others run on the generic path.
+ */
+isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
+                           int64_t ldy, int32_t* arg, void* stream);
+
+/*
+ * Backward of isp_spmm_reduce with respect to X, through the cached transpose (Section 3.3), which must
+ * have been built (isp_csr_transpose_cached) - otherwise ISP_EINVAL.  dX is n_cols x d and is overwritten.
+ *   sum : dX = A^T dY.   mean: dX[j] = sum_{p in column j} (values[p] / len(row(p))) dY[row(p)].
+ *   min / max: dX[j,k] = sum over entries p in column j with arg[row(p),k] == p of values[p] dY[row(p),k];
+ *         arg is the array the forward call filled.
+ */
+isp_status isp_spmm_reduce_backward(isp_csr_t* A, const float* dY, int64_t lddy, int32_t d, int reduce,
+                                    const int32_t* arg, float* dX, int64_t lddx, void* stream);
+
 /* Free the host-side handle and its cached transpose handle.  Never touches caller buffers.  NULL ok. */
 void isp_csr_destroy(isp_csr_t* A);
 

@@ -7,5 +7,5 @@ the import of :mod:`paper_2403_14853_amd.binding` fails loudly.
 """
 from .binding import (  # noqa: F401
     CSR, IspError, lib_path, load_library, csr_build, csr_transpose_cached, spmm, sddmm, fusedmm,
-    fusedmm_backward, EXPORTED_SYMBOLS,
+    fusedmm_backward, spmm_reduce, spmm_reduce_backward, EXPORTED_SYMBOLS,
 )

@@ -15,7 +15,7 @@ _lib = None
 EXPORTED_SYMBOLS = [
     "isp_csr_build_workspace", "isp_csr_build", "isp_csr_transpose_workspace", "isp_csr_transpose_cached",
     "isp_csr_export", "isp_csr_info", "isp_spmm", "isp_sddmm", "isp_fusedmm", "isp_fusedmm_backward",
-    "isp_csr_destroy", "isp_last_error", "isp_version",
+    "isp_spmm_reduce", "isp_spmm_reduce_backward", "isp_csr_destroy", "isp_last_error", "isp_version",
 ]
 
 ISP_TRUSTED = 1
@@ -64,6 +64,8 @@ def load_library():
     lib.isp_sddmm.argtypes = [vp, vp, i64, vp, i64, i32, u32, vp, vp]
     lib.isp_fusedmm.argtypes = [vp, vp, i64, i32, ctypes.c_int, vp, i64, vp]
     lib.isp_fusedmm_backward.argtypes = [vp, vp, i64, vp, i64, i32, ctypes.c_int, vp, i64, vp]
+    lib.isp_spmm_reduce.argtypes = [vp, vp, i64, i32, ctypes.c_int, vp, i64, vp, vp]
+    lib.isp_spmm_reduce_backward.argtypes = [vp, vp, i64, i32, ctypes.c_int, vp, vp, i64, vp]
     lib.isp_csr_destroy.argtypes = [vp]
     lib.isp_csr_destroy.restype = None
     for name in EXPORTED_SYMBOLS:
@@ -244,4 +246,28 @@ def fusedmm_backward(A: CSR, X, dY, dX, *, op=ISP_OP_SIGMOID, stream=None):
     assert dY.shape == X.shape and dX.shape == X.shape
     _check(load_library().isp_fusedmm_backward(A._h, _dptr(X), _ld(X), _dptr(dY), _ld(dY), d, op, _dptr(dX),
                                                _ld(dX), _stream(stream)))
+    return dX
+
+
+REDUCE = {"sum": 0, "mean": 1, "min": 2, "max": 3}
+
+
+def spmm_reduce(A: CSR, X, Y, reduce: str, arg=None, *, stream=None):
+    """isp_spmm_reduce: reduce in 'sum' | 'mean' | 'min' | 'max'; arg (int32 [n_rows, d], contiguous) for min / max."""
+    import torch
+    d = X.shape[1]
+    assert X.shape[0] == A.n_cols and Y.shape == (A.n_rows, d)
+    if arg is not None:
+        assert arg.dtype == torch.int32 and arg.is_contiguous() and arg.shape == (A.n_rows, d)
+    _check(load_library().isp_spmm_reduce(A._h, _dptr(X), _ld(X), d, REDUCE[reduce], _dptr(Y), _ld(Y), _dptr(arg),
+                                          _stream(stream)))
+    return Y
+
+
+def spmm_reduce_backward(A: CSR, dY, dX, reduce: str, arg=None, *, stream=None):
+    """isp_spmm_reduce_backward (needs csr_transpose_cached(A) first)."""
+    d = dY.shape[1]
+    assert dY.shape[0] == A.n_rows and dX.shape == (A.n_cols, d)
+    _check(load_library().isp_spmm_reduce_backward(A._h, _dptr(dY), _ld(dY), d, REDUCE[reduce], _dptr(arg),
+                                                   _dptr(dX), _ld(dX), _stream(stream)))
     return dX

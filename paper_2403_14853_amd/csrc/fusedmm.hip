@@ -40,7 +40,7 @@ constexpr int pick_u(int regs_per_edge) { return regs_per_edge >= 8 ? 2 : (regs_
 template <int VEC_, int T_, bool HAS_VAL_>
 struct fwd_policy {
   static constexpr int VEC = VEC_, T = T_, NG = 1, U = pick_u(VEC_ * T_);
-  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false;
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = false, HAS_FINISH = false;
   struct args { const float* src[1]; int64_t ld[1]; };
   struct row_state { float xi[T][VEC]; };
   __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
@@ -48,7 +48,7 @@ struct fwd_policy {
     load_row<VEC, T>(pa.src[0], pa.ld[0], row, col, on, rs.xi);
   }
   __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[1][T][VEC],
-                                     float (&acc)[T][VEC], const bool (&)[T]) {
+                                     float (&acc)[T][VEC], const bool (&)[T], const edge_info&) {
     const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xi, x[0]));
     const float w = a * sigmoidf_fast(z);
 #pragma unroll
@@ -62,7 +62,7 @@ struct fwd_policy {
 template <int VEC_, int T_, bool HAS_VAL_>
 struct bwd_row_policy {
   static constexpr int VEC = VEC_, T = T_, NG = 1, U = pick_u(VEC_ * T_);
-  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false;
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = false, HAS_FINISH = false;
   struct args { const float* src[1]; int64_t ld[1]; const float* G; int64_t ldg; };
   struct row_state { float xi[T][VEC]; float gi[T][VEC]; };
   __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
@@ -71,7 +71,7 @@ struct bwd_row_policy {
     load_row<VEC, T>(pa.G, pa.ldg, row, col, on, rs.gi);
   }
   __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[1][T][VEC],
-                                     float (&acc)[T][VEC], const bool (&)[T]) {
+                                     float (&acc)[T][VEC], const bool (&)[T], const edge_info&) {
     const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xi, x[0]));
     const float gd = wave_allreduce(dot_lanes<VEC, T>(rs.gi, x[0]));
     const float sg = sigmoidf_fast(z);
@@ -88,7 +88,7 @@ struct bwd_row_policy {
 template <int VEC_, int T_, bool HAS_VAL_>
 struct bwd_col_policy {
   static constexpr int VEC = VEC_, T = T_, NG = 2, U = pick_u(2 * VEC_ * T_);
-  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = true;
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = true, NEEDS_PERM = false, HAS_FINISH = false;
   struct args { const float* src[2]; int64_t ld[2]; };  // src[0] = X, src[1] = dY
   struct row_state { float xj[T][VEC]; };
   __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
@@ -96,7 +96,7 @@ struct bwd_col_policy {
     load_row<VEC, T>(pa.src[0], pa.ld[0], row, col, on, rs.xj);
   }
   __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[2][T][VEC],
-                                     float (&acc)[T][VEC], const bool (&)[T]) {
+                                     float (&acc)[T][VEC], const bool (&)[T], const edge_info&) {
     const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xj, x[0]));
     const float gd = wave_allreduce(dot_lanes<VEC, T>(rs.xj, x[1]));
     const float sg = sigmoidf_fast(z);

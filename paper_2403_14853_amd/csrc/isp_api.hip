@@ -145,6 +145,34 @@ isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const
   return isp_fusedmm_bwd_launch(A, X, ldx, dY, lddy, d, dX, lddx, (hipStream_t)stream);
 }
 
+isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
+                           int64_t ldy, int32_t* arg, void* stream) {
+  if (reduce == ISP_REDUCE_SUM) return isp_spmm(A, X, ldx, d, Y, ldy, stream);
+  if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");
+  if (reduce != ISP_REDUCE_MEAN && reduce != ISP_REDUCE_MIN && reduce != ISP_REDUCE_MAX)
+    return isp_fail(ISP_EUNSUPPORTED, "unknown reduction %d", reduce);
+  isp_status st;
+  if ((st = check_dense(X, ldx, d, A->v.nnz > 0 ? A->v.n_cols : 0, "X")) != ISP_OK) return st;
+  if ((st = check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
+  if (reduce != ISP_REDUCE_MEAN && A->v.n_rows > 0 && !arg) return isp_fail(ISP_EINVAL, "arg is NULL");
+  return isp_spmm_reduce_launch(A, X, ldx, d, reduce, Y, ldy, arg, (hipStream_t)stream);
+}
+
+isp_status isp_spmm_reduce_backward(isp_csr_t* A, const float* dY, int64_t lddy, int32_t d, int reduce,
+                                    const int32_t* arg, float* dX, int64_t lddx, void* stream) {
+  if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");
+  if (A->is_transpose) return isp_fail(ISP_EINVAL, "pass the source handle, not its transpose");
+  if (!A->At) return isp_fail(ISP_EINVAL, "call isp_csr_transpose_cached on the handle first");
+  if (reduce == ISP_REDUCE_SUM) return isp_spmm(A->At, dY, lddy, d, dX, lddx, stream);
+  if (reduce != ISP_REDUCE_MEAN && reduce != ISP_REDUCE_MIN && reduce != ISP_REDUCE_MAX)
+    return isp_fail(ISP_EUNSUPPORTED, "unknown reduction %d", reduce);
+  isp_status st;
+  if ((st = check_dense(dY, lddy, d, A->v.nnz > 0 ? A->v.n_rows : 0, "dY")) != ISP_OK) return st;
+  if ((st = check_dense(dX, lddx, d, A->v.n_cols, "dX")) != ISP_OK) return st;
+  if (reduce != ISP_REDUCE_MEAN && A->v.nnz > 0 && !arg) return isp_fail(ISP_EINVAL, "arg is NULL");
+  return isp_spmm_reduce_bwd_launch(A, dY, lddy, d, reduce, arg, dX, lddx, (hipStream_t)stream);
+}
+
 void isp_csr_destroy(isp_csr_t* A) {
   if (!A) return;
   if (A->is_transpose) return;  // owned by its source handle

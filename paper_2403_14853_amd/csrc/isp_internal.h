@@ -75,3 +75,7 @@ isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int
                               hipStream_t s);
 isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx, const float* G, int64_t ldg,
                                   int32_t d, float* dX, int64_t lddx, hipStream_t s);
+isp_status isp_spmm_reduce_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
+                                  int64_t ldy, int32_t* arg, hipStream_t s);
+isp_status isp_spmm_reduce_bwd_launch(const isp_csr* A, const float* dY, int64_t lddy, int32_t d, int reduce,
+                                      const int32_t* arg, float* dX, int64_t lddx, hipStream_t s);

@@ -50,6 +50,13 @@ __device__ inline float wave_allreduce(float v) {
   return v;
 }
 
+// Per-entry facts handed to a policy's edge function (all wave-uniform).
+struct edge_info {
+  int col;      // column index of the entry (row of the gathered operand)
+  int perm;     // perm[p] when the policy asked for it, else 0
+  int64_t pos;  // position p of the entry in the CSR arrays
+};
+
 // What a work item covers.
 struct item_range {
   int64_t p, p_end;      // nonzero range
@@ -87,8 +94,10 @@ __device__ inline item_range locate_item(const isp_view& A, const int64_t* __res
 // Policy P supplies:
 //   static constexpr int VEC, T, NG, U;  static constexpr bool HAS_VAL, ACCUMULATE;
 //   struct args { const float* src[NG]; int64_t ld[NG]; ... };
+//   static constexpr bool NEEDS_PERM (also read perm[p] per entry), HAS_FINISH (call finish before a row is stored)
 //   struct row_state;  static void row_begin(args, row_state&, int row, cols...)
-//   static void edge(args, row_state&, float a, x[NG][T][VEC], acc[T][VEC], on[T])
+//   static void edge(args, row_state&, float a, x[NG][T][VEC], acc[T][VEC], on[T], edge_info)
+//   static void finish(args, row_state&, acc[T][VEC], out_row, is_seg, row_len, side, col[T], on[T])
 template <class P>
 __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                    const int32_t* __restrict__ indices, const float* __restrict__ values,
@@ -118,6 +127,7 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
   const int64_t p_end = it.p_end;
   const int64_t never = INT64_MAX;
   int64_t row_end, row_end_next;
+  int64_t row_start = p;
   if (it.is_seg) { row_end = p_end; row_end_next = never; }
   else {
     row_end = indptr[row + 1];
@@ -134,6 +144,9 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
   int src_row = it.src_row;
 
   auto write_row = [&]() {
+    if constexpr (P::HAS_FINISH)
+      P::finish(pa, rs, acc, row, it.is_seg, row_end - row_start,
+                it.is_seg ? A.partials + (int64_t)row * ISP_PARTIAL_TILE : nullptr, col, on, k0);
 #pragma unroll
     for (int tt = 0; tt < T; ++tt) {
       if (on[tt]) {
@@ -153,6 +166,7 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
   auto next_row = [&]() {
     ++row;
     ++src_row;
+    row_start = row_end;
     row_end = row_end_next;
     row_end_next = (row + 1 < row_last) ? indptr[row + 2] : never;
   };
@@ -164,11 +178,12 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
   while (p < p_end) {
     const int64_t left = p_end - p;
     const int cnt = left < ISP_WAVE ? (int)left : ISP_WAVE;
-    int c = 0;
+    int c = 0, pm = 0;
     float a = 1.f;
     if (lane < cnt) {
       c = __builtin_nontemporal_load(indices + p + lane);
       if (P::HAS_VAL) a = __builtin_nontemporal_load(values + p + lane);
+      if constexpr (P::NEEDS_PERM) pm = __builtin_nontemporal_load(pa.perm + p + lane);
     }
     for (int t = 0; t < cnt; t += U) {
       float x[U][NG][T][VEC];
@@ -195,7 +210,11 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
       for (int u = 0; u < U; ++u) {
         if (full || t + u < cnt) {
           const float av = P::HAS_VAL ? bcast_f(a, t + u) : 1.f;
-          P::edge(pa, rs, av, x[u], acc, on);
+          edge_info ei;
+          ei.col = bcast_i(c, t + u);
+          ei.perm = P::NEEDS_PERM ? bcast_i(pm, t + u) : 0;
+          ei.pos = p + t + u;
+          P::edge(pa, rs, av, x[u], acc, on, ei);
           if (p + t + u + 1 == row_end) {
             write_row();
             next_row();

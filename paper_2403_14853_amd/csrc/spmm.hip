@@ -12,12 +12,12 @@ template <int VEC_, int T_, bool HAS_VAL_>
 struct spmm_policy {
   static constexpr int VEC = VEC_, T = T_, NG = 1;
   static constexpr int U = (VEC * T >= 4) ? 4 : 8;
-  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false;
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = false, HAS_FINISH = false;
   struct args { const float* src[1]; int64_t ld[1]; };
   struct row_state {};
   __device__ static inline void row_begin(const args&, row_state&, int, const int (&)[T], const bool (&)[T]) {}
   __device__ static inline void edge(const args&, row_state&, float a, const float (&x)[1][T][VEC],
-                                     float (&acc)[T][VEC], const bool (&)[T]) {
+                                     float (&acc)[T][VEC], const bool (&)[T], const edge_info&) {
 #pragma unroll
     for (int tt = 0; tt < T; ++tt)
 #pragma unroll

@@ -1,0 +1,267 @@
+// Sparse-dense product with the other reductions the paper's matmul offers (Section 3.4, 3.5):
+// mean, min, max - and their backward through the cached transpose.  As in the paper, only the
+// sum reduction has the tuned kernels; these run on the generic row-streaming skeleton (one
+// nonzero per wave iteration, any width and alignment).
+//   mean : Y[i] = (sum_p a_p x_j) / len_i
+//   min / max : Y[i,k] = min / max_p a_p x_jk (product and comparison in fp32), arg[i,k] = position p of
+//               the first entry attaining it; empty row -> 0 and -1
+//   backward mean    : dX[j] = sum_{p in column j} (a_p / len_row(p)) dY[row(p)]
+//   backward min/max : dX[j,k] = sum_{p in column j, arg[row(p),k] == p} a_p dY[row(p),k]
+// Both backward forms are row passes over the cached transpose (whose perm gives p), so no
+// floating-point atomics are needed and results are deterministic.
+#include "row_stream.h"
+
+namespace {
+using namespace isp_dev;
+
+constexpr int R_MEAN = 1, R_MIN = 2, R_MAX = 3;
+constexpr int ARG_OFF = ISP_PARTIAL_TILE / 2;  // hub partial rows: values in [0,128), arg bits in [128,256)
+
+// ---- forward -----------------------------------------------------------------------------------
+template <int VEC_, int MODE, bool HAS_VAL_>
+struct reduce_fwd_policy {
+  static constexpr int VEC = VEC_, T = 1, NG = 1, U = 8;
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = false, HAS_FINISH = true;
+  struct args { const float* src[1]; int64_t ld[1]; int32_t* arg; int d; const int32_t* perm; };
+  struct row_state { int where[VEC]; };
+  __device__ static inline void row_begin(const args&, row_state& rs, int, const int (&)[1], const bool (&)[1]) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) rs.where[v] = -1;
+  }
+  __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[1][1][VEC],
+                                     float (&acc)[1][VEC], const bool (&)[1], const edge_info& ei) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      if (MODE == R_MEAN) {
+        acc[0][v] = fmaf(a, x[0][0][v], acc[0][v]);
+      } else {
+        const float t = __fmul_rn(a, x[0][0][v]);  // one rounded fp32 multiply, never fused
+        const bool take = rs.where[v] < 0 || (MODE == R_MIN ? t < acc[0][v] : t > acc[0][v]);
+        acc[0][v] = take ? t : acc[0][v];
+        rs.where[v] = take ? (int)ei.pos : rs.where[v];
+      }
+    }
+  }
+  __device__ static inline void finish(const args& pa, row_state& rs, float (&acc)[1][VEC], int out_row, bool is_seg,
+                                       int64_t row_len, float* side, const int (&col)[1], const bool (&on)[1],
+                                       int k0) {
+    if (MODE == R_MEAN) {
+      if (!is_seg) {  // segments hold plain partial sums; the fix-up divides
+        const float inv = row_len > 0 ? 1.f / (float)row_len : 0.f;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[0][v] *= inv;
+      }
+    } else if (on[0]) {
+      // an empty row never saw row_begin: its position is -1 by definition
+      const bool empty = !is_seg && row_len == 0;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) {
+        const int w = empty ? -1 : rs.where[v];
+        if (is_seg) side[ARG_OFF + col[0] - k0 + v] = __int_as_float(w);
+        else pa.arg[(int64_t)out_row * pa.d + col[0] + v] = w;
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) rs.where[v] = -1;
+  }
+};
+
+template <int VEC, int MODE, bool HAS_VAL>
+__global__ void __launch_bounds__(ISP_WG) k_reduce_fwd(isp_view A, const int64_t* __restrict__ indptr,
+                                                       const int32_t* __restrict__ indices,
+                                                       const float* __restrict__ values, const float* __restrict__ X,
+                                                       int64_t ldx, int d, int k0, float* __restrict__ Y, int64_t ldy,
+                                                       int32_t* __restrict__ arg) {
+  using P = reduce_fwd_policy<VEC, MODE, HAS_VAL>;
+  typename P::args pa;
+  pa.src[0] = X; pa.ld[0] = ldx; pa.arg = arg; pa.d = d; pa.perm = nullptr;
+  stream_item<P>(A, indptr, indices, values, pa, d, k0, Y, ldy);
+}
+
+// One wave per hub row: combine the segments' partial results in segment order.
+template <int VEC, int MODE>
+__global__ void __launch_bounds__(ISP_WG) k_reduce_fixup(isp_view A, int d, int k0, float* __restrict__ Y, int64_t ldy,
+                                                         int32_t* __restrict__ arg) {
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int h = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6)));
+  if (h >= A.n_hub) return;
+  const int s0 = A.hub_seg_ptr[h], s1 = A.hub_seg_ptr[h + 1];
+  const int row = A.hub_rows[h];
+  const int rel = lane * VEC;
+  if (k0 + rel >= d) return;
+  float best[VEC];
+  int where[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) { best[v] = 0.f; where[v] = -1; }
+  for (int s = s0; s < s1; ++s) {
+    const float* pr = A.partials + (int64_t)s * ISP_PARTIAL_TILE + rel;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      const float t = pr[v];
+      if (MODE == R_MEAN) {
+        best[v] += t;
+      } else {
+        const int w = __float_as_int(pr[ARG_OFF + v]);
+        const bool take = where[v] < 0 || (MODE == R_MIN ? t < best[v] : t > best[v]);
+        best[v] = take ? t : best[v];
+        where[v] = take ? w : where[v];
+      }
+    }
+  }
+  if (MODE == R_MEAN) {
+    const int64_t len = A.indptr[row + 1] - A.indptr[row];
+    const float inv = len > 0 ? 1.f / (float)len : 0.f;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) best[v] *= inv;
+  }
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) {
+    Y[(int64_t)row * ldy + k0 + rel + v] = best[v];
+    if (MODE != R_MEAN) arg[(int64_t)row * d + k0 + rel + v] = where[v];
+  }
+}
+
+// ---- backward (row passes over the cached transpose) ---------------------------------------------
+// mean: entry (j <- i) contributes (a / len_A(i)) dY[i]; len_A from the source matrix's row offsets.
+template <int VEC_, bool HAS_VAL_>
+struct mean_bwd_policy {
+  static constexpr int VEC = VEC_, T = 1, NG = 1, U = 8;
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = false, HAS_FINISH = false;
+  struct args { const float* src[1]; int64_t ld[1]; const int64_t* src_indptr; const int32_t* perm; };
+  struct row_state {};
+  __device__ static inline void row_begin(const args&, row_state&, int, const int (&)[1], const bool (&)[1]) {}
+  __device__ static inline void edge(const args& pa, row_state&, float a, const float (&x)[1][1][VEC],
+                                     float (&acc)[1][VEC], const bool (&)[1], const edge_info& ei) {
+    const int64_t len = pa.src_indptr[ei.col + 1] - pa.src_indptr[ei.col];
+    const float w = a / (float)len;  // len >= 1: the entry itself lies in that row
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[0][v] = fmaf(w, x[0][0][v], acc[0][v]);
+  }
+};
+
+// min / max: gathers dY[i] and arg[i] (as bit patterns); the entry contributes where arg equals its
+// position p = perm[q] in the source matrix.
+template <int VEC_, bool HAS_VAL_>
+struct select_bwd_policy {
+  static constexpr int VEC = VEC_, T = 1, NG = 2, U = 4;
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = true, HAS_FINISH = false;
+  struct args { const float* src[2]; int64_t ld[2]; const int32_t* perm; };
+  struct row_state {};
+  __device__ static inline void row_begin(const args&, row_state&, int, const int (&)[1], const bool (&)[1]) {}
+  __device__ static inline void edge(const args&, row_state&, float a, const float (&x)[2][1][VEC],
+                                     float (&acc)[1][VEC], const bool (&)[1], const edge_info& ei) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+      const bool mine = __float_as_int(x[1][0][v]) == ei.perm;
+      acc[0][v] = mine ? fmaf(a, x[0][0][v], acc[0][v]) : acc[0][v];
+    }
+  }
+};
+
+template <class P>
+__global__ void __launch_bounds__(ISP_WG) k_reduce_bwd(isp_view At, const int64_t* __restrict__ indptr,
+                                                       const int32_t* __restrict__ indices,
+                                                       const float* __restrict__ values, typename P::args pa, int d,
+                                                       int k0, float* __restrict__ dX, int64_t lddx) {
+  stream_item<P>(At, indptr, indices, values, pa, d, k0, dX, lddx);
+}
+
+template <int VEC>
+__global__ void __launch_bounds__(ISP_WG) k_sum_fixup(isp_view A, int d, int k0, float* __restrict__ Y, int64_t ldy) {
+  hub_fixup<VEC, 1, false>(A, d, k0, Y, ldy);
+}
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+unsigned item_grid(const isp_view& v) { return (unsigned)((v.n_blocks + v.n_seg + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG); }
+unsigned hub_grid(const isp_view& v) { return (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG); }
+
+template <int VEC, int MODE>
+isp_status fwd_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int k0, float* Y, int64_t ldy, int32_t* arg,
+                    hipStream_t s) {
+  const isp_view& v = A->v;
+  if (v.n_blocks + v.n_seg > 0) {
+    if (v.values) k_reduce_fwd<VEC, MODE, true><<<item_grid(v), ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy, arg);
+    else k_reduce_fwd<VEC, MODE, false><<<item_grid(v), ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k0, Y, ldy, arg);
+    ISP_LAUNCH_CHECK();
+  }
+  if (v.n_hub > 0) {
+    k_reduce_fixup<VEC, MODE><<<hub_grid(v), ISP_WG, 0, s>>>(v, d, k0, Y, ldy, arg);
+    ISP_LAUNCH_CHECK();
+  }
+  return ISP_OK;
+}
+
+template <int MODE>
+isp_status fwd_all(const isp_csr* A, const float* X, int64_t ldx, int d, float* Y, int64_t ldy, int32_t* arg,
+                   hipStream_t s) {
+  // min / max keep (value, position) pairs in the hub partial rows, so their column tiles stop at 128
+  const bool v2 = d % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8) && d > ISP_WAVE;
+  isp_status st = ISP_OK;
+  for (int k0 = 0; k0 < d && st == ISP_OK; k0 += (v2 ? 2 : 1) * ISP_WAVE)
+    st = v2 ? fwd_tile<2, MODE>(A, X, ldx, d, k0, Y, ldy, arg, s) : fwd_tile<1, MODE>(A, X, ldx, d, k0, Y, ldy, arg, s);
+  return st;
+}
+
+template <class P, int VEC>
+isp_status bwd_tile(const isp_csr* At, const typename P::args& pa, int d, int k0, float* dX, int64_t lddx,
+                    hipStream_t s) {
+  const isp_view& v = At->v;
+  if (v.n_blocks + v.n_seg > 0) {
+    k_reduce_bwd<P><<<item_grid(v), ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, k0, dX, lddx);
+    ISP_LAUNCH_CHECK();
+  }
+  if (v.n_hub > 0) {
+    k_sum_fixup<VEC><<<hub_grid(v), ISP_WG, 0, s>>>(v, d, k0, dX, lddx);
+    ISP_LAUNCH_CHECK();
+  }
+  return ISP_OK;
+}
+
+template <int VEC, bool HV>
+isp_status mean_bwd(const isp_csr* A, const float* dY, int64_t lddy, int d, int k0, float* dX, int64_t lddx,
+                    hipStream_t s) {
+  using P = mean_bwd_policy<VEC, HV>;
+  typename P::args pa{{dY}, {lddy}, A->v.indptr, nullptr};
+  return bwd_tile<P, VEC>(A->At, pa, d, k0, dX, lddx, s);
+}
+
+template <int VEC, bool HV>
+isp_status select_bwd(const isp_csr* A, const float* dY, int64_t lddy, const int32_t* arg, int d, int k0, float* dX,
+                      int64_t lddx, hipStream_t s) {
+  using P = select_bwd_policy<VEC, HV>;
+  typename P::args pa{{dY, reinterpret_cast<const float*>(arg)}, {lddy, (int64_t)d}, A->At->perm};
+  return bwd_tile<P, VEC>(A->At, pa, d, k0, dX, lddx, s);
+}
+
+}  // namespace
+
+isp_status isp_spmm_reduce_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
+                                  int64_t ldy, int32_t* arg, hipStream_t s) {
+  if (reduce == R_MEAN) return fwd_all<R_MEAN>(A, X, ldx, d, Y, ldy, arg, s);
+  if (reduce == R_MIN) return fwd_all<R_MIN>(A, X, ldx, d, Y, ldy, arg, s);
+  return fwd_all<R_MAX>(A, X, ldx, d, Y, ldy, arg, s);
+}
+
+isp_status isp_spmm_reduce_bwd_launch(const isp_csr* A, const float* dY, int64_t lddy, int32_t d, int reduce,
+                                      const int32_t* arg, float* dX, int64_t lddx, hipStream_t s) {
+  const isp_csr* At = A->At;
+  const bool hv = At->v.values != nullptr;
+  const bool v2 = d % 2 == 0 && lddy % 2 == 0 && lddx % 2 == 0 && aligned(dY, 8) && aligned(dX, 8) &&
+                  aligned(arg, 8) && d > ISP_WAVE;
+  isp_status st = ISP_OK;
+  for (int k0 = 0; k0 < d && st == ISP_OK; k0 += (v2 ? 2 : 1) * ISP_WAVE) {
+    if (reduce == R_MEAN) {
+      if (v2 && hv) st = mean_bwd<2, true>(A, dY, lddy, d, k0, dX, lddx, s);
+      else if (v2) st = mean_bwd<2, false>(A, dY, lddy, d, k0, dX, lddx, s);
+      else if (hv) st = mean_bwd<1, true>(A, dY, lddy, d, k0, dX, lddx, s);
+      else st = mean_bwd<1, false>(A, dY, lddy, d, k0, dX, lddx, s);
+    } else {
+      if (v2 && hv) st = select_bwd<2, true>(A, dY, lddy, arg, d, k0, dX, lddx, s);
+      else if (v2) st = select_bwd<2, false>(A, dY, lddy, arg, d, k0, dX, lddx, s);
+      else if (hv) st = select_bwd<1, true>(A, dY, lddy, arg, d, k0, dX, lddx, s);
+      else st = select_bwd<1, false>(A, dY, lddy, arg, d, k0, dX, lddx, s);
+    }
+  }
+  return st;
+}
