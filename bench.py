@@ -37,6 +37,9 @@ def main():
                          "the cached transpose and with the transpose rebuilt every epoch")
     ap.add_argument("--sweep-d", action="store_true",
                     help="instead of the benchmark line: SpMM forward time over feature widths 8..1024")
+    ap.add_argument("--gcn-step", action="store_true",
+                    help="instead of the benchmark line: a 2-layer GCN training step (sparse ops through the "
+                         "autograd wrappers, dense GEMMs through torch) with hidden width d")
     ap.add_argument("--reductions", action="store_true",
                     help="instead of the benchmark line: forward and backward time of the mean / min / max reductions")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -86,6 +89,9 @@ def main():
         return
     if args.reductions:
         print(json.dumps(reductions(isp, w, A, X, dY)))
+        return
+    if args.gcn_step:
+        print(json.dumps(gcn_step(w, indptr, indices, values, X)))
         return
 
     ops = list(w.ops)
@@ -235,6 +241,33 @@ def sweep_d(isp, w, A):
                     "gather_GBps": round(w.nnz * (8.0 + 4.0 * d) / ms / 1e6, 1)})
         del X, Y
     return {"what": "SpMM forward vs feature width", "workload": w.name, "nnz": w.nnz, "sweep": out}
+
+
+def gcn_step(w, indptr, indices, values, X):
+    """End-to-end 2-layer GCN step: out = A relu(A (X W1)) W2, MSE-style loss, backward, SGD update."""
+    import torch
+    from paper_2403_14853_amd import autograd as ag
+    g = ag.SparseGraph(indptr, indices, values)
+    d = w.d
+    torch.manual_seed(0)
+    W1 = (torch.randn(d, d, device="cuda") / d ** 0.5).requires_grad_(True)
+    W2 = (torch.randn(d, d, device="cuda") / d ** 0.5).requires_grad_(True)
+
+    def step():
+        out = ag.spmm(g, torch.relu(ag.spmm(g, X @ W1)) @ W2)
+        loss = out.square().mean()
+        loss.backward()
+        with torch.no_grad():
+            for W in (W1, W2):
+                W -= 1e-3 * W.grad
+                W.grad = None
+
+    step()
+    step()
+    ms = _time_ms(step, 10)
+    return {"what": "2-layer GCN training step (4 SpMM + 6 GEMM + elementwise)", "workload": w.name, "hidden": d,
+            "ms_per_step": round(ms, 3), "sparse_flops": 4 * 2.0 * w.nnz * d,
+            "sparse_gflops_if_all_time_were_sparse": round(4 * 2.0 * w.nnz * d / ms / 1e6, 1)}
 
 
 def reductions(isp, w, A, X, dY):

@@ -1,0 +1,82 @@
+"""Thin ``torch.autograd.Function`` wrappers over the C ABI, so the sparse operations can sit
+inside an ordinary PyTorch training step (the role of the paper's C++ wrapper that connects
+forward and backward propagation to the kernels, Section 3.1).  Everything numerical still runs
+in the library's HIP kernels; these classes only route tensors and remember what backward needs.
+
+``SparseGraph`` owns the handle; its transpose is built on the first backward and cached in the
+handle for all later epochs (Section 3.3).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as _b
+
+
+class SparseGraph:
+    """A CSR matrix on the GPU plus its library handle.  ``values`` may be a leaf tensor that
+    requires grad; its gradient is the SDDMM of (dY, X)."""
+
+    def __init__(self, indptr, indices, values=None, n_cols=None):
+        self.indptr, self.indices, self.values = indptr, indices, values
+        self.handle = _b.csr_build(indptr, indices, None if values is None else values.detach(), n_cols=n_cols)
+        self.n_rows, self.n_cols, self.nnz = self.handle.n_rows, self.handle.n_cols, self.handle.nnz
+
+    def transpose(self):
+        return _b.csr_transpose_cached(self.handle)[0]
+
+
+class _SpMM(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, graph, values, X):
+        X = X.contiguous()
+        Y = torch.empty(graph.n_rows, X.shape[1], device=X.device, dtype=torch.float32)
+        _b.spmm(graph.handle, X, Y)
+        ctx.graph = graph
+        ctx.save_for_backward(X)
+        ctx.need_dA = values is not None and values.requires_grad
+        return Y
+
+    @staticmethod
+    def backward(ctx, dY):
+        (X,) = ctx.saved_tensors
+        graph = ctx.graph
+        dY = dY.contiguous()
+        dX = dA = None
+        if ctx.needs_input_grad[2]:
+            dX = torch.empty(graph.n_cols, dY.shape[1], device=dY.device, dtype=torch.float32)
+            _b.spmm(graph.transpose(), dY, dX)  # cached after the first call
+        if ctx.need_dA:
+            dA = torch.empty(graph.nnz, device=dY.device, dtype=torch.float32)
+            _b.sddmm(graph.handle, dY, X, dA)
+        return None, dA, dX
+
+
+def spmm(graph: SparseGraph, X):
+    """Differentiable Y = A X (with respect to X and, if ``graph.values`` requires grad, to the values)."""
+    return _SpMM.apply(graph, graph.values, X)
+
+
+class _FusedMM(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, graph, X):
+        X = X.contiguous()
+        Y = torch.empty_like(X)
+        _b.fusedmm(graph.handle, X, Y)
+        ctx.graph = graph
+        ctx.save_for_backward(X)
+        return Y
+
+    @staticmethod
+    def backward(ctx, dY):
+        (X,) = ctx.saved_tensors
+        graph = ctx.graph
+        graph.transpose()
+        dX = torch.empty_like(X)
+        _b.fusedmm_backward(graph.handle, X, dY.contiguous(), dX)
+        return None, dX
+
+
+def fusedmm(graph: SparseGraph, X):
+    """Differentiable sigmoid FusedMM: y_i = sum_j a_ij sigmoid(<x_i, x_j>) x_j."""
+    return _FusedMM.apply(graph, X)
