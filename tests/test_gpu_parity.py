@@ -199,3 +199,51 @@ def test_malformed_csr_is_rejected():
         isp.fusedmm(A, torch.ones(w.n, 260, device="cuda"), torch.empty(w.n, 260, device="cuda"))
     assert e.value.status_name == "ISP_EUNSUPPORTED"
     A.destroy()
+
+
+def test_nonfinite_rows_do_not_leak_into_other_rows(small_partition):
+    """Lanes without a live entry read row 0 of the dense operand and discard it; a NaN / Inf there
+    must only reach the rows that really reference column 0."""
+    w = graphgen.make_config(1, shrink=128)
+    d = 64
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((w.n, d)).astype(np.float32)
+    X[0, : d // 2] = np.nan
+    X[0, d // 2:] = np.inf
+    A = build(w.indptr, w.indices, w.values)
+    Y = torch.empty(w.n, d, device="cuda")
+    isp.spmm(A, dev(X), Y)
+    touches0 = np.array([0 in w.indices[w.indptr[i]:w.indptr[i + 1]] for i in range(w.n)])
+    Yh = Y.cpu().numpy()
+    assert np.all(np.isfinite(Yh[~touches0])), "a non-finite value leaked into a row that does not use column 0"
+    Xc = X.copy()
+    Xc[0] = 0.0
+    ref, mag = oracle.spmm(w.indptr, w.indices, w.values, Xc)
+    assert_close(Y[torch.from_numpy(~touches0).cuda()], ref[~touches0], mag[~touches0], "rows not using column 0")
+    out = torch.empty(w.nnz, device="cuda")
+    G = dev(rng.standard_normal((w.n, d)).astype(np.float32))
+    isp.sddmm(A, G, dev(X), out)
+    uses0 = w.indices == 0
+    assert np.all(np.isfinite(out.cpu().numpy()[~uses0]))
+    A.destroy()
+
+
+def test_two_handles_on_two_streams():
+    """Different handles have separate scratch, so they may run concurrently on different streams."""
+    w = graphgen.make_config(1, shrink=8)
+    A1 = build(w.indptr, w.indices, w.values)
+    A2 = build(w.indptr, w.indices, w.values)
+    X = dev(w.X)
+    Y1, Y2 = torch.empty_like(X), torch.empty_like(X)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        isp.spmm(A1, X, Y1, stream=s1)
+        isp.spmm(A2, X, Y2, stream=s2)
+    s1.synchronize()
+    s2.synchronize()
+    assert torch.equal(Y1, Y2)
+    ref, mag = oracle.spmm(w.indptr, w.indices, w.values, w.X)
+    assert_close(Y1, ref, mag, "spmm on a side stream")
+    A1.destroy()
+    A2.destroy()
