@@ -68,7 +68,7 @@ isp_status launch_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int
 // LPG lanes x float4 cover one slice of 4 * LPG feature columns; G = 64 / LPG nonzeros per gather
 // instruction.  Slice s of tile k_base covers columns [k_base + s * 4 * LPG, +4 * LPG).
 template <int LPG, bool HAS_VAL>
-__global__ void __launch_bounds__(ISP_WG) k_spmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
+__global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 4))) k_spmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                          const int32_t* __restrict__ indices,
                                                          const float* __restrict__ values,
                                                          const float* __restrict__ X, int64_t ldx, int d, int k_base,
