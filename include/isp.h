@@ -53,8 +53,10 @@ typedef enum {
 #define ISP_TRUSTED 1u /* skip the structural validation pass (the caller vouches for the CSR) */
 /* flags of isp_sddmm */
 #define ISP_SCALE_BY_A 1u /* multiply each dot product by the entry's value */
-/* op of isp_fusedmm / isp_fusedmm_backward */
-#define ISP_OP_SIGMOID 0
+/* op of isp_fusedmm / isp_fusedmm_backward: the edge function s = f(z) applied to z = <x_i, x_j> */
+#define ISP_OP_SIGMOID 0 /* f(z) = 1 / (1 + exp(-z)) */
+#define ISP_OP_DOT 1     /* f(z) = z */
+#define ISP_OP_ONE 2     /* f(z) = 1: plain aggregation through the fused path */
 
 /* Summary of a handle's row classes and work partition (all counts are rows unless named). */
 typedef struct {
@@ -131,16 +133,17 @@ isp_status isp_sddmm(const isp_csr_t* A, const float* U, int64_t ldu, const floa
                      int32_t d, unsigned flags, float* out, void* stream);
 
 /*
- * FusedMM forward (Section 1(a)), op = ISP_OP_SIGMOID, A square:
- *   s_p = 1 / (1 + exp(-<X[i], X[j]>)), j = indices[p];  Y[i] = sum_p values[p] * s_p * X[j].
- * The per-edge scores are never written to memory.  d <= 1024, else ISP_EUNSUPPORTED.
+ * FusedMM forward (Section 1(a): SDDMM, an edge function and SpMM as one operation), A square:
+ *   s_p = f(<X[i], X[j]>), j = indices[p];  Y[i] = sum_p values[p] * s_p * X[j],
+ * f chosen by op (ISP_OP_SIGMOID, ISP_OP_DOT, ISP_OP_ONE).  The per-edge scores are never written to
+ * memory.  d <= 256, else ISP_EUNSUPPORTED.
  */
 isp_status isp_fusedmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,
                        int64_t ldy, void* stream);
 
 /*
  * FusedMM backward: dX for upstream gradient dY of the forward above.  With g = dY and
- * dz_p = values[p] <g_i, x_j> s_p (1 - s_p):
+ * dz_p = values[p] <g_i, x_j> f'(z_p)   (s_p (1 - s_p) for the sigmoid):
  *   dX[i] = sum_{p in row i} dz_p x_j  +  sum_{p: indices[p] = i} (values[p] s_p g_r + dz_p x_r),
  * r = row of p.  The second sum runs over row i of the cached transpose, so
  * isp_csr_transpose_cached(A) must have succeeded before; otherwise ISP_EINVAL.

@@ -45,9 +45,9 @@ def _load():
     lib.isp_oracle_spmm_scatter.restype = None
     lib.isp_oracle_sddmm.argtypes = [i64, vp, vp, vp, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
     lib.isp_oracle_sddmm.restype = None
-    lib.isp_oracle_fusedmm.argtypes = [i64, vp, vp, vp, vp, i64, i32, vp, vp]
+    lib.isp_oracle_fusedmm.argtypes = [i64, vp, vp, vp, vp, i64, i32, ctypes.c_int, vp, vp]
     lib.isp_oracle_fusedmm.restype = None
-    lib.isp_oracle_fusedmm_backward.argtypes = [i64, vp, vp, vp, vp, i64, vp, i64, i32, vp, vp]
+    lib.isp_oracle_fusedmm_backward.argtypes = [i64, vp, vp, vp, vp, i64, vp, i64, i32, ctypes.c_int, vp, vp]
     lib.isp_oracle_fusedmm_backward.restype = None
     lib.isp_oracle_spmm_reduce.argtypes = [i64, vp, vp, vp, vp, i64, i32, ctypes.c_int, vp, vp, vp]
     lib.isp_oracle_spmm_reduce.restype = None
@@ -141,8 +141,11 @@ def sddmm(indptr, indices, values, U, V, scale_by_a=False, want_mag=True):
     return out, mag
 
 
-def fusedmm(indptr, indices, values, X, want_mag=True):
-    """Sigmoid FusedMM forward: y_i = sum_j a_ij sigmoid(<x_i,x_j>) x_j."""
+EDGE_OPS = {"sigmoid": 0, "dot": 1, "one": 2}
+
+
+def fusedmm(indptr, indices, values, X, want_mag=True, op="sigmoid"):
+    """FusedMM forward: y_i = sum_j a_ij f(<x_i,x_j>) x_j, f = sigmoid | dot (identity) | one."""
     indptr, indices, values = _csr(indptr, indices, values)
     X = _dense(X)
     n, d = indptr.shape[0] - 1, X.shape[1]
@@ -151,12 +154,13 @@ def fusedmm(indptr, indices, values, X, want_mag=True):
         assert indices.max() < X.shape[0] and indices.min() >= 0
     Y = np.empty((n, d), dtype=np.float64)
     mag = np.empty((n, d), dtype=np.float64) if want_mag else None
-    _load().isp_oracle_fusedmm(n, _ptr(indptr), _ptr(indices), _ptr(values), _ptr(X), d, d, _ptr(Y), _ptr(mag))
+    _load().isp_oracle_fusedmm(n, _ptr(indptr), _ptr(indices), _ptr(values), _ptr(X), d, d, EDGE_OPS[op], _ptr(Y),
+                               _ptr(mag))
     return Y, mag
 
 
-def fusedmm_backward(indptr, indices, values, X, dY, want_mag=True):
-    """dX of the sigmoid FusedMM for upstream gradient dY."""
+def fusedmm_backward(indptr, indices, values, X, dY, want_mag=True, op="sigmoid"):
+    """dX of FusedMM (edge function op) for upstream gradient dY."""
     indptr, indices, values = _csr(indptr, indices, values)
     X, dY = _dense(X), _dense(dY)
     n, d = indptr.shape[0] - 1, X.shape[1]
@@ -166,7 +170,7 @@ def fusedmm_backward(indptr, indices, values, X, dY, want_mag=True):
     dX = np.empty((n, d), dtype=np.float64)
     mag = np.empty((n, d), dtype=np.float64) if want_mag else None
     _load().isp_oracle_fusedmm_backward(n, _ptr(indptr), _ptr(indices), _ptr(values), _ptr(X), d, _ptr(dY), d, d,
-                                        _ptr(dX), _ptr(mag))
+                                        EDGE_OPS[op], _ptr(dX), _ptr(mag))
     return dX, mag
 
 

@@ -18,9 +18,10 @@
  *     counting sort by column, which makes it unique.
  *   - SDDMM (sampled dense-dense product, one dot product per stored entry): Section 1.
  *   - FusedMM (SDDMM -> edge function -> SpMM without materialising the edge matrix):
- *     Section 1(a).  The paper gives no formula; the instance is the sigmoid one,
- *     s_ij = sigmoid(<x_i, x_j>), y_i = sum_j a_ij s_ij x_j.  Its backward is derived by the
- *     chain rule (the paper is silent) and pinned by finite differences in the tests.
+ *     Section 1(a).  The paper gives no formula; the form taken is s_ij = f(<x_i, x_j>),
+ *     y_i = sum_j a_ij s_ij x_j with f the sigmoid (the benchmark's instance), the identity or
+ *     the constant one.  Its backward is derived by the chain rule (the paper is silent) and
+ *     pinned by finite differences in the tests.
  *
  * Parity pins (tests/test_oracle_*.py): dense brute force, scipy, closed forms, adjoint
  * identities, finite differences.  No function here is unpinned.
@@ -150,14 +151,23 @@ void isp_oracle_sddmm(int64_t n_rows, const int64_t* indptr, const int32_t* indi
   }
 }
 
-static double sigmoid(double z) { return 1.0 / (1.0 + exp(-z)); }
+/* Edge functions of FusedMM: the score s = f(z) of an entry from z = <x_i, x_j>, its derivative, and
+ * bounds L1 >= |f'|, L2 >= |f''| used only for the error-scale output.
+ *   op 0: sigmoid, f = 1/(1+exp(-z));   op 1: identity, f = z;   op 2: constant one (plain aggregation). */
+static double edge_f(int op, double z) { return op == 0 ? 1.0 / (1.0 + exp(-z)) : (op == 1 ? z : 1.0); }
+static double edge_df(int op, double z) {
+  if (op == 0) { const double s = 1.0 / (1.0 + exp(-z)); return s * (1.0 - s); }
+  return op == 1 ? 1.0 : 0.0;
+}
+static double edge_l1(int op) { return op == 0 ? 0.25 : (op == 1 ? 1.0 : 0.0); }
+static double edge_l2(int op) { return op == 0 ? 0.1 : 0.0; }
 
-/* FusedMM forward, sigmoid instance (square A):
- *   z_p = <x_i, x_j>, s_p = 1/(1+exp(-z_p)), Y[i,:] = sum_{p in row i} a_p s_p x_j, j = col_p.
- * mag[i,k] = sum_p |a_p| (s_p + 0.25 * sum_k' |x_ik' x_jk'|) |x_jk|: first-order error scale of the
- * fp32 evaluation (the derivative of the sigmoid is at most 1/4). */
+/* FusedMM forward (square A):
+ *   z_p = <x_i, x_j>, s_p = f(z_p), Y[i,:] = sum_{p in row i} a_p s_p x_j, j = col_p.
+ * mag[i,k] = sum_p |a_p| (|s_p| + L1 * sum_k' |x_ik' x_jk'|) |x_jk|: first-order error scale of the
+ * fp32 evaluation (L1 bounds the edge function's derivative: 1/4 for the sigmoid). */
 void isp_oracle_fusedmm(int64_t n_rows, const int64_t* indptr, const int32_t* indices, const float* values,
-                        const float* X, int64_t ldx, int32_t d, double* Y, double* mag) {
+                        const float* X, int64_t ldx, int32_t d, int op, double* Y, double* mag) {
 #pragma omp parallel for schedule(dynamic, 256)
   for (int64_t i = 0; i < n_rows; ++i) {
     const float* xi = X + i * ldx;
@@ -173,27 +183,26 @@ void isp_oracle_fusedmm(int64_t n_rows, const int64_t* indptr, const int32_t* in
         z += t;
         za += fabs(t);
       }
-      const double s = sigmoid(z);
+      const double s = edge_f(op, z);
       const double a = values ? (double)values[p] : 1.0;
       for (int32_t k = 0; k < d; ++k) {
         y[k] += a * s * (double)xj[k];
-        if (m) m[k] += fabs(a) * (s + 0.25 * za) * fabs((double)xj[k]);
+        if (m) m[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)xj[k]);
       }
     }
   }
 }
 
 /* FusedMM backward, chain rule on the forward above.  With g = dY, for entry p = (i, j):
- *   ds_p = a_p <g_i, x_j>,  dz_p = ds_p s_p (1 - s_p),
+ *   ds_p = a_p <g_i, x_j>,  dz_p = ds_p f'(z_p),
  *   dX[i,:] += dz_p x_j                      (x_i enters only through z_p)
  *   dX[j,:] += a_p s_p g_i + dz_p x_i        (x_j enters directly and through z_p)
  * Scatter form, sequential.  dX is n x d, zeroed here.
  * mag[r,k] accumulates first-order error scales of the same terms: with za = sum_k |x_ik x_jk| and
- * ga = sum_k |g_ik x_jk|, |dz| is replaced by |a_p| ga (0.25 + 0.1 za) (s(1-s) <= 1/4 and its
- * derivative <= 0.1 carries the error of z), and s by s + 0.25 za. */
+ * ga = sum_k |g_ik x_jk|, |dz| is replaced by |a_p| ga (|f'| + L2 za) and s by |s| + L1 za. */
 void isp_oracle_fusedmm_backward(int64_t n, const int64_t* indptr, const int32_t* indices, const float* values,
-                                 const float* X, int64_t ldx, const float* dY, int64_t ldg, int32_t d, double* dX,
-                                 double* mag) {
+                                 const float* X, int64_t ldx, const float* dY, int64_t ldg, int32_t d, int op,
+                                 double* dX, double* mag) {
   memset(dX, 0, (size_t)n * (size_t)d * sizeof(double));
   if (mag) memset(mag, 0, (size_t)n * (size_t)d * sizeof(double));
   for (int64_t i = 0; i < n; ++i) {
@@ -211,10 +220,10 @@ void isp_oracle_fusedmm_backward(int64_t n, const int64_t* indptr, const int32_t
         gd += t;
         gda += fabs(t);
       }
-      const double s = sigmoid(z);
+      const double s = edge_f(op, z);
       const double a = values ? (double)values[p] : 1.0;
-      const double dz = a * gd * s * (1.0 - s);
-      const double dzm = fabs(a) * gda * (0.25 + 0.1 * za);
+      const double dz = a * gd * edge_df(op, z);
+      const double dzm = fabs(a) * gda * (fabs(edge_df(op, z)) + edge_l2(op) * za);
       double* oi = dX + i * (int64_t)d;
       double* oj = dX + j * (int64_t)d;
       for (int32_t k = 0; k < d; ++k) {
@@ -226,7 +235,7 @@ void isp_oracle_fusedmm_backward(int64_t n, const int64_t* indptr, const int32_t
         double* mj = mag + j * (int64_t)d;
         for (int32_t k = 0; k < d; ++k) {
           mi[k] += dzm * fabs((double)xj[k]);
-          mj[k] += fabs(a) * (s + 0.25 * za) * fabs((double)gi[k]) + dzm * fabs((double)xi[k]);
+          mj[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)gi[k]) + dzm * fabs((double)xi[k]);
         }
       }
     }

@@ -20,7 +20,8 @@ EXPORTED_SYMBOLS = [
 
 ISP_TRUSTED = 1
 ISP_SCALE_BY_A = 1
-ISP_OP_SIGMOID = 0
+ISP_OP_SIGMOID, ISP_OP_DOT, ISP_OP_ONE = 0, 1, 2
+EDGE_OPS = {"sigmoid": 0, "dot": 1, "one": 2}
 _STATUS = {0: "ISP_OK", 1: "ISP_EINVAL", 2: "ISP_EBADCSR", 3: "ISP_ENOMEM", 4: "ISP_EHIP", 5: "ISP_EUNSUPPORTED"}
 
 
@@ -233,7 +234,8 @@ def sddmm(A: CSR, U, V, out, *, scale_by_a=False, stream=None):
 
 
 def fusedmm(A: CSR, X, Y, *, op=ISP_OP_SIGMOID, stream=None):
-    """isp_fusedmm forward."""
+    """isp_fusedmm forward; op is ISP_OP_* or one of 'sigmoid', 'dot', 'one'."""
+    op = EDGE_OPS.get(op, op)
     d = X.shape[1]
     assert X.shape[0] == A.n_rows and Y.shape == X.shape
     _check(load_library().isp_fusedmm(A._h, _dptr(X), _ld(X), d, op, _dptr(Y), _ld(Y), _stream(stream)))
@@ -242,6 +244,7 @@ def fusedmm(A: CSR, X, Y, *, op=ISP_OP_SIGMOID, stream=None):
 
 def fusedmm_backward(A: CSR, X, dY, dX, *, op=ISP_OP_SIGMOID, stream=None):
     """isp_fusedmm_backward (needs csr_transpose_cached(A) first)."""
+    op = EDGE_OPS.get(op, op)
     d = X.shape[1]
     assert dY.shape == X.shape and dX.shape == X.shape
     _check(load_library().isp_fusedmm_backward(A._h, _dptr(X), _ld(X), _dptr(dY), _ld(dY), d, op, _dptr(dX),

@@ -13,6 +13,14 @@ using namespace isp_dev;
 
 __device__ inline float sigmoidf_fast(float z) { return 1.f / (1.f + __expf(-z)); }
 
+// Edge function s = f(z) and its derivative; op is wave-uniform (ISP_OP_SIGMOID / _DOT / _ONE).
+// The grouped kernels pass it as a compile-time constant, the generic ones at run time.
+__device__ inline void edge_fn(int op, float z, float& s, float& ds) {
+  if (op == ISP_OP_SIGMOID) { s = sigmoidf_fast(z); ds = s * (1.f - s); }
+  else if (op == ISP_OP_DOT) { s = z; ds = 1.f; }
+  else { s = 1.f; ds = 0.f; }
+}
+
 template <int VEC, int T>
 __device__ inline float dot_lanes(const float (&a)[T][VEC], const float (&b)[T][VEC]) {
   float s = 0.f;
@@ -41,16 +49,17 @@ template <int VEC_, int T_, bool HAS_VAL_>
 struct fwd_policy {
   static constexpr int VEC = VEC_, T = T_, NG = 1, U = pick_u(VEC_ * T_);
   static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = false, HAS_FINISH = false;
-  struct args { const float* src[1]; int64_t ld[1]; };
+  struct args { const float* src[1]; int64_t ld[1]; int op; };
   struct row_state { float xi[T][VEC]; };
   __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
                                           const bool (&on)[T]) {
     load_row<VEC, T>(pa.src[0], pa.ld[0], row, col, on, rs.xi);
   }
-  __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[1][T][VEC],
+  __device__ static inline void edge(const args& pa, row_state& rs, float a, const float (&x)[1][T][VEC],
                                      float (&acc)[T][VEC], const bool (&)[T], const edge_info&) {
-    const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xi, x[0]));
-    const float w = a * sigmoidf_fast(z);
+    float sg = 1.f, dsg = 0.f;
+    if (pa.op != ISP_OP_ONE) edge_fn(pa.op, wave_allreduce(dot_lanes<VEC, T>(rs.xi, x[0])), sg, dsg);
+    const float w = a * sg;
 #pragma unroll
     for (int tt = 0; tt < T; ++tt)
 #pragma unroll
@@ -63,19 +72,21 @@ template <int VEC_, int T_, bool HAS_VAL_>
 struct bwd_row_policy {
   static constexpr int VEC = VEC_, T = T_, NG = 1, U = pick_u(VEC_ * T_);
   static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = false, HAS_FINISH = false;
-  struct args { const float* src[1]; int64_t ld[1]; const float* G; int64_t ldg; };
+  struct args { const float* src[1]; int64_t ld[1]; const float* G; int64_t ldg; int op; };
   struct row_state { float xi[T][VEC]; float gi[T][VEC]; };
   __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
                                           const bool (&on)[T]) {
     load_row<VEC, T>(pa.src[0], pa.ld[0], row, col, on, rs.xi);
     load_row<VEC, T>(pa.G, pa.ldg, row, col, on, rs.gi);
   }
-  __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[1][T][VEC],
+  __device__ static inline void edge(const args& pa, row_state& rs, float a, const float (&x)[1][T][VEC],
                                      float (&acc)[T][VEC], const bool (&)[T], const edge_info&) {
+    if (pa.op == ISP_OP_ONE) return;  // s does not depend on x_i: nothing flows through z
     const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xi, x[0]));
     const float gd = wave_allreduce(dot_lanes<VEC, T>(rs.gi, x[0]));
-    const float sg = sigmoidf_fast(z);
-    const float dz = a * gd * sg * (1.f - sg);
+    float sg, dsg;
+    edge_fn(pa.op, z, sg, dsg);
+    const float dz = a * gd * dsg;
 #pragma unroll
     for (int tt = 0; tt < T; ++tt)
 #pragma unroll
@@ -89,19 +100,21 @@ template <int VEC_, int T_, bool HAS_VAL_>
 struct bwd_col_policy {
   static constexpr int VEC = VEC_, T = T_, NG = 2, U = pick_u(2 * VEC_ * T_);
   static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = true, NEEDS_PERM = false, HAS_FINISH = false;
-  struct args { const float* src[2]; int64_t ld[2]; };  // src[0] = X, src[1] = dY
+  struct args { const float* src[2]; int64_t ld[2]; int op; };  // src[0] = X, src[1] = dY
   struct row_state { float xj[T][VEC]; };
   __device__ static inline void row_begin(const args& pa, row_state& rs, int row, const int (&col)[T],
                                           const bool (&on)[T]) {
     load_row<VEC, T>(pa.src[0], pa.ld[0], row, col, on, rs.xj);
   }
-  __device__ static inline void edge(const args&, row_state& rs, float a, const float (&x)[2][T][VEC],
+  __device__ static inline void edge(const args& pa, row_state& rs, float a, const float (&x)[2][T][VEC],
                                      float (&acc)[T][VEC], const bool (&)[T], const edge_info&) {
-    const float z = wave_allreduce(dot_lanes<VEC, T>(rs.xj, x[0]));
-    const float gd = wave_allreduce(dot_lanes<VEC, T>(rs.xj, x[1]));
-    const float sg = sigmoidf_fast(z);
+    float sg = 1.f, dsg = 0.f, gd = 0.f;
+    if (pa.op != ISP_OP_ONE) {
+      edge_fn(pa.op, wave_allreduce(dot_lanes<VEC, T>(rs.xj, x[0])), sg, dsg);
+      gd = wave_allreduce(dot_lanes<VEC, T>(rs.xj, x[1]));
+    }
     const float w = a * sg;
-    const float dz = a * gd * sg * (1.f - sg);
+    const float dz = a * gd * dsg;
 #pragma unroll
     for (int tt = 0; tt < T; ++tt)
 #pragma unroll
@@ -140,58 +153,63 @@ isp_status run_pass(const isp_csr* A, const typename P::args& pa, int d, float* 
 }
 
 // ---- grouped fast path (d % 4 == 0, 16-byte aligned operands) -----------------------------------
-struct g_args1 { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
-struct g_args12 { const float* src[1]; int64_t lds_[1]; const float* rowop[2]; int64_t ldr[2]; float* out_entry; };
-struct g_args21 { const float* src[2]; int64_t lds_[2]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
+struct g_args1 { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; int op; };
+struct g_args12 { const float* src[1]; int64_t lds_[1]; const float* rowop[2]; int64_t ldr[2]; float* out_entry; int op; };
+struct g_args21 { const float* src[2]; int64_t lds_[2]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; int op; };
 
+template <int OP>
 struct g_fwd {  // gathered x_j, row operand x_i
   static constexpr int NSRC = 1, NROW = 1;
   static constexpr bool PER_ENTRY = false, ACCUMULATE = false;
   using args = g_args1;
   template <int LPG>
-  __device__ static inline void edge(float a, const float (&x)[1][4], const float (&r)[1][4], float (&acc)[4]) {
-    const float z = group_allreduce<LPG>(dot4(r[0], x[0]));
-    const float w = a * sigmoidf_fast(z);
+  __device__ static inline void edge(const args&, float a, const float (&x)[1][4], const float (&r)[1][4],
+                                     float (&acc)[4]) {
+    float sg = 1.f, dsg = 0.f;
+    if (OP != ISP_OP_ONE) edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0])), sg, dsg);
+    const float w = a * sg;
 #pragma unroll
     for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[0][v], acc[v]);
   }
-  template <int LPG>
-  __device__ static inline float entry(float, const float (&)[1][4], const float (&)[1][4]) { return 0.f; }
 };
 
+template <int OP>
 struct g_bwd_row {  // gathered x_j, row operands x_i and g_i:  dX_i += dz x_j
   static constexpr int NSRC = 1, NROW = 2;
   static constexpr bool PER_ENTRY = false, ACCUMULATE = false;
   using args = g_args12;
   template <int LPG>
-  __device__ static inline void edge(float a, const float (&x)[1][4], const float (&r)[2][4], float (&acc)[4]) {
+  __device__ static inline void edge(const args&, float a, const float (&x)[1][4], const float (&r)[2][4],
+                                     float (&acc)[4]) {
+    if (OP == ISP_OP_ONE) return;  // s does not depend on x_i: nothing flows through z
     const float z = group_allreduce<LPG>(dot4(r[0], x[0]));
     const float gd = group_allreduce<LPG>(dot4(r[1], x[0]));
-    const float sg = sigmoidf_fast(z);
-    const float dz = a * gd * sg * (1.f - sg);
+    float sg, dsg;
+    edge_fn(OP, z, sg, dsg);
+    const float dz = a * gd * dsg;
 #pragma unroll
     for (int v = 0; v < 4; ++v) acc[v] = fmaf(dz, x[0][v], acc[v]);
   }
-  template <int LPG>
-  __device__ static inline float entry(float, const float (&)[1][4], const float (&)[2][4]) { return 0.f; }
 };
 
+template <int OP>
 struct g_bwd_col {  // over A^T: gathered x_i and g_i, row operand x_j:  dX_j += a s g_i + dz x_i
   static constexpr int NSRC = 2, NROW = 1;
   static constexpr bool PER_ENTRY = false, ACCUMULATE = true;
   using args = g_args21;
   template <int LPG>
-  __device__ static inline void edge(float a, const float (&x)[2][4], const float (&r)[1][4], float (&acc)[4]) {
-    const float z = group_allreduce<LPG>(dot4(r[0], x[0]));
-    const float gd = group_allreduce<LPG>(dot4(r[0], x[1]));
-    const float sg = sigmoidf_fast(z);
+  __device__ static inline void edge(const args&, float a, const float (&x)[2][4], const float (&r)[1][4],
+                                     float (&acc)[4]) {
+    float sg = 1.f, dsg = 0.f, gd = 0.f;
+    if (OP != ISP_OP_ONE) {
+      edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0])), sg, dsg);
+      gd = group_allreduce<LPG>(dot4(r[0], x[1]));
+    }
     const float w = a * sg;
-    const float dz = a * gd * sg * (1.f - sg);
+    const float dz = a * gd * dsg;
 #pragma unroll
     for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
   }
-  template <int LPG>
-  __device__ static inline float entry(float, const float (&)[2][4], const float (&)[1][4]) { return 0.f; }
 };
 
 template <class P, int LPG, bool HAS_VAL>
@@ -256,13 +274,15 @@ int pick_shape(int d, bool ok4, bool ok2) {
 
 }  // namespace
 
-isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                              hipStream_t s) {
+isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,
+                              int64_t ldy, hipStream_t s) {
   const bool ok4 = ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16);
   const bool ok2 = ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8);
   if (ok4 && d % 4 == 0 && grouped_partition_ok(A)) {
-    g_fwd::args pa{{X}, {ldx}, {X}, {ldx}, nullptr};
-    return run_grouped_d<g_fwd>(A, pa, d, Y, ldy, s);
+    g_args1 pa{{X}, {ldx}, {X}, {ldx}, nullptr, op};
+    if (op == ISP_OP_SIGMOID) return run_grouped_d<g_fwd<ISP_OP_SIGMOID>>(A, pa, d, Y, ldy, s);
+    if (op == ISP_OP_DOT) return run_grouped_d<g_fwd<ISP_OP_DOT>>(A, pa, d, Y, ldy, s);
+    return run_grouped_d<g_fwd<ISP_OP_ONE>>(A, pa, d, Y, ldy, s);
   }
   const int shape = pick_shape(d, ok4, ok2);
   const bool hv = A->v.values != nullptr;
@@ -273,6 +293,7 @@ isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int
     P::args pa;                                   \
     pa.src[0] = X;                                \
     pa.ld[0] = ldx;                               \
+    pa.op = op;                                   \
     st = run_pass<P>(A, pa, d, Y, ldy, s);        \
   }
   ISP_SHAPE_SWITCH(shape, hv, ISP_FWD)
@@ -281,15 +302,23 @@ isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int
 }
 
 isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx, const float* G, int64_t ldg,
-                                  int32_t d, float* dX, int64_t lddx, hipStream_t s) {
+                                  int32_t d, int op, float* dX, int64_t lddx, hipStream_t s) {
   const bool ok4 = ldx % 4 == 0 && ldg % 4 == 0 && lddx % 4 == 0 && aligned(X, 16) && aligned(G, 16) && aligned(dX, 16);
   const bool ok2 = ldx % 2 == 0 && ldg % 2 == 0 && lddx % 2 == 0 && aligned(X, 8) && aligned(G, 8) && aligned(dX, 8);
   if (ok4 && d % 4 == 0 && grouped_partition_ok(A) && grouped_partition_ok(A->At)) {
-    g_bwd_row::args p1{{X}, {ldx}, {X, G}, {ldx, ldg}, nullptr};
-    isp_status st1 = run_grouped_d<g_bwd_row>(A, p1, d, dX, lddx, s);
-    if (st1 != ISP_OK) return st1;
-    g_bwd_col::args p2{{X, G}, {ldx, ldg}, {X}, {ldx}, nullptr};
-    return run_grouped_d<g_bwd_col>(A->At, p2, d, dX, lddx, s);
+    g_args12 p1{{X}, {ldx}, {X, G}, {ldx, ldg}, nullptr, op};
+    g_args21 p2{{X, G}, {ldx, ldg}, {X}, {ldx}, nullptr, op};
+    isp_status st1;
+    if (op == ISP_OP_SIGMOID) {
+      st1 = run_grouped_d<g_bwd_row<ISP_OP_SIGMOID>>(A, p1, d, dX, lddx, s);
+      return st1 != ISP_OK ? st1 : run_grouped_d<g_bwd_col<ISP_OP_SIGMOID>>(A->At, p2, d, dX, lddx, s);
+    }
+    if (op == ISP_OP_DOT) {
+      st1 = run_grouped_d<g_bwd_row<ISP_OP_DOT>>(A, p1, d, dX, lddx, s);
+      return st1 != ISP_OK ? st1 : run_grouped_d<g_bwd_col<ISP_OP_DOT>>(A->At, p2, d, dX, lddx, s);
+    }
+    st1 = run_grouped_d<g_bwd_row<ISP_OP_ONE>>(A, p1, d, dX, lddx, s);
+    return st1 != ISP_OK ? st1 : run_grouped_d<g_bwd_col<ISP_OP_ONE>>(A->At, p2, d, dX, lddx, s);
   }
   const int shape = pick_shape(d, ok4, ok2);
   const bool hv = A->v.values != nullptr;
@@ -298,12 +327,12 @@ isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx,
   {                                                        \
     using P1 = bwd_row_policy<V, T, HV>;                   \
     P1::args p1;                                           \
-    p1.src[0] = X; p1.ld[0] = ldx; p1.G = G; p1.ldg = ldg; \
+    p1.src[0] = X; p1.ld[0] = ldx; p1.G = G; p1.ldg = ldg; p1.op = op; \
     st = run_pass<P1>(A, p1, d, dX, lddx, s);              \
     if (st == ISP_OK) {                                    \
       using P2 = bwd_col_policy<V, T, HV>;                 \
       P2::args p2;                                         \
-      p2.src[0] = X; p2.ld[0] = ldx; p2.src[1] = G; p2.ld[1] = ldg; \
+      p2.src[0] = X; p2.ld[0] = ldx; p2.src[1] = G; p2.ld[1] = ldg; p2.op = op; \
       st = run_pass<P2>(A->At, p2, d, dX, lddx, s);        \
     }                                                      \
   }

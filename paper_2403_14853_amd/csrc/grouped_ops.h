@@ -11,7 +11,7 @@ namespace isp_dev {
 
 // Policy P:  NSRC gathered operands (rows picked by column index), NROW row operands (rows picked
 // by the step's matrix row); args { src[NSRC], lds_[NSRC], rowop[NROW], ldr[NROW], out_entry };
-// either edge<LPG>(a, src, rowop, acc) accumulating into the row's result, or (PER_ENTRY)
+// either edge<LPG>(args, a, src, rowop, acc) accumulating into the row's result, or (PER_ENTRY)
 // entry<LPG>(a, src, rowop) returning the value stored for the entry.
 template <class P, int LPG, bool HAS_VAL>
 __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __restrict__ indptr,
@@ -99,7 +99,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
           *o = val;
         }
       } else {
-        P::template edge<LPG>(a[u], x[u], r[u], acc);
+        P::template edge<LPG>(pa, a[u], x[u], r[u], acc);
         if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
       }
     }

@@ -119,7 +119,8 @@ isp_status isp_sddmm(const isp_csr_t* A, const float* U, int64_t ldu, const floa
 
 static isp_status check_fused(const isp_csr_t* A, int32_t d, int op) {
   if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");
-  if (op != ISP_OP_SIGMOID) return isp_fail(ISP_EUNSUPPORTED, "unknown edge op %d", op);
+  if (op != ISP_OP_SIGMOID && op != ISP_OP_DOT && op != ISP_OP_ONE)
+    return isp_fail(ISP_EUNSUPPORTED, "unknown edge op %d", op);
   if (A->v.n_rows != A->v.n_cols) return isp_fail(ISP_EINVAL, "FusedMM needs a square matrix");
   if (d > ISP_PARTIAL_TILE) return isp_fail(ISP_EUNSUPPORTED, "FusedMM supports d <= %d", ISP_PARTIAL_TILE);
   return ISP_OK;
@@ -131,7 +132,7 @@ isp_status isp_fusedmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t 
   if ((st = check_fused(A, d, op)) != ISP_OK) return st;
   if ((st = check_dense(X, ldx, d, A->v.n_rows, "X")) != ISP_OK) return st;
   if ((st = check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
-  return isp_fusedmm_launch(A, X, ldx, d, Y, ldy, (hipStream_t)stream);
+  return isp_fusedmm_launch(A, X, ldx, d, op, Y, ldy, (hipStream_t)stream);
 }
 
 isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const float* dY, int64_t lddy, int32_t d,
@@ -142,7 +143,7 @@ isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const
   if ((st = check_dense(X, ldx, d, A->v.n_rows, "X")) != ISP_OK) return st;
   if ((st = check_dense(dY, lddy, d, A->v.n_rows, "dY")) != ISP_OK) return st;
   if ((st = check_dense(dX, lddx, d, A->v.n_rows, "dX")) != ISP_OK) return st;
-  return isp_fusedmm_bwd_launch(A, X, ldx, dY, lddy, d, dX, lddx, (hipStream_t)stream);
+  return isp_fusedmm_bwd_launch(A, X, ldx, dY, lddy, d, op, dX, lddx, (hipStream_t)stream);
 }
 
 isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,

@@ -71,10 +71,10 @@ isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_
                            hipStream_t s);
 isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv,
                             int32_t d, bool scale, float* out, hipStream_t s);
-isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                              hipStream_t s);
+isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,
+                              int64_t ldy, hipStream_t s);
 isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx, const float* G, int64_t ldg,
-                                  int32_t d, float* dX, int64_t lddx, hipStream_t s);
+                                  int32_t d, int op, float* dX, int64_t lddx, hipStream_t s);
 isp_status isp_spmm_reduce_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
                                   int64_t ldy, int32_t* arg, hipStream_t s);
 isp_status isp_spmm_reduce_bwd_launch(const isp_csr* A, const float* dY, int64_t lddy, int32_t d, int reduce,

@@ -101,8 +101,6 @@ struct sddmm_policy {
     const float dot = group_allreduce<LPG>(dot4(r[0], x[0]));
     return SCALE ? a * dot : dot;
   }
-  template <int LPG>
-  __device__ static inline void edge(float, const float (&)[1][4], const float (&)[1][4], float (&)[4]) {}
 };
 
 template <int LPG, bool SCALE>

@@ -186,7 +186,8 @@ isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_
   if (d > 2 * ISP_WAVE && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16)) vec = 4;
   else if (d > ISP_WAVE && d % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8)) vec = 2;
   const isp_view& av = A->v;
-  const bool grouped_ok = d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16) &&
+  // (a matrix without entries never reads X, which may then be absent: the generic path handles it)
+  const bool grouped_ok = av.nnz > 0 && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16) &&
                           A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + av.hub_t <= GS_MAX_ENT &&
                           av.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
   if (grouped_ok) {

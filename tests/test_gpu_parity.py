@@ -92,17 +92,18 @@ def _run_all_ops(indptr, indices, values, n_rows, n_cols, d, seed, fused=True):
     if fused and n_rows == n_cols and d <= 256:
         Xs = (0.3 * X).astype(np.float32)
         Xsd = dev(Xs)
-        Yf = torch.full((n_rows, d), float("nan"), device="cuda")
-        isp.fusedmm(A, Xsd, Yf)
-        ref, mag = oracle.fusedmm(indptr, indices, values, Xs)
-        assert_close(Yf, ref, mag, "fusedmm")
-        dXf = torch.full((n_rows, d), float("nan"), device="cuda")
-        isp.fusedmm_backward(A, Xsd, Gd, dXf)
-        ref, mag = oracle.fusedmm_backward(indptr, indices, values, Xs, G)
-        assert_close(dXf, ref, mag, "fusedmm backward")
-        dXf2 = torch.empty_like(dXf)
-        isp.fusedmm_backward(A, Xsd, Gd, dXf2)
-        assert torch.equal(dXf, dXf2)
+        for op in ("sigmoid", "dot", "one"):
+            Yf = torch.full((n_rows, d), float("nan"), device="cuda")
+            isp.fusedmm(A, Xsd, Yf, op=op)
+            ref, mag = oracle.fusedmm(indptr, indices, values, Xs, op=op)
+            assert_close(Yf, ref, mag, "fusedmm " + op)
+            dXf = torch.full((n_rows, d), float("nan"), device="cuda")
+            isp.fusedmm_backward(A, Xsd, Gd, dXf, op=op)
+            ref, mag = oracle.fusedmm_backward(indptr, indices, values, Xs, G, op=op)
+            assert_close(dXf, ref, mag, "fusedmm backward " + op)
+            dXf2 = torch.empty_like(dXf)
+            isp.fusedmm_backward(A, Xsd, Gd, dXf2, op=op)
+            assert torch.equal(dXf, dXf2)
     A.destroy()
 
 
@@ -147,6 +148,16 @@ def test_degenerate_shapes():
     assert torch.equal(ti, torch.zeros(6, dtype=torch.int64, device="cuda")) and tj.numel() == 0
     isp.spmm(At, torch.ones(5, 7, device="cuda"), Y)
     assert torch.equal(Y, torch.zeros_like(Y))
+    # same with a 16-byte friendly width and no X at all (nothing may be read from it)
+    Y8 = torch.full((5, 8), float("nan"), device="cuda")
+    isp.spmm(A, torch.empty(5, 8, device="cuda"), Y8)
+    assert torch.equal(Y8, torch.zeros_like(Y8))
+    import ctypes
+    lib = isp.load_library()
+    Y8.fill_(float("nan"))
+    st = lib.isp_spmm(A.handle, None, 8, 8, ctypes.c_void_p(Y8.data_ptr()), 8, None)
+    torch.cuda.synchronize()
+    assert st == 0 and torch.equal(Y8, torch.zeros_like(Y8))
     A.destroy()
     # n_rows = 0
     A = build(np.zeros(1, dtype=np.int64), np.zeros(0, np.int32), None, n_cols=0)

@@ -222,9 +222,10 @@ def test_sddmm_bruteforce_and_identity(case):
 
 
 # ---------------------------------------------------------------- FusedMM
-def _fused_dense(A, X):
-    """Unfused composition in dense fp64: S = sigmoid(X X^T), Y = (A * S) X."""
-    S = 1.0 / (1.0 + np.exp(-(X @ X.T)))
+def _fused_dense(A, X, op="sigmoid"):
+    """Unfused composition in dense fp64: S = f(X X^T), Y = (A * S) X."""
+    Z = X @ X.T
+    S = {"sigmoid": lambda z: 1.0 / (1.0 + np.exp(-z)), "dot": lambda z: z, "one": lambda z: np.ones_like(z)}[op](Z)
     return (A * S) @ X
 
 
@@ -234,6 +235,14 @@ def test_fusedmm_forward_is_unfused_composition(case):
     n, _, d, seed, indptr, indices, values = case
     rng = np.random.default_rng(seed + 3)
     X = (0.5 * rng.standard_normal((n, d))).astype(np.float32)
+    for op in ("dot", "one"):
+        Yo, mo = oracle.fusedmm(indptr, indices, values, X, op=op)
+        np.testing.assert_allclose(Yo, _fused_dense(_dense(n, n, indptr, indices, values), X.astype(np.float64), op),
+                                   rtol=1e-11, atol=1e-12)
+        assert np.all(mo + 1e-12 >= np.abs(Yo))
+    # the constant-one edge function is the plain SpMM
+    np.testing.assert_allclose(oracle.fusedmm(indptr, indices, values, X, op="one")[0],
+                               oracle.spmm(indptr, indices, values, X)[0], rtol=1e-13, atol=1e-13)
     Y, mag = oracle.fusedmm(indptr, indices, values, X)
     # route 1: dense
     np.testing.assert_allclose(Y, _fused_dense(_dense(n, n, indptr, indices, values), X.astype(np.float64)),
@@ -265,8 +274,9 @@ def test_fusedmm_special_cases():
     np.testing.assert_allclose(Y, deg[:, None] * sig * X.astype(np.float64), rtol=1e-13, atol=0)
 
 
+@pytest.mark.parametrize("op", ["sigmoid", "dot", "one"])
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
-def test_fusedmm_backward_finite_differences(seed):
+def test_fusedmm_backward_finite_differences(seed, op):
     """dX from the oracle equals the central finite difference of L = <dY, Y(X)>, where Y(X) is
     evaluated by the independent dense composition above (not by the oracle)."""
     rng = np.random.default_rng(seed)
@@ -279,7 +289,7 @@ def test_fusedmm_backward_finite_differences(seed):
     X = (np.round(rng.standard_normal((n, d)) * 64) / 128).astype(np.float32)
     G = (np.round(rng.standard_normal((n, d)) * 64) / 64).astype(np.float32)
     A = _dense(n, n, indptr, indices, values)
-    dX, mag = oracle.fusedmm_backward(indptr, indices, values, X, G)
+    dX, mag = oracle.fusedmm_backward(indptr, indices, values, X, G, op=op)
     h = 2.0 ** -12
     X64, G64 = X.astype(np.float64), G.astype(np.float64)
     fd = np.zeros((n, d))
@@ -288,7 +298,7 @@ def test_fusedmm_backward_finite_differences(seed):
             Xp, Xm = X64.copy(), X64.copy()
             Xp[r, k] += h
             Xm[r, k] -= h
-            fd[r, k] = (np.sum(G64 * _fused_dense(A, Xp)) - np.sum(G64 * _fused_dense(A, Xm))) / (2 * h)
+            fd[r, k] = (np.sum(G64 * _fused_dense(A, Xp, op)) - np.sum(G64 * _fused_dense(A, Xm, op))) / (2 * h)
     np.testing.assert_allclose(dX, fd, rtol=1e-6, atol=1e-6)
     assert np.all(mag >= 0)
 
