@@ -79,10 +79,17 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   }
   const int n_rows = it.row_last - it.row;
   if (it.is_seg) {
-    if (lane == 0) { rp[0] = 0; rp[1] = (gs_u16)n_ent; }
-  } else {
-    for (int r = lane; r <= n_rows; r += ISP_WAVE) rp[r] = (gs_u16)(indptr[it.row + r] - it.p);
+    // one row, no table to search: step s covers entries [s * G, s * G + G), the last one ends the row
+    const int n_steps = (n_ent + G - 1) / G;
+    const int n_padded = (n_steps + GS_U - 1) / GS_U * GS_U;
+    for (int s = lane; s < n_padded; s += ISP_WAVE) {
+      const int left = n_ent - s * G;
+      step[s] = s < n_steps ? gs_pack(s * G, left >= G ? G : left, s + 1 == n_steps) : (gs_u16)0;
+    }
+    wave_lds_sync();
+    return n_padded;
   }
+  for (int r = lane; r <= n_rows; r += ISP_WAVE) rp[r] = (gs_u16)(indptr[it.row + r] - it.p);
   wave_lds_sync();
   int carry = 0;
   for (int c = 0; c < n_rows; c += ISP_WAVE) {
