@@ -258,3 +258,13 @@ def test_two_handles_on_two_streams():
     assert_close(Y1, ref, mag, "spmm on a side stream")
     A1.destroy()
     A2.destroy()
+
+
+@pytest.mark.parametrize("n_rows,n_cols,nnz", [(50, 1, 40), (300, 200, 5000), (1000, 3_000_000, 4096), (5000, 70_000, 16384),
+                                               (4096, 4096, 4096 * 4)])
+def test_transpose_shapes(n_rows, n_cols, nnz):
+    """One, two and three radix passes; a single column; mostly empty columns; nnz a multiple of the sort tile."""
+    indptr, indices, values = graphgen.random_csr(n_rows, n_cols, nnz, 21, sorted_cols=False, allow_dup=True)
+    A = build(indptr, indices, values, n_cols=n_cols)
+    _check_transpose(A, indptr, indices, values, n_rows, n_cols)
+    A.destroy()
