@@ -18,8 +18,9 @@ constexpr int RS_WAVE_KEYS = RS_ROUNDS * ISP_WAVE;  // contiguous keys owned by 
 constexpr int RS_TILE = RS_WAVE_KEYS * RS_WAVES;    // keys per workgroup
 constexpr int RS_RADIX = 256;
 
-// Source row of every stored entry, written by the same work items the compute kernels use.
-__global__ void __launch_bounds__(ISP_WG) k_row_of(isp_view A, int32_t* __restrict__ row_of) {
+// (source row, value bits) of every stored entry, written by the same work items the compute
+// kernels use; the final gather then needs one 8-byte read per entry instead of two 4-byte ones.
+__global__ void __launch_bounds__(ISP_WG) k_row_of(isp_view A, int2* __restrict__ row_of) {
   const int lane = threadIdx.x & (ISP_WAVE - 1);
   const int item = blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6);
   if (item >= A.n_blocks + A.n_seg) return;
@@ -28,7 +29,8 @@ __global__ void __launch_bounds__(ISP_WG) k_row_of(isp_view A, int32_t* __restri
     if (r1 == r0 + 1 && A.indptr[r1] - A.indptr[r0] > A.hub_t) return;  // hub row: written by its segments
     for (int r = r0; r < r1; ++r) {
       const int64_t e = A.indptr[r + 1];
-      for (int64_t p = A.indptr[r] + lane; p < e; p += ISP_WAVE) row_of[p] = r;
+      for (int64_t p = A.indptr[r] + lane; p < e; p += ISP_WAVE)
+        row_of[p] = make_int2(r, A.values ? __float_as_int(A.values[p]) : 0);
     }
   } else {
     const int s = item - A.n_blocks;
@@ -37,7 +39,8 @@ __global__ void __launch_bounds__(ISP_WG) k_row_of(isp_view A, int32_t* __restri
     const int64_t re = A.indptr[hr + 1];
     const int64_t b = A.indptr[hr] + (int64_t)(s - A.hub_seg_ptr[h]) * A.seg_len;
     const int64_t e = (b + A.seg_len < re) ? b + A.seg_len : re;
-    for (int64_t p = b + lane; p < e; p += ISP_WAVE) row_of[p] = hr;
+    for (int64_t p = b + lane; p < e; p += ISP_WAVE)
+      row_of[p] = make_int2(hr, A.values ? __float_as_int(A.values[p]) : 0);
   }
 }
 
@@ -119,8 +122,8 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(const int32_t* __r
 // of A^T (found where the sorted column changes; empty columns get the next offset).
 __global__ void __launch_bounds__(256) k_transpose_finish(const int32_t* __restrict__ skey,
                                                           const int32_t* __restrict__ spay, int64_t nnz,
-                                                          int64_t n_cols, const int32_t* __restrict__ row_of,
-                                                          const float* __restrict__ values,
+                                                          int64_t n_cols, const int2* __restrict__ row_of,
+                                                          bool has_values,
                                                           int64_t* __restrict__ t_indptr,
                                                           int32_t* __restrict__ t_indices, int32_t* __restrict__ perm,
                                                           float* __restrict__ t_values) {
@@ -128,9 +131,10 @@ __global__ void __launch_bounds__(256) k_transpose_finish(const int32_t* __restr
   if (q >= nnz) return;
   const int32_t c = skey[q];
   const int32_t src = spay[q];
+  const int2 rv = row_of[src];
   perm[q] = src;
-  t_indices[q] = row_of[src];
-  if (values) t_values[q] = values[src];
+  t_indices[q] = rv.x;
+  if (has_values) t_values[q] = __int_as_float(rv.y);
   const int32_t prev = q > 0 ? skey[q - 1] : -1;
   // (the clamp only matters for an unvalidated CSR with a column >= n_cols)
   const int64_t c_hi = c < n_cols ? (int64_t)c : n_cols - 1;
@@ -161,7 +165,7 @@ t_layout make_layout(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_value
   L.t_indices = take(e);
   L.perm = take(e);
   L.t_values = take(has_values ? e : 0);
-  L.row_of = take(e);
+  L.row_of = take(2 * e);
   L.key_a = take(e);
   L.key_b = take(e);
   L.pay_a = take(e);
@@ -194,7 +198,7 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   int32_t* t_indices = (int32_t*)(base + L.t_indices);
   int32_t* perm = (int32_t*)(base + L.perm);
   float* t_values = has_values ? (float*)(base + L.t_values) : nullptr;
-  int32_t* row_of = (int32_t*)(base + L.row_of);
+  int2* row_of = (int2*)(base + L.row_of);
   int32_t* key[2] = {(int32_t*)(base + L.key_a), (int32_t*)(base + L.key_b)};
   int32_t* pay[2] = {(int32_t*)(base + L.pay_a), (int32_t*)(base + L.pay_b)};
   int32_t* table = (int32_t*)(base + L.table);
@@ -230,7 +234,7 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
       kin = kout;
       pin = pout;
     }
-    k_transpose_finish<<<(unsigned)((nnz + 255) / 256), 256, 0, s>>>(kin, pin, nnz, n_cols, row_of, v.values, t_indptr,
+    k_transpose_finish<<<(unsigned)((nnz + 255) / 256), 256, 0, s>>>(kin, pin, nnz, n_cols, row_of, has_values, t_indptr,
                                                                     t_indices, perm, t_values);
     ISP_LAUNCH_CHECK();
   }
