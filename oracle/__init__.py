@@ -18,13 +18,28 @@ _LIB = os.path.join(_HERE, "libisp_oracle.so")
 _lib = None
 
 
+def compile_source(src: str, out: str) -> str:
+    """gcc line shared by the real build and by the tests that compile deliberately broken copies."""
+    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", src, "-o", out, "-lm"])
+    return out
+
+
 def build(force: bool = False) -> str:
     """Compile isp_oracle.c into libisp_oracle.so with gcc."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", _SRC, "-o", tmp, "-lm"])
+        compile_source(_SRC, tmp)
         os.replace(tmp, _LIB)
     return _LIB
+
+
+def use_library(path):
+    """Point this module at another build of the oracle (tests of the pins use broken copies);
+    ``None`` goes back to the real one."""
+    global _lib
+    _lib = None
+    if path is not None:
+        _lib = _bind(ctypes.CDLL(path))
 
 
 def _load():
@@ -32,7 +47,11 @@ def _load():
     if _lib is not None:
         return _lib
     build()
-    lib = ctypes.CDLL(_LIB)
+    _lib = _bind(ctypes.CDLL(_LIB))
+    return _lib
+
+
+def _bind(lib):
     vp = ctypes.c_void_p
     i64, i32 = ctypes.c_int64, ctypes.c_int32
     lib.isp_oracle_max_threads.restype = ctypes.c_int
@@ -53,7 +72,6 @@ def _load():
     lib.isp_oracle_spmm_reduce.restype = None
     lib.isp_oracle_spmm_reduce_backward.argtypes = [i64, i64, vp, vp, vp, vp, i64, i32, ctypes.c_int, vp, vp, vp]
     lib.isp_oracle_spmm_reduce_backward.restype = None
-    _lib = lib
     return lib
 
 
