@@ -173,6 +173,8 @@ def main():
         "op_gflops": {("%d:%s" % (i, o)): round(flops_of[o] / (op_ms[i] * 1e-3) / 1e9, 1) for i, o in enumerate(ops)},
         "setup_ms": {"generate_host": round(gen_s * 1e3, 1), "csr_build": round(build_ms, 3),
                      "transpose_first_call": round(transpose_ms, 3)},
+        # how many backward passes the one-time transpose costs (it is cached from then on)
+        "transpose_cost_in_backward_ops": round(transpose_ms / op_ms[-1], 2),
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
@@ -308,12 +310,19 @@ def cpu_baseline(w, Y_gpu, dom):
         ref, mag = oracle.fusedmm(sp, si, sv, w.X, want_mag=True)
         flops, kind = 4.0 * nnz_s * w.d, "fusedmm forward"
     dt = time.perf_counter() - t0
+    single = None
+    if nnz_s <= 5_000_000:  # small workloads: also the oracle on one thread
+        oracle.set_threads(1)
+        t1 = time.perf_counter()
+        (oracle.spmm if dom == "spmm" else oracle.fusedmm)(sp, si, sv, w.X, want_mag=False)
+        single = round(flops / (time.perf_counter() - t1) / 1e9, 2)
+        oracle.set_threads(threads)
     got = Y_gpu[:rows].cpu().numpy().astype(np.float64)
     ratio = float(np.max(np.abs(got - ref) / (1e-5 * mag + 1e-6)))
     return {"value": round(flops / dt / 1e9, 2), "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
             "sample": "%s on rows [0, %d) of the same graph (%d stored entries), fp64 accumulate, "
                       "OpenMP over rows, %.1f s" % (kind, rows, nnz_s, dt),
-            "gpu_vs_oracle_max_err_over_tol": ratio}
+            "single_thread_value": single, "gpu_vs_oracle_max_err_over_tol": ratio}
 
 
 if __name__ == "__main__":

@@ -268,3 +268,18 @@ def test_transpose_shapes(n_rows, n_cols, nnz):
     A = build(indptr, indices, values, n_cols=n_cols)
     _check_transpose(A, indptr, indices, values, n_rows, n_cols)
     A.destroy()
+
+
+def test_trusted_build_skips_validation_only():
+    w = graphgen.make_config(0)
+    A = isp.csr_build(dev(w.indptr), dev(w.indices), dev(w.values), trusted=True)
+    B = build(w.indptr, w.indices, w.values)
+    ia, ib = A.info(), B.info()
+    assert ia == ib
+    X = dev(w.X)
+    Ya, Yb = torch.empty_like(X), torch.empty_like(X)
+    isp.spmm(A, X, Ya)
+    isp.spmm(B, X, Yb)
+    assert torch.equal(Ya, Yb)
+    A.destroy()
+    B.destroy()
