@@ -37,6 +37,9 @@ def main():
                          "the cached transpose and with the transpose rebuilt every epoch")
     ap.add_argument("--sweep-d", action="store_true",
                     help="instead of the benchmark line: SpMM forward time over feature widths 8..1024")
+    ap.add_argument("--graph", action="store_true",
+                    help="instead of the benchmark line: the step captured in a HIP graph vs launched eagerly "
+                         "(matters for the launch-bound small workloads)")
     ap.add_argument("--gcn-step", action="store_true",
                     help="instead of the benchmark line: a 2-layer GCN training step (sparse ops through the "
                          "autograd wrappers, dense GEMMs through torch) with hidden width d")
@@ -119,6 +122,23 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    if args.graph:
+        torch.cuda.synchronize()
+        eager_ms = _time_ms(step, args.steps)
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                step()
+        torch.cuda.synchronize()
+        g.replay()
+        graph_ms = _time_ms(g.replay, args.steps)
+        print(json.dumps({"what": "one step launched eagerly vs replayed from a captured HIP graph", "workload": w.name,
+                          "ops": ops, "eager_ms_per_step": round(eager_ms, 4), "graph_ms_per_step": round(graph_ms, 4)}))
+        return
     if args.copy_calibration:
         for _ in range(3):
             Y.copy_(X)  # plain copy kernel: reads 4*n*d bytes, writes 4*n*d bytes
