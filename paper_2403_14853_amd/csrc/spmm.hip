@@ -67,7 +67,9 @@ isp_status launch_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int
 // ---- grouped fast path -------------------------------------------------------------------------
 // LPG lanes x float4 cover one slice of 4 * LPG feature columns; G = 64 / LPG nonzeros per gather
 // instruction.  Slice s of tile k_base covers columns [k_base + s * 4 * LPG, +4 * LPG).
-template <int LPG, bool HAS_VAL>
+// ADDR32: every byte offset into X fits 32 bits and both factors of column * row-pitch fit 24 bits, so
+// the gather address is one full-rate 24-bit multiply-add on top of a scalar base pointer.
+template <int LPG, bool HAS_VAL, bool ADDR32>
 __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 4))) k_spmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                          const int32_t* __restrict__ indices,
                                                          const float* __restrict__ values,
@@ -89,9 +91,12 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_base + (slice * LPG + q) * 4;
   const bool lane_on = col < d;
-  // lanes without a live entry (row tails, null steps, columns past d) read row 0 of X and have
-  // their data replaced by zeros, so every step issues exactly one gather per lane
+  // lanes without a live entry (row tails, null steps, columns past d) still issue their gather -
+  // from row 0 of X - so that every step is exactly one load per lane (exact wait counts, no
+  // branches around loads); what they fetch is never used
   const float* __restrict__ xcol = lane_on ? X + col : X;
+  const unsigned lane_byte = lane_on ? (unsigned)col * 4u : 0u;
+  const unsigned pitch_byte = (unsigned)ldx * 4u;
   float* __restrict__ out = it.is_seg ? A.partials + (col - k_base) : Y + col;
   const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
   int row = it.row;
@@ -118,16 +123,23 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool act = g < gs_cnt(dsc[u]) && lane_on;
-      a[u] = act ? __int_as_float(e[u].y) : 0.f;
-      load_vec<4>(xcol + (int64_t)(act ? e[u].x : 0) * ldx, x[u]);
+      a[u] = __int_as_float(e[u].y);
+      const int cj = act ? e[u].x : 0;
+      if constexpr (ADDR32) {
+        const unsigned off = __umul24((unsigned)cj, pitch_byte) + lane_byte;
+        load_vec<4>(reinterpret_cast<const float*>(reinterpret_cast<const char*>(X) + off), x[u]);
+      } else {
+        load_vec<4>(xcol + (int64_t)cj * ldx, x[u]);
+      }
     }
   };
   auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][4], const float (&a)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const bool act = g < gs_cnt(dsc[u]) && lane_on;
+      if (g < gs_cnt(dsc[u]) && lane_on) {  // divergent on purpose: dead lanes skip the FMAs, nothing to zero
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc[v] = fmaf(a[u], act ? x[u][v] : 0.f, acc[v]);
+        for (int v = 0; v < 4; ++v) acc[v] = fmaf(a[u], x[u][v], acc[v]);
+      }
       if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
     }
   };
@@ -161,10 +173,13 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * (unsigned)n_slices;
-    if (v.values)
-      k_spmm_grouped<LPG, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy);
-    else
-      k_spmm_grouped<LPG, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy);
+    const bool a32 = v.n_cols < (1 << 24) && ldx * 4 < (1 << 24) &&
+                     ((uint64_t)v.n_cols * (uint64_t)ldx + (uint64_t)d) * 4u < ((uint64_t)1 << 32);
+#define ISP_GO(HV, A32) \
+  k_spmm_grouped<LPG, HV, A32><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy)
+    if (v.values) { if (a32) ISP_GO(true, true); else ISP_GO(true, false); }
+    else { if (a32) ISP_GO(false, true); else ISP_GO(false, false); }
+#undef ISP_GO
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
