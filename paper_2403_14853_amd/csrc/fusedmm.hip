@@ -164,12 +164,14 @@ struct g_fwd {  // gathered x_j, row operand x_i
   using args = g_args1;
   template <int LPG>
   __device__ static inline void edge(const args&, float a, const float (&x)[1][4], const float (&r)[1][4],
-                                     float (&acc)[4]) {
+                                     float (&acc)[4], bool lane_on, bool live) {
     float sg = 1.f, dsg = 0.f;
-    if (OP != ISP_OP_ONE) edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0])), sg, dsg);
+    if (OP != ISP_OP_ONE) edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0], lane_on)), sg, dsg);
     const float w = a * sg;
+    if (live) {
 #pragma unroll
-    for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[0][v], acc[v]);
+      for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[0][v], acc[v]);
+    }
   }
 };
 
@@ -180,15 +182,17 @@ struct g_bwd_row {  // gathered x_j, row operands x_i and g_i:  dX_i += dz x_j
   using args = g_args12;
   template <int LPG>
   __device__ static inline void edge(const args&, float a, const float (&x)[1][4], const float (&r)[2][4],
-                                     float (&acc)[4]) {
+                                     float (&acc)[4], bool lane_on, bool live) {
     if (OP == ISP_OP_ONE) return;  // s does not depend on x_i: nothing flows through z
-    const float z = group_allreduce<LPG>(dot4(r[0], x[0]));
-    const float gd = group_allreduce<LPG>(dot4(r[1], x[0]));
+    const float z = group_allreduce<LPG>(dot4(r[0], x[0], lane_on));
+    const float gd = group_allreduce<LPG>(dot4(r[1], x[0], lane_on));
     float sg, dsg;
     edge_fn(OP, z, sg, dsg);
     const float dz = a * gd * dsg;
+    if (live) {
 #pragma unroll
-    for (int v = 0; v < 4; ++v) acc[v] = fmaf(dz, x[0][v], acc[v]);
+      for (int v = 0; v < 4; ++v) acc[v] = fmaf(dz, x[0][v], acc[v]);
+    }
   }
 };
 
@@ -199,16 +203,18 @@ struct g_bwd_col {  // over A^T: gathered x_i and g_i, row operand x_j:  dX_j +=
   using args = g_args21;
   template <int LPG>
   __device__ static inline void edge(const args&, float a, const float (&x)[2][4], const float (&r)[1][4],
-                                     float (&acc)[4]) {
+                                     float (&acc)[4], bool lane_on, bool live) {
     float sg = 1.f, dsg = 0.f, gd = 0.f;
     if (OP != ISP_OP_ONE) {
-      edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0])), sg, dsg);
-      gd = group_allreduce<LPG>(dot4(r[0], x[1]));
+      edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0], lane_on)), sg, dsg);
+      gd = group_allreduce<LPG>(dot4(r[0], x[1], lane_on));
     }
     const float w = a * sg;
     const float dz = a * gd * dsg;
+    if (live) {
 #pragma unroll
-    for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
+      for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
+    }
   }
 };
 

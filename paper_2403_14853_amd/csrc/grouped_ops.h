@@ -11,8 +11,8 @@ namespace isp_dev {
 
 // Policy P:  NSRC gathered operands (rows picked by column index), NROW row operands (rows picked
 // by the step's matrix row); args { src[NSRC], lds_[NSRC], rowop[NROW], ldr[NROW], out_entry };
-// either edge<LPG>(args, a, src, rowop, acc) accumulating into the row's result, or (PER_ENTRY)
-// entry<LPG>(a, src, rowop) returning the value stored for the entry.
+// either edge<LPG>(args, a, src, rowop, acc, lane_on, live) accumulating into the row's result in live
+// lanes, or (PER_ENTRY) entry<LPG>(a, src, rowop, lane_on) returning the value stored for the entry.
 template <class P, int LPG, bool HAS_VAL>
 __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                           const int32_t* __restrict__ indices, const float* __restrict__ values,
@@ -70,8 +70,8 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool act = g < gs_cnt(dsc[u]) && lane_on;
-      a[u] = act ? __int_as_float(e[u].y) : 0.f;
-      const int64_t cj = act ? e[u].x : 0;
+      a[u] = __int_as_float(e[u].y);
+      const int64_t cj = act ? e[u].x : 0;  // dead lanes gather row 0; what they fetch is never used
 #pragma unroll
       for (int k = 0; k < NSRC; ++k) load_vec<4>(pa.src[k] + cj * pa.lds_[k] + coff, x[u][k]);
       const int64_t ri = srow[u] < A.n_rows ? srow[u] : 0;  // null steps after the last row
@@ -79,27 +79,19 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
       for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + ri * pa.ldr[k] + coff, r[u][k]);
     }
   };
-  auto consume = [&](const unsigned (&dsc)[U], float (&x)[U][NSRC][4], float (&r)[U][NROW][4], const float (&a)[U]) {
+  auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][NSRC][4], const float (&r)[U][NROW][4],
+                     const float (&a)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const bool act = g < gs_cnt(dsc[u]) && lane_on;
-#pragma unroll
-      for (int k = 0; k < NSRC; ++k)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) x[u][k][v] = act ? x[u][k][v] : 0.f;
-#pragma unroll
-      for (int k = 0; k < NROW; ++k)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) r[u][k][v] = lane_on ? r[u][k][v] : 0.f;
+      // The policies mask the per-lane partial dot products with lane_on (columns past d) and
+      // accumulate only in live lanes, so nothing fetched by a dead lane reaches a result.
+      const bool live = g < gs_cnt(dsc[u]);
       if constexpr (P::PER_ENTRY) {
         // one output per stored entry: lane 0 of every live group writes its entry's value
-        const float val = P::template entry<LPG>(a[u], x[u], r[u]);
-        if (g < gs_cnt(dsc[u]) && q == 0) {
-          float* o = pa.out_entry + it.p + gs_off(dsc[u]) + g;
-          *o = val;
-        }
+        const float val = P::template entry<LPG>(a[u], x[u], r[u], lane_on);
+        if (live && q == 0) pa.out_entry[it.p + gs_off(dsc[u]) + g] = val;
       } else {
-        P::template edge<LPG>(pa, a[u], x[u], r[u], acc);
+        P::template edge<LPG>(pa, a[u], x[u], r[u], acc, lane_on, live && lane_on);
         if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
       }
     }
@@ -127,8 +119,10 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   }
 }
 
-__device__ inline float dot4(const float (&a)[4], const float (&b)[4]) {
-  return fmaf(a[3], b[3], fmaf(a[2], b[2], fmaf(a[1], b[1], a[0] * b[0])));
+// Partial dot product of a lane's four columns; lanes whose columns lie past d contribute zero.
+__device__ inline float dot4(const float (&a)[4], const float (&b)[4], bool lane_on) {
+  const float p = fmaf(a[3], b[3], fmaf(a[2], b[2], fmaf(a[1], b[1], a[0] * b[0])));
+  return lane_on ? p : 0.f;
 }
 
 }  // namespace isp_dev

@@ -97,8 +97,8 @@ struct sddmm_policy {
   static constexpr bool PER_ENTRY = true, ACCUMULATE = false;
   struct args { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
   template <int LPG>
-  __device__ static inline float entry(float a, const float (&x)[1][4], const float (&r)[1][4]) {
-    const float dot = group_allreduce<LPG>(dot4(r[0], x[0]));
+  __device__ static inline float entry(float a, const float (&x)[1][4], const float (&r)[1][4], bool lane_on) {
+    const float dot = group_allreduce<LPG>(dot4(r[0], x[0], lane_on));
     return SCALE ? a * dot : dot;
   }
 };
