@@ -1,0 +1,89 @@
+"""Seeded sweep over random matrix shapes, feature widths, partition parameters and CSR
+irregularities (unsorted rows, repeated columns, missing value array, ld > d): every operation
+against the oracle."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import graphgen
+import oracle
+import paper_2403_14853_amd as isp
+from gpu_util import assert_close, build, dev
+
+pytestmark = pytest.mark.gpu
+
+WIDTHS = [1, 2, 4, 7, 8, 12, 16, 24, 32, 36, 48, 64, 72, 96, 100, 128, 132, 160, 192, 256, 260, 320, 512]
+
+
+def _case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    square = bool(rng.integers(0, 2))
+    n_rows = int(rng.integers(1, 2500))
+    n_cols = n_rows if square else int(rng.integers(1, 2500))
+    nnz = int(rng.integers(0, 30000))
+    d = int(rng.choice(WIDTHS))
+    env = dict(ISP_HUB_THRESHOLD=str(int(rng.choice([8, 24, 100, 512]))),
+               ISP_SEGMENT_LEN=str(int(rng.choice([8, 16, 64, 512]))),
+               ISP_BLOCK_COST=str(int(rng.choice([16, 32, 100, 256]))))
+    return dict(square=square, n_rows=n_rows, n_cols=n_cols, nnz=nnz, d=d, env=env,
+                sorted_cols=bool(rng.integers(0, 2)), allow_dup=bool(rng.integers(0, 2)),
+                has_values=bool(rng.integers(0, 4)), pad=int(rng.choice([0, 0, 4, 12])), skew=bool(rng.integers(0, 2)))
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_shape(seed):
+    c = _case(seed)
+    print("[random-shape] seed=%d %s" % (seed, {k: v for k, v in c.items()}), flush=True)
+    os.environ.update(c["env"])
+    try:
+        indptr, indices, values = graphgen.random_csr(c["n_rows"], c["n_cols"], c["nnz"], seed, sorted_cols=c["sorted_cols"],
+                                                      allow_dup=c["allow_dup"])
+        if c["skew"] and len(indices):  # pile a third of the entries onto a few hub columns / rows
+            rng = np.random.default_rng(seed)
+            hubs = rng.integers(0, c["n_cols"], size=3)
+            pick = rng.random(len(indices)) < 0.33
+            indices = np.where(pick, hubs[rng.integers(0, 3, size=len(indices))], indices).astype(np.int32)
+        if not c["has_values"]:
+            values = None
+        n_rows, n_cols, d, ld = c["n_rows"], c["n_cols"], c["d"], c["d"] + c["pad"]
+        rng = np.random.default_rng(seed + 5)
+        Xf = rng.standard_normal((n_cols, ld)).astype(np.float32)
+        Gf = rng.standard_normal((n_rows, ld)).astype(np.float32)
+        X, G = Xf[:, :d], Gf[:, :d]
+        Xd, Gd = dev(Xf)[:, :d], dev(Gf)[:, :d]
+        A = build(indptr, indices, values, n_cols=n_cols)
+        Ybuf = torch.full((n_rows, ld), 3.0, device="cuda")
+        isp.spmm(A, Xd, Ybuf[:, :d])
+        assert_close(Ybuf[:, :d].contiguous(), *oracle.spmm(indptr, indices, values, X), "spmm")
+        assert torch.all(Ybuf[:, d:] == 3.0)
+        At, _ = isp.csr_transpose_cached(A)
+        ti, tj, tv, perm = At.export()
+        o_ti, o_tj, o_perm, o_tv = oracle.transpose(n_rows, n_cols, indptr, indices, values)
+        assert np.array_equal(ti.cpu().numpy(), o_ti) and np.array_equal(tj.cpu().numpy(), o_tj)
+        assert np.array_equal(perm.cpu().numpy(), o_perm)
+        if values is not None:
+            assert np.array_equal(tv.cpu().numpy(), o_tv)
+        dXbuf = torch.full((n_cols, ld), 3.0, device="cuda")
+        isp.spmm(At, Gd, dXbuf[:, :d])
+        assert_close(dXbuf[:, :d].contiguous(), *oracle.spmm(o_ti, o_tj, o_tv, G), "spmm backward")
+        out = torch.full((len(indices),), float("nan"), device="cuda")
+        isp.sddmm(A, Gd, Xd, out, scale_by_a=bool(seed % 2))
+        assert_close(out, *oracle.sddmm(indptr, indices, values, G, X, scale_by_a=bool(seed % 2)), "sddmm")
+        if c["square"] and d <= 256:
+            op = ("sigmoid", "dot", "one")[seed % 3]
+            Xs = (0.3 * Xf).astype(np.float32)
+            Xsd = dev(Xs)[:, :d]
+            Yf = torch.full((n_rows, ld), 3.0, device="cuda")
+            isp.fusedmm(A, Xsd, Yf[:, :d], op=op)
+            assert_close(Yf[:, :d].contiguous(), *oracle.fusedmm(indptr, indices, values, Xs[:, :d], op=op), "fusedmm " + op)
+            dXf = torch.full((n_rows, ld), 3.0, device="cuda")
+            isp.fusedmm_backward(A, Xsd, Gd, dXf[:, :d], op=op)
+            assert_close(dXf[:, :d].contiguous(), *oracle.fusedmm_backward(indptr, indices, values, Xs[:, :d], G, op=op),
+                         "fusedmm backward " + op)
+            assert torch.all(Yf[:, d:] == 3.0) and torch.all(dXf[:, d:] == 3.0)
+        A.destroy()
+    finally:
+        for k in c["env"]:
+            os.environ.pop(k, None)
