@@ -89,6 +89,9 @@ def _run_all_ops(indptr, indices, values, n_rows, n_cols, d, seed, fused=True):
     isp.sddmm(A, Gd, Xd, out, scale_by_a=True)
     ref, mag = oracle.sddmm(indptr, indices, values, G, X, scale_by_a=True)
     assert_close(out, ref, mag, "sddmm scaled")
+    out2 = torch.empty_like(out)
+    isp.sddmm(A, Gd, Xd, out2, scale_by_a=True)
+    assert torch.equal(out, out2)  # run-to-run bitwise determinism
     if fused and n_rows == n_cols and d <= 256:
         Xs = (0.3 * X).astype(np.float32)
         Xsd = dev(Xs)
@@ -97,6 +100,9 @@ def _run_all_ops(indptr, indices, values, n_rows, n_cols, d, seed, fused=True):
             isp.fusedmm(A, Xsd, Yf, op=op)
             ref, mag = oracle.fusedmm(indptr, indices, values, Xs, op=op)
             assert_close(Yf, ref, mag, "fusedmm " + op)
+            Yf2 = torch.empty_like(Yf)
+            isp.fusedmm(A, Xsd, Yf2, op=op)
+            assert torch.equal(Yf, Yf2)
             dXf = torch.full((n_rows, d), float("nan"), device="cuda")
             isp.fusedmm_backward(A, Xsd, Gd, dXf, op=op)
             ref, mag = oracle.fusedmm_backward(indptr, indices, values, Xs, G, op=op)

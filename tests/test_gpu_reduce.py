@@ -44,6 +44,9 @@ def _check(indptr, indices, values, n_rows, n_cols, d, seed, integer_inputs=Fals
         else:
             assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), reduce + ": values differ"
             assert np.array_equal(arg.cpu().numpy(), ref_arg), reduce + ": positions differ"
+        Y2 = torch.empty_like(Y)
+        isp.spmm_reduce(A, Xd, Y2, reduce, arg)
+        assert torch.equal(Y, Y2)  # run-to-run bitwise determinism
         dX = torch.full((n_cols, d), float("nan"), device="cuda")
         isp.spmm_reduce_backward(A, Gd, dX, reduce, arg)
         ref, mag = oracle.spmm_reduce_backward(n_cols, indptr, indices, values, G, reduce, ref_arg)
