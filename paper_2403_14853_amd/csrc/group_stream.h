@@ -62,10 +62,13 @@ __device__ inline int wave_exclusive_scan_i(int v, int lane, int* total) {
 
 // Stage the item's entries and build its step table.  Returns the number of steps, rounded up to
 // a multiple of GS_U with null steps (no live entry, not a row end).
+// entry_scale (optional): row offsets of another matrix; entry p is staged with its value divided by
+// the length of row indices[p] of that matrix (the backward of the mean reduction runs over the
+// transpose and needs the source rows' lengths).
 template <int G, bool HAS_VAL>
 __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict__ indptr,
                                  const int32_t* __restrict__ indices, const float* __restrict__ values,
-                                 gs_wave_lds& L, int lane) {
+                                 gs_wave_lds& L, int lane, const int64_t* __restrict__ entry_scale = nullptr) {
   int2* __restrict__ ent = L.ent;
   gs_u16* __restrict__ step = L.step;
   gs_u16* __restrict__ rp = L.rp;
@@ -74,7 +77,9 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   for (int i = lane; i < n_ent; i += ISP_WAVE) {
     int2 e;
     e.x = __builtin_nontemporal_load(indices + it.p + i);
-    e.y = HAS_VAL ? __float_as_int(__builtin_nontemporal_load(values + it.p + i)) : 0x3f800000;
+    float val = HAS_VAL ? __builtin_nontemporal_load(values + it.p + i) : 1.f;
+    if (entry_scale) val /= (float)(entry_scale[e.x + 1] - entry_scale[e.x]);  // >= 1: the entry lies in that row
+    e.y = __float_as_int(val);
     ent[i] = e;
   }
   const int n_rows = it.row_last - it.row;

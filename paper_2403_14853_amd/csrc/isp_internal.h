@@ -69,6 +69,11 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
 // ---- compute (spmm.hip, sddmm.hip, fusedmm.hip) ------------------------------------------------
 isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
                            hipStream_t s);
+// Grouped fast path of SpMM; *done = false (nothing launched) when the operands do not qualify.
+// mean_mode 0: plain sum; 1: rows divided by their length; 2: entries divided by the length of row
+// indices[p] of the matrix whose row offsets are src_indptr.
+isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
+                                   int mean_mode, const int64_t* src_indptr, hipStream_t s, bool* done);
 isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv,
                             int32_t d, bool scale, float* out, hipStream_t s);
 isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,

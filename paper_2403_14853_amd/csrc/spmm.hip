@@ -42,6 +42,23 @@ __global__ void __launch_bounds__(ISP_WG) k_spmm_fixup(isp_view A, int d, int k0
   hub_fixup<VEC, T, false>(A, d, k0, Y, ldy);
 }
 
+// Mean reduction: the fixed-order sum of a hub row's segments, divided by the row's length.
+__global__ void __launch_bounds__(ISP_WG) k_spmm_fixup_mean(isp_view A, int d, int k0, float* __restrict__ Y,
+                                                            int64_t ldy) {
+  hub_fixup<4, 1, false>(A, d, k0, Y, ldy);
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int h = (int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6));
+  if (h >= A.n_hub || k0 + lane * 4 >= d) return;
+  const int row = A.hub_rows[h];
+  const float inv = 1.f / (float)(A.indptr[row + 1] - A.indptr[row]);  // a hub row is never empty
+  float* o = Y + (int64_t)row * ldy + k0 + lane * 4;  // written just above by this same lane
+  float t[4];
+  load_vec<4>(o, t);
+#pragma unroll
+  for (int v = 0; v < 4; ++v) t[v] *= inv;
+  store_vec<4>(o, t);
+}
+
 template <int VEC, int T>
 isp_status launch_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int k0, float* Y, int64_t ldy,
                        hipStream_t s) {
@@ -74,7 +91,10 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
                                                          const int32_t* __restrict__ indices,
                                                          const float* __restrict__ values,
                                                          const float* __restrict__ X, int64_t ldx, int d, int k_base,
-                                                         int n_slices, float* __restrict__ Y, int64_t ldy) {
+                                                         int n_slices, float* __restrict__ Y, int64_t ldy, int mean_mode,
+                                                         const int64_t* __restrict__ src_indptr) {
+  // mean_mode 1: divide every finished row by its length (mean reduction, forward);
+  // mean_mode 2: stage every entry divided by the length of source row indices[p] (its backward)
   constexpr int G = ISP_WAVE / LPG;
   constexpr int U = GS_U;
   __shared__ gs_lds lds;
@@ -86,7 +106,8 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const item_range it = locate_item(A, indptr, item);
   if (it.skip) return;
   gs_wave_lds& L = lds.w[w];
-  const int n_steps = gs_prepare<G, HAS_VAL>(it, indptr, indices, values, L, lane);  // multiple of U
+  const int n_steps = gs_prepare<G, HAS_VAL>(it, indptr, indices, values, L, lane,
+                                             mean_mode == 2 ? src_indptr : nullptr);  // multiple of U
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_base + (slice * LPG + q) * 4;
@@ -105,6 +126,13 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   auto finish_row = [&]() {
 #pragma unroll
     for (int v = 0; v < 4; ++v) acc[v] = group_sum<LPG>(acc[v]);
+    if (mean_mode == 1 && !it.is_seg) {  // hub segments keep plain partial sums; their fix-up divides
+      const int r_local = row - it.row;
+      const int len = (int)L.rp[r_local + 1] - (int)L.rp[r_local];
+      const float inv = len > 0 ? 1.f / (float)len : 0.f;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[v] *= inv;
+    }
     if (g == 0 && lane_on) store_vec<4>(out + (int64_t)row * ldo, acc);
 #pragma unroll
     for (int v = 0; v < 4; ++v) acc[v] = 0.f;
@@ -168,7 +196,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 
 template <int LPG>
 isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, int k_base, int n_slices, float* Y,
-                          int64_t ldy, hipStream_t s) {
+                          int64_t ldy, int mean_mode, const int64_t* src_indptr, hipStream_t s) {
   const isp_view& v = A->v;
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
@@ -176,7 +204,8 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
     const bool a32 = v.n_cols < (1 << 24) && ldx * 4 < (1 << 24) &&
                      ((uint64_t)v.n_cols * (uint64_t)ldx + (uint64_t)d) * 4u < ((uint64_t)1 << 32);
 #define ISP_GO(HV, A32) \
-  k_spmm_grouped<LPG, HV, A32><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy)
+  k_spmm_grouped<LPG, HV, A32><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy, \
+                                                       mean_mode, src_indptr)
     if (v.values) { if (a32) ISP_GO(true, true); else ISP_GO(true, false); }
     else { if (a32) ISP_GO(false, true); else ISP_GO(false, false); }
 #undef ISP_GO
@@ -184,7 +213,8 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
   }
   if (v.n_hub > 0) {
     const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    k_spmm_fixup<4, 1><<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
+    if (mean_mode == 1) k_spmm_fixup_mean<<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
+    else k_spmm_fixup<4, 1><<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   return ISP_OK;
@@ -194,45 +224,54 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 }  // namespace
 
-isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                           hipStream_t s) {
-  // lanes-over-features layout: the widest vector the width and alignment allow
-  int vec = 1;
-  if (d > 2 * ISP_WAVE && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16)) vec = 4;
-  else if (d > ISP_WAVE && d % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8)) vec = 2;
+// The grouped fast path; *done = false (and nothing launched) when the operands do not qualify.
+// mean_mode / src_indptr: see k_spmm_grouped.
+isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
+                                   int mean_mode, const int64_t* src_indptr, hipStream_t s, bool* done) {
   const isp_view& av = A->v;
   // (a matrix without entries never reads X, which may then be absent: the generic path handles it)
   const bool grouped_ok = av.nnz > 0 && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16) &&
                           A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + av.hub_t <= GS_MAX_ENT &&
                           av.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
-  if (grouped_ok) {
-    // Lanes per group 4 / 8 / 16 / 32 / 64 <-> column slices of 16 / 32 / 64 / 128 / 256 floats.
-    // Measured on R-MAT graphs (2.4 M and 124 M nonzeros, d = 8..256): the slice that just covers
-    // the row wins up to d = 128; on large graphs two 64-float slices per 128-float row win
-    // (dealt to alternating XCDs, each L2 then keeps half-rows of twice as many hot columns,
-    // which outweighs reading the CSR arrays twice) provided both halves are whole 128-byte lines;
-    // wider rows run as 128-float slices.  ISP_SPMM_LPG overrides the choice for tuning.
-    const bool large = av.nnz >= (int64_t)8 << 20;
-    int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : 32);
-    if (large && d > 64 && d <= 128 && d % 64 == 0) lpg = 16;
-    if (const char* e = getenv("ISP_SPMM_LPG")) {
-      const int v = atoi(e);
-      if (v == 4 || v == 8 || v == 16 || v == 32 || v == 64) lpg = v;
-    }
-    isp_status st = ISP_OK;
-    for (int k_base = 0; k_base < d && st == ISP_OK; k_base += ISP_PARTIAL_TILE) {
-      const int w = (d - k_base < ISP_PARTIAL_TILE) ? d - k_base : ISP_PARTIAL_TILE;
-      const int ns = (w + 4 * lpg - 1) / (4 * lpg);
-      switch (lpg) {
-        case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
-        case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
-        case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
-        case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
-        default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, s); break;
-      }
-    }
-    return st;
+  *done = grouped_ok;
+  if (!grouped_ok) return ISP_OK;
+  // Lanes per group 4 / 8 / 16 / 32 / 64 <-> column slices of 16 / 32 / 64 / 128 / 256 floats.
+  // Measured on R-MAT graphs (2.4 M and 124 M nonzeros, d = 8..256): the slice that just covers
+  // the row wins up to d = 128; on large graphs two 64-float slices per 128-float row win
+  // (dealt to alternating XCDs, each L2 then keeps half-rows of twice as many hot columns,
+  // which outweighs reading the CSR arrays twice) provided both halves are whole 128-byte lines;
+  // wider rows run as 128-float slices.  ISP_SPMM_LPG overrides the choice for tuning.
+  const bool large = av.nnz >= (int64_t)8 << 20;
+  int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : 32);
+  if (large && d > 64 && d <= 128 && d % 64 == 0) lpg = 16;
+  if (const char* e = getenv("ISP_SPMM_LPG")) {
+    const int v = atoi(e);
+    if (v == 4 || v == 8 || v == 16 || v == 32 || v == 64) lpg = v;
   }
+  isp_status st = ISP_OK;
+  for (int k_base = 0; k_base < d && st == ISP_OK; k_base += ISP_PARTIAL_TILE) {
+    const int w = (d - k_base < ISP_PARTIAL_TILE) ? d - k_base : ISP_PARTIAL_TILE;
+    const int ns = (w + 4 * lpg - 1) / (4 * lpg);
+    switch (lpg) {
+      case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
+      case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
+      case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
+      case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
+      default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
+    }
+  }
+  return st;
+}
+
+isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
+                           hipStream_t s) {
+  bool done = false;
+  isp_status st0 = isp_spmm_grouped_launch(A, X, ldx, d, Y, ldy, 0, nullptr, s, &done);
+  if (done || st0 != ISP_OK) return st0;
+  // lanes-over-features layout: the widest vector the width and alignment allow
+  int vec = 1;
+  if (d > 2 * ISP_WAVE && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16)) vec = 4;
+  else if (d > ISP_WAVE && d % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8)) vec = 2;
   isp_status st = ISP_OK;
   int k0 = 0;
   while (k0 < d && st == ISP_OK) {  // column tiles of at most ISP_PARTIAL_TILE floats

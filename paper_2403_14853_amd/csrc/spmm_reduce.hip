@@ -1,7 +1,8 @@
 // Sparse-dense product with the other reductions the paper's matmul offers (Section 3.4, 3.5):
 // mean, min, max - and their backward through the cached transpose.  As in the paper, only the
-// sum reduction has the tuned kernels; these run on the generic row-streaming skeleton (one
-// nonzero per wave iteration, any width and alignment).
+// sum reduction has its own tuned kernels; mean reuses them when the operands qualify (rows
+// divided by their length), min / max and everything unaligned run on the generic row-streaming
+// skeleton (one nonzero per wave iteration, any width and alignment).
 //   mean : Y[i] = (sum_p a_p x_j) / len_i
 //   min / max : Y[i,k] = min / max_p a_p x_jk (product and comparison in fp32), arg[i,k] = position p of
 //               the first entry attaining it; empty row -> 0 and -1
@@ -238,7 +239,12 @@ isp_status select_bwd(const isp_csr* A, const float* dY, int64_t lddy, const int
 
 isp_status isp_spmm_reduce_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
                                   int64_t ldy, int32_t* arg, hipStream_t s) {
-  if (reduce == R_MEAN) return fwd_all<R_MEAN>(A, X, ldx, d, Y, ldy, arg, s);
+  if (reduce == R_MEAN) {  // the tuned kernel divides each finished row by its length
+    bool done = false;
+    const isp_status st = isp_spmm_grouped_launch(A, X, ldx, d, Y, ldy, 1, nullptr, s, &done);
+    if (done || st != ISP_OK) return st;
+    return fwd_all<R_MEAN>(A, X, ldx, d, Y, ldy, arg, s);
+  }
   if (reduce == R_MIN) return fwd_all<R_MIN>(A, X, ldx, d, Y, ldy, arg, s);
   return fwd_all<R_MAX>(A, X, ldx, d, Y, ldy, arg, s);
 }
@@ -246,6 +252,11 @@ isp_status isp_spmm_reduce_launch(const isp_csr* A, const float* X, int64_t ldx,
 isp_status isp_spmm_reduce_bwd_launch(const isp_csr* A, const float* dY, int64_t lddy, int32_t d, int reduce,
                                       const int32_t* arg, float* dX, int64_t lddx, hipStream_t s) {
   const isp_csr* At = A->At;
+  if (reduce == R_MEAN) {  // the tuned kernel on A^T with every entry divided by its source row's length
+    bool done = false;
+    const isp_status st = isp_spmm_grouped_launch(At, dY, lddy, d, dX, lddx, 2, A->v.indptr, s, &done);
+    if (done || st != ISP_OK) return st;
+  }
   const bool hv = At->v.values != nullptr;
   const bool v2 = d % 2 == 0 && lddy % 2 == 0 && lddx % 2 == 0 && aligned(dY, 8) && aligned(dX, 8) &&
                   aligned(arg, 8) && d > ISP_WAVE;
