@@ -86,7 +86,7 @@ isp_status launch_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int
 // instruction.  Slice s of tile k_base covers columns [k_base + s * 4 * LPG, +4 * LPG).
 // ADDR32: every byte offset into X fits 32 bits and both factors of column * row-pitch fit 24 bits, so
 // the gather address is one full-rate 24-bit multiply-add on top of a scalar base pointer.
-template <int LPG, bool HAS_VAL, bool ADDR32>
+template <int LPG, bool HAS_VAL, bool ADDR32, int VEC = 4>
 __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 4))) k_spmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                          const int32_t* __restrict__ indices,
                                                          const float* __restrict__ values,
@@ -110,7 +110,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
                                              mean_mode == 2 ? src_indptr : nullptr);  // multiple of U
 
   const int g = lane / LPG, q = lane % LPG;
-  const int col = k_base + (slice * LPG + q) * 4;
+  const int col = k_base + (slice * LPG + q) * VEC;
   const bool lane_on = col < d;
   // lanes without a live entry (row tails, null steps, columns past d) still issue their gather -
   // from row 0 of X - so that every step is exactly one load per lane (exact wait counts, no
@@ -121,25 +121,27 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   float* __restrict__ out = it.is_seg ? A.partials + (col - k_base) : Y + col;
   const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
   int row = it.row;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  float acc[VEC];
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
 
   auto finish_row = [&]() {
 #pragma unroll
-    for (int v = 0; v < 4; ++v) acc[v] = group_sum<LPG>(acc[v]);
+    for (int v = 0; v < VEC; ++v) acc[v] = group_sum<LPG>(acc[v]);
     if (mean_mode == 1 && !it.is_seg) {  // hub segments keep plain partial sums; their fix-up divides
       const int r_local = row - it.row;
       const int len = (int)L.rp[r_local + 1] - (int)L.rp[r_local];
       const float inv = len > 0 ? 1.f / (float)len : 0.f;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc[v] *= inv;
+      for (int v = 0; v < VEC; ++v) acc[v] *= inv;
     }
-    if (g == 0 && lane_on) store_vec<4>(out + (int64_t)row * ldo, acc);
+    if (g == 0 && lane_on) store_vec<VEC>(out + (int64_t)row * ldo, acc);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) acc[v] = 0.f;
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
     ++row;
   };
   // descriptors of U consecutive steps = one 16-byte LDS read
-  auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][4], float (&a)[U]) {
+  auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][VEC], float (&a)[U]) {
     const uint4 pk = *reinterpret_cast<const uint4*>(L.step + s0);
     const unsigned raw[4] = {pk.x, pk.y, pk.z, pk.w};
     int2 e[U];
@@ -155,18 +157,18 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
       const int cj = act ? e[u].x : 0;
       if constexpr (ADDR32) {
         const unsigned off = __umul24((unsigned)cj, pitch_byte) + lane_byte;
-        load_vec<4>(reinterpret_cast<const float*>(reinterpret_cast<const char*>(X) + off), x[u]);
+        load_vec<VEC>(reinterpret_cast<const float*>(reinterpret_cast<const char*>(X) + off), x[u]);
       } else {
-        load_vec<4>(xcol + (int64_t)cj * ldx, x[u]);
+        load_vec<VEC>(xcol + (int64_t)cj * ldx, x[u]);
       }
     }
   };
-  auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][4], const float (&a)[U]) {
+  auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][VEC], const float (&a)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (g < gs_cnt(dsc[u]) && lane_on) {  // divergent on purpose: dead lanes skip the FMAs, nothing to zero
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc[v] = fmaf(a[u], x[u][v], acc[v]);
+        for (int v = 0; v < VEC; ++v) acc[v] = fmaf(a[u], x[u][v], acc[v]);
       }
       if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
     }
@@ -175,7 +177,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const int n_groups = n_steps / U;
   if (n_groups == 0) return;
   unsigned dA[U], dB[U];
-  float xA[U][4], xB[U][4], aA[U], aB[U];
+  float xA[U][VEC], xB[U][VEC], aA[U], aB[U];
   issue(0, dA, xA, aA);
   int gi = 0;
   while (gi + 2 < n_groups) {  // steady state: the next group's gathers are in flight while one is consumed
@@ -194,7 +196,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   }
 }
 
-template <int LPG>
+template <int LPG, int VEC = 4>
 isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, int k_base, int n_slices, float* Y,
                           int64_t ldy, int mean_mode, const int64_t* src_indptr, hipStream_t s) {
   const isp_view& v = A->v;
@@ -204,17 +206,21 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
     const bool a32 = v.n_cols < (1 << 24) && ldx * 4 < (1 << 24) &&
                      ((uint64_t)v.n_cols * (uint64_t)ldx + (uint64_t)d) * 4u < ((uint64_t)1 << 32);
 #define ISP_GO(HV, A32) \
-  k_spmm_grouped<LPG, HV, A32><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy, \
+  k_spmm_grouped<LPG, HV, A32, VEC><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy, \
                                                        mean_mode, src_indptr)
-    if (v.values) { if (a32) ISP_GO(true, true); else ISP_GO(true, false); }
-    else { if (a32) ISP_GO(false, true); else ISP_GO(false, false); }
+    if constexpr (VEC < 4) {  // narrow lanes are only dispatched with 32-bit addressing
+      if (v.values) ISP_GO(true, true); else ISP_GO(false, true);
+    } else {
+      if (v.values) { if (a32) ISP_GO(true, true); else ISP_GO(true, false); }
+      else { if (a32) ISP_GO(false, true); else ISP_GO(false, false); }
+    }
 #undef ISP_GO
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
     const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    if (mean_mode == 1) k_spmm_fixup_mean<<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
-    else k_spmm_fixup<4, 1><<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
+    if (mean_mode == 1) k_spmm_fixup_mean<<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);  // VEC = 4 only
+    else k_spmm_fixup<VEC, 4 / VEC><<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   return ISP_OK;
@@ -229,13 +235,39 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
                                    int mean_mode, const int64_t* src_indptr, hipStream_t s, bool* done) {
   const isp_view& av = A->v;
+  // Lane width: float4 when width, pitch and pointers allow; float2 / float lanes otherwise (any d),
+  // those two only with 32-bit addressing and for the plain sum.
+  int vec = 1;
+  if (d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16)) vec = 4;
+  else if (d % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8)) vec = 2;
+  const bool a32 = av.n_cols < (1 << 24) && ldx * 4 < (1 << 24) &&
+                   ((uint64_t)av.n_cols * (uint64_t)ldx + (uint64_t)d) * 4u < ((uint64_t)1 << 32);
   // (a matrix without entries never reads X, which may then be absent: the generic path handles it)
-  const bool grouped_ok = av.nnz > 0 && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16) &&
-                          A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + av.hub_t <= GS_MAX_ENT &&
-                          av.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
+  const bool grouped_ok = av.nnz > 0 && (vec == 4 || (a32 && mean_mode == 0)) && A->info.block_cost <= GS_MAX_ROWS &&
+                          A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT &&
+                          !getenv("ISP_NO_GROUPED");
   *done = grouped_ok;
   if (!grouped_ok) return ISP_OK;
-  // Lanes per group 4 / 8 / 16 / 32 / 64 <-> column slices of 16 / 32 / 64 / 128 / 256 floats.
+  if (vec < 4) {
+    // narrow lanes: the smallest group that covers the row, at most 64 * vec columns per slice
+    isp_status st = ISP_OK;
+    for (int k_base = 0; k_base < d && st == ISP_OK; k_base += ISP_PARTIAL_TILE) {
+      const int w = (d - k_base < ISP_PARTIAL_TILE) ? d - k_base : ISP_PARTIAL_TILE;
+      const int lpg = w <= 16 * vec ? 16 : (w <= 32 * vec ? 32 : 64);
+      const int ns = (w + lpg * vec - 1) / (lpg * vec);
+      if (vec == 2) {
+        if (lpg == 16) st = launch_grouped<16, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
+        else if (lpg == 32) st = launch_grouped<32, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
+        else st = launch_grouped<64, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
+      } else {
+        if (lpg == 16) st = launch_grouped<16, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
+        else if (lpg == 32) st = launch_grouped<32, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
+        else st = launch_grouped<64, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
+      }
+    }
+    return st;
+  }
+  // float4 lanes: 4 / 8 / 16 / 32 / 64 lanes per group <-> column slices of 16 / 32 / 64 / 128 / 256 floats.
   // Measured on R-MAT graphs (2.4 M and 124 M nonzeros, d = 8..256): the slice that just covers
   // the row wins up to d = 128; on large graphs two 64-float slices per 128-float row win
   // (dealt to alternating XCDs, each L2 then keeps half-rows of twice as many hot columns,
