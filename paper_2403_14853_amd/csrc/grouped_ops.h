@@ -5,6 +5,7 @@
 // x_i / g_i for FusedMM) is re-read with every step instead of being kept across steps: it is an
 // L1 hit after a row's first step and keeps the main loop free of row-change stalls.
 #pragma once
+#include <type_traits>
 #include "group_stream.h"
 
 namespace isp_dev {
@@ -17,7 +18,9 @@ template <class P, int LPG, bool HAS_VAL>
 __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                           const int32_t* __restrict__ indices, const float* __restrict__ values,
                                           const typename P::args& pa, int d, float* __restrict__ Y, int64_t ldy,
-                                          gs_lds& lds) {
+                                          gs_lds& lds, int k_lo = 0) {
+  // k_lo: first feature column of this pass (only the per-entry policies run in column windows;
+  // their partial dot products are then added up across passes)
   constexpr int G = ISP_WAVE / LPG;
   constexpr int NSRC = P::NSRC, NROW = P::NROW;
   constexpr int U = 4;  // steps in flight per buffer; two buffers
@@ -31,7 +34,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   const int n_steps = gs_prepare<G, HAS_VAL>(it, indptr, indices, values, L, lane);
 
   const int g = lane / LPG, q = lane % LPG;
-  const int col = q * 4;
+  const int col = k_lo + q * 4;
   const bool lane_on = col < d;
   const int coff = lane_on ? col : 0;
   float* __restrict__ out = it.is_seg ? A.partials + col : Y + col;
@@ -57,65 +60,94 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
     for (int v = 0; v < 4; ++v) acc[v] = 0.f;
     ++row;
   };
-  auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][NSRC][4], float (&r)[U][NROW][4], float (&a)[U]) {
-    int2 e[U];
-    int srow[U];
+  // SEG (a hub segment: one matrix row for the whole item): the row operand is loaded once and stays in
+  // registers.  Row blocks re-read it with every step, which keeps their loop free of row-change stalls.
+  auto run = [&](auto seg_tag) {
+    constexpr bool SEG = decltype(seg_tag)::value;
+    constexpr int NR = SEG ? 0 : NROW;  // per-step row-operand registers
+    float rS[NROW][4];
+    if constexpr (SEG) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      dsc[u] = L.step[s0 + u];
-      e[u] = L.ent[gs_off(dsc[u]) + g];
-      srow[u] = irow;
-      irow += (int)((dsc[u] >> 15) & 1u);  // a row end moves the following steps to the next row
+      for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + (int64_t)irow * pa.ldr[k] + coff, rS[k]);
     }
+    auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][NSRC][4], float (&r)[U][NR + 1][4], float (&a)[U]) {
+      int2 e[U];
+      int srow[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bool act = g < gs_cnt(dsc[u]) && lane_on;
-      a[u] = __int_as_float(e[u].y);
-      const int64_t cj = act ? e[u].x : 0;  // dead lanes gather row 0; what they fetch is never used
-#pragma unroll
-      for (int k = 0; k < NSRC; ++k) load_vec<4>(pa.src[k] + cj * pa.lds_[k] + coff, x[u][k]);
-      const int64_t ri = srow[u] < A.n_rows ? srow[u] : 0;  // null steps after the last row
-#pragma unroll
-      for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + ri * pa.ldr[k] + coff, r[u][k]);
-    }
-  };
-  auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][NSRC][4], const float (&r)[U][NROW][4],
-                     const float (&a)[U]) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      // The policies mask the per-lane partial dot products with lane_on (columns past d) and
-      // accumulate only in live lanes, so nothing fetched by a dead lane reaches a result.
-      const bool live = g < gs_cnt(dsc[u]);
-      if constexpr (P::PER_ENTRY) {
-        // one output per stored entry: lane 0 of every live group writes its entry's value
-        const float val = P::template entry<LPG>(a[u], x[u], r[u], lane_on);
-        if (live && q == 0) pa.out_entry[it.p + gs_off(dsc[u]) + g] = val;
-      } else {
-        P::template edge<LPG>(pa, a[u], x[u], r[u], acc, lane_on, live && lane_on);
-        if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
+      for (int u = 0; u < U; ++u) {
+        dsc[u] = L.step[s0 + u];
+        e[u] = L.ent[gs_off(dsc[u]) + g];
+        srow[u] = irow;
+        irow += (int)((dsc[u] >> 15) & 1u);  // a row end moves the following steps to the next row
       }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const bool act = g < gs_cnt(dsc[u]) && lane_on;
+        a[u] = __int_as_float(e[u].y);
+        const int64_t cj = act ? e[u].x : 0;  // dead lanes gather row 0; what they fetch is never used
+#pragma unroll
+        for (int k = 0; k < NSRC; ++k) load_vec<4>(pa.src[k] + cj * pa.lds_[k] + coff, x[u][k]);
+        if constexpr (!SEG) {
+          const int64_t ri = srow[u] < A.n_rows ? srow[u] : 0;  // null steps after the last row
+#pragma unroll
+          for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + ri * pa.ldr[k] + coff, r[u][k]);
+        }
+      }
+    };
+    auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][NSRC][4], const float (&r)[U][NR + 1][4],
+                       const float (&a)[U]) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        // The policies mask the per-lane partial dot products with lane_on (columns past d) and
+        // accumulate only in live lanes, so nothing fetched by a dead lane reaches a result.
+        const bool live = g < gs_cnt(dsc[u]);
+        float rr[NROW][4];
+#pragma unroll
+        for (int k = 0; k < NROW; ++k)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) rr[k][v] = SEG ? rS[k][v] : r[u][k < NR ? k : 0][v];
+        if constexpr (P::PER_ENTRY) {
+          // one output per stored entry, parked in the entry's LDS slot (its value has been read by
+          // the step's issue) and written out in one coalesced sweep when the item is done
+          const float val = P::template entry<LPG>(a[u], x[u], rr, lane_on);
+          if (live && q == 0) L.ent[gs_off(dsc[u]) + g].y = __float_as_int(val);
+        } else {
+          P::template edge<LPG>(pa, a[u], x[u], rr, acc, lane_on, live && lane_on);
+          if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
+        }
+      }
+    };
+
+    const int n_groups = n_steps / U;
+    unsigned dA[U], dB[U];
+    float xA[U][NSRC][4], xB[U][NSRC][4], rA[U][NR + 1][4], rB[U][NR + 1][4], aA[U], aB[U];
+    issue(0, dA, xA, rA, aA);
+    int gi = 0;
+    while (gi + 2 < n_groups) {
+      issue((gi + 1) * U, dB, xB, rB, aB);
+      consume(dA, xA, rA, aA);
+      issue((gi + 2) * U, dA, xA, rA, aA);
+      consume(dB, xB, rB, aB);
+      gi += 2;
+    }
+    if (gi + 1 < n_groups) {
+      issue((gi + 1) * U, dB, xB, rB, aB);
+      consume(dA, xA, rA, aA);
+      consume(dB, xB, rB, aB);
+    } else {
+      consume(dA, xA, rA, aA);
     }
   };
-
-  const int n_groups = n_steps / U;
-  if (n_groups == 0) return;
-  unsigned dA[U], dB[U];
-  float xA[U][NSRC][4], xB[U][NSRC][4], rA[U][NROW][4], rB[U][NROW][4], aA[U], aB[U];
-  issue(0, dA, xA, rA, aA);
-  int gi = 0;
-  while (gi + 2 < n_groups) {
-    issue((gi + 1) * U, dB, xB, rB, aB);
-    consume(dA, xA, rA, aA);
-    issue((gi + 2) * U, dA, xA, rA, aA);
-    consume(dB, xB, rB, aB);
-    gi += 2;
-  }
-  if (gi + 1 < n_groups) {
-    issue((gi + 1) * U, dB, xB, rB, aB);
-    consume(dA, xA, rA, aA);
-    consume(dB, xB, rB, aB);
-  } else {
-    consume(dA, xA, rA, aA);
+  if (n_steps == 0) return;
+  if (it.is_seg) run(std::true_type{}); else run(std::false_type{});
+  if constexpr (P::PER_ENTRY) {
+    wave_lds_sync();
+    const int n_ent = (int)(it.p_end - it.p);
+    for (int i = lane; i < n_ent; i += ISP_WAVE) {
+      float* o = pa.out_entry + it.p + i;
+      const float val = __int_as_float(L.ent[i].y);
+      *o = P::ADD ? *o + val : val;
+    }
   }
 }
 

@@ -91,10 +91,11 @@ __global__ void __launch_bounds__(ISP_WG) k_sddmm(isp_view A, const int64_t* __r
 }
 
 // ---- grouped fast path (d <= 256, 16-byte aligned operands) -------------------------------------
-template <bool SCALE>
+// ADD: this pass covers a window of the feature columns and adds its partial dot product to out.
+template <bool SCALE, bool ADD_ = false>
 struct sddmm_policy {
   static constexpr int NSRC = 1, NROW = 1;
-  static constexpr bool PER_ENTRY = true, ACCUMULATE = false;
+  static constexpr bool PER_ENTRY = true, ACCUMULATE = false, ADD = ADD_;
   struct args { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
   template <int LPG>
   __device__ static inline float entry(float a, const float (&x)[1][4], const float (&r)[1][4], bool lane_on) {
@@ -103,29 +104,32 @@ struct sddmm_policy {
   }
 };
 
-template <int LPG, bool SCALE>
+template <int LPG, bool SCALE, bool ADD>
 __global__ void __launch_bounds__(ISP_WG) k_sddmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                           const int32_t* __restrict__ indices,
                                                           const float* __restrict__ values,
-                                                          typename sddmm_policy<SCALE>::args pa, int d) {
+                                                          typename sddmm_policy<SCALE, ADD>::args pa, int d, int k_lo) {
   __shared__ gs_lds lds;
-  fused_grouped_item<sddmm_policy<SCALE>, LPG, SCALE>(A, indptr, indices, values, pa, d, nullptr, 0, lds);
+  fused_grouped_item<sddmm_policy<SCALE, ADD>, LPG, SCALE>(A, indptr, indices, values, pa, d, nullptr, 0, lds, k_lo);
 }
 
+// One pass over the feature columns [k_lo, d_hi) (d_hi - k_lo <= 4 * LPG); add: accumulate into out.
 template <int LPG>
-isp_status launch_grouped(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv, int d,
-                          bool scale, float* out, hipStream_t s) {
+isp_status launch_grouped(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv, int k_lo,
+                          int d_hi, bool add, bool scale, float* out, hipStream_t s) {
   const isp_view& v = A->v;
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items == 0 || v.nnz == 0) return ISP_OK;
   const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-  if (scale && v.values) {
-    sddmm_policy<true>::args pa{{V}, {ldv}, {U}, {ldu}, out};
-    k_sddmm_grouped<LPG, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d);
-  } else {
-    sddmm_policy<false>::args pa{{V}, {ldv}, {U}, {ldu}, out};
-    k_sddmm_grouped<LPG, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d);
-  }
+  const bool sc = scale && v.values;
+#define ISP_GO(SC, AD)                                                                                  \
+  do {                                                                                                  \
+    typename sddmm_policy<SC, AD>::args pa{{V}, {ldv}, {U}, {ldu}, out};                                \
+    k_sddmm_grouped<LPG, SC, AD><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d_hi, k_lo); \
+  } while (0)
+  if (sc) { if (add) ISP_GO(true, true); else ISP_GO(true, false); }
+  else { if (add) ISP_GO(false, true); else ISP_GO(false, false); }
+#undef ISP_GO
   ISP_LAUNCH_CHECK();
   return ISP_OK;
 }
@@ -159,10 +163,18 @@ isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const
                           A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT &&
                           !getenv("ISP_NO_GROUPED");
   if (grouped_ok) {
-    if (d <= 32) return launch_grouped<8>(A, U, ldu, V, ldv, d, scale, out, s);
-    if (d <= 64) return launch_grouped<16>(A, U, ldu, V, ldv, d, scale, out, s);
-    if (d <= 128) return launch_grouped<32>(A, U, ldu, V, ldv, d, scale, out, s);
-    return launch_grouped<64>(A, U, ldu, V, ldv, d, scale, out, s);
+    // Large graphs, 128-wide rows: two passes over 64-column halves, the second adding its partial dot
+    // products.  Every L2 then holds half-rows of twice as many hot columns (the same effect as the two
+    // column slices of SpMM), which outweighs staging the CSR arrays twice and one more sweep over out.
+    if (av.nnz >= ((int64_t)8 << 20) && d == 2 * ISP_WAVE && !getenv("ISP_SDDMM_ONE_PASS")) {
+      isp_status st = launch_grouped<16>(A, U, ldu, V, ldv, 0, ISP_WAVE, false, scale, out, s);
+      if (st != ISP_OK) return st;
+      return launch_grouped<16>(A, U, ldu, V, ldv, ISP_WAVE, d, true, scale, out, s);
+    }
+    if (d <= 32) return launch_grouped<8>(A, U, ldu, V, ldv, 0, d, false, scale, out, s);
+    if (d <= 64) return launch_grouped<16>(A, U, ldu, V, ldv, 0, d, false, scale, out, s);
+    if (d <= 128) return launch_grouped<32>(A, U, ldu, V, ldv, 0, d, false, scale, out, s);
+    return launch_grouped<64>(A, U, ldu, V, ldv, 0, d, false, scale, out, s);
   }
   int vec = 1;
   if (d > 2 * ISP_WAVE && d % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 && aligned(U, 16) && aligned(V, 16)) vec = 4;
