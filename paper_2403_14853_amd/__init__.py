@@ -6,6 +6,7 @@ used for device memory and streams.  There is no CPU fallback: without the compi
 the import of :mod:`paper_2403_14853_amd.binding` fails loudly.
 """
 from .binding import (  # noqa: F401
-    CSR, IspError, lib_path, load_library, csr_build, csr_transpose_cached, spmm, sddmm, fusedmm,
+    CSR, IspError, lib_path, load_library, csr_build, csr_build_workspace, csr_transpose_cached,
+    csr_transpose_workspace, spmm, sddmm, fusedmm,
     fusedmm_backward, spmm_reduce, spmm_reduce_backward, EXPORTED_SYMBOLS,
 )

@@ -171,8 +171,33 @@ def ctypes_copy(dst_ptr: int, src_ptr: int, nbytes: int):
         raise RuntimeError("hipMemcpy failed with %d" % rc)
 
 
-def csr_build(indptr, indices, values=None, n_cols=None, *, trusted=False, stream=None) -> CSR:
-    """isp_csr_build on torch CUDA tensors (indptr int64, indices int32, values fp32 or None)."""
+def csr_build_workspace(n_rows, n_cols, nnz) -> int:
+    """isp_csr_build_workspace: bytes of device workspace isp_csr_build needs."""
+    need = ctypes.c_size_t()
+    _check(load_library().isp_csr_build_workspace(int(n_rows), int(n_cols), int(nnz), ctypes.byref(need)))
+    return int(need.value)
+
+
+def csr_transpose_workspace(A: "CSR") -> int:
+    """isp_csr_transpose_workspace: bytes of device workspace the first transpose of A needs."""
+    need = ctypes.c_size_t()
+    _check(load_library().isp_csr_transpose_workspace(A._h, ctypes.byref(need)))
+    return int(need.value)
+
+
+def _own_workspace(workspace, nbytes, device):
+    """The caller's uint8 CUDA tensor when given (checked for size), else a fresh allocation."""
+    if workspace is None:
+        return _workspace(nbytes, device)
+    import torch
+    assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()
+    assert workspace.numel() >= nbytes, "workspace too small: %d < %d bytes" % (workspace.numel(), nbytes)
+    return workspace
+
+
+def csr_build(indptr, indices, values=None, n_cols=None, *, trusted=False, stream=None, workspace=None) -> CSR:
+    """isp_csr_build on torch CUDA tensors (indptr int64, indices int32, values fp32 or None).
+    workspace: optional uint8 CUDA tensor of at least csr_build_workspace() bytes (kept alive by the handle)."""
     import torch
     lib = load_library()
     assert indptr.is_cuda and indptr.dtype == torch.int64 and indptr.is_contiguous()
@@ -183,15 +208,16 @@ def csr_build(indptr, indices, values=None, n_cols=None, *, trusted=False, strea
     n_cols = n_rows if n_cols is None else int(n_cols)
     need = ctypes.c_size_t()
     _check(lib.isp_csr_build_workspace(n_rows, n_cols, nnz, ctypes.byref(need)))
-    ws = _workspace(need.value, indptr.device)
+    ws = _own_workspace(workspace, need.value, indptr.device)
     h = ctypes.c_void_p()
     _check(lib.isp_csr_build(n_rows, n_cols, nnz, _dptr(indptr), _dptr(indices), _dptr(values), _dptr(ws),
                              ws.numel(), ISP_TRUSTED if trusted else 0, _stream(stream), ctypes.byref(h)))
     return CSR(h, n_rows, n_cols, nnz, [indptr, indices, values, ws])
 
 
-def csr_transpose_cached(A: CSR, *, stream=None):
-    """isp_csr_transpose_cached.  Returns (At, was_cached)."""
+def csr_transpose_cached(A: CSR, *, stream=None, workspace=None):
+    """isp_csr_transpose_cached.  Returns (At, was_cached).
+    workspace: optional uint8 CUDA tensor of at least csr_transpose_workspace(A) bytes, used on a cache miss."""
     lib = load_library()
     At_h = ctypes.c_void_p()
     was = ctypes.c_int(0)
@@ -201,7 +227,7 @@ def csr_transpose_cached(A: CSR, *, stream=None):
         return A._At, bool(was.value)
     need = ctypes.c_size_t()
     _check(lib.isp_csr_transpose_workspace(A._h, ctypes.byref(need)))
-    ws = _workspace(need.value, A._keep[0].device)
+    ws = _own_workspace(workspace, need.value, A._keep[0].device)
     _check(lib.isp_csr_transpose_cached(A._h, _dptr(ws), ws.numel(), _stream(stream), ctypes.byref(At_h),
                                         ctypes.byref(was)))
     A._keep.append(ws)

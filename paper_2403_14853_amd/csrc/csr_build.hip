@@ -3,9 +3,13 @@
 // Rows are classed by degree (0 | 1..4 | 5..32 | 33..hub_t | hub).  Short rows are grouped
 // into contiguous row blocks of about block_cost units, one unit per nonzero plus one per row
 // (a row's output write costs about as much as one gathered input row).  Hub rows
-// (degree > hub_t) never share a block; each is cut into segments of seg_len nonzeros whose
-// partial sums are combined later in a fixed order.  Everything here is integer work and runs
-// once per graph (balanced scheduling: paper Section 1(b); CSR operand: Section 3.5).
+// (degree > hub_t) never share a block; each is cut into segments of at most seg_len nonzeros whose
+// partial sums are combined later in a fixed order.  A hub row is cut first where its (sorted) columns
+// cross the boundaries of column bands, so that a segment gathers dense rows from one band only, and the
+// segments are scheduled band by band: the whole chip then works on one band of the dense operand at a
+// time and the L2 caches hold that band's frequently used rows instead of a sample of all of them.
+// Everything here is integer work and runs once per graph (balanced scheduling: paper Section 1(b); CSR
+// operand: Section 3.5).
 #include <stdlib.h>
 #include <new>
 #include "isp_internal.h"
@@ -22,7 +26,11 @@ struct build_counters {
 
 struct partition_params {
   int block_cost, hub_t, seg_len;
+  int bands;      // column bands of the finest cut (a power of two); 1 = no band cuts
+  int min_piece;  // a hub row is cut into at most degree / min_piece bands
 };
+
+constexpr int MAX_BANDS = 32;
 
 int env_int(const char* name, int dflt, int lo, int hi) {
   const char* s = getenv(name);
@@ -41,11 +49,48 @@ partition_params get_params() {
   p.block_cost = env_int("ISP_BLOCK_COST", 256, 16, 256);
   p.hub_t = env_int("ISP_HUB_THRESHOLD", 512, 8, 512);
   p.seg_len = env_int("ISP_SEGMENT_LEN", 512, 8, 768);
+  int b = env_int("ISP_BANDS", 16, 1, MAX_BANDS);
+  while (b & (b - 1)) b &= b - 1;  // round down to a power of two
+  p.bands = b;
+  // (the lower limit bounds the number of segments, hence the partial-sum rows the workspace must hold)
+  const int mp_lo = p.seg_len / 8 > 4 ? p.seg_len / 8 : 4;
+  p.min_piece = env_int("ISP_MIN_PIECE", p.seg_len / 2 > mp_lo ? p.seg_len / 2 : mp_lo, mp_lo, 1 << 20);
   return p;
 }
 
 __global__ void k_zero_counters(build_counters* c) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *c = build_counters{};
+}
+
+// Pieces of a hub row: its entries [a, b) cut where the columns cross band boundaries.  A row of degree
+// deg is cut into br = the largest power of two <= min(bands, deg / min_piece) coarse bands, each made of
+// bands / br fine bands of width ceil(n_cols / bands).  The cut positions are found by binary search, which
+// assumes ascending columns; on a row that is not sorted they are still valid cut positions (monotone, inside
+// the row), so only the scheduling benefit is lost, never correctness.  f(fine band, first, last) is called
+// for every non-empty piece, in order.
+template <class F>
+__device__ inline void for_each_piece(const int32_t* __restrict__ indices, int64_t a, int64_t b, int64_t n_cols,
+                                      const partition_params& pp, F f) {
+  const int64_t deg = b - a;
+  int br = 1;
+  while (br * 2 <= pp.bands && (int64_t)(br * 2) * pp.min_piece <= deg) br *= 2;
+  const int64_t bw = (n_cols + pp.bands - 1) / pp.bands;
+  const int step = pp.bands / br;
+  int64_t first = a;
+  for (int j = 1; j <= br; ++j) {
+    int64_t last = b;
+    if (j < br) {
+      const int64_t target = (int64_t)j * step * bw;
+      int64_t lo = first, hi = b;  // first position in [first, b) whose column is >= target
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)indices[mid] < target) lo = mid + 1; else hi = mid;
+      }
+      last = lo;
+    }
+    if (last > first) f((j - 1) * step, first, last);
+    first = last;
+  }
 }
 
 __device__ inline int degree_bin(long long deg, int hub_t) {
@@ -58,8 +103,9 @@ __device__ inline int degree_bin(long long deg, int hub_t) {
 
 // Per row: degree, class, cost, segment count; indptr checks.  Grid-stride; the class histogram,
 // maximum degree and segment total are reduced per workgroup before a handful of integer atomics.
-__global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ indptr, int64_t n_rows, int64_t nnz,
-                                                  partition_params pp, int32_t* __restrict__ cost,
+__global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ indptr,
+                                                  const int32_t* __restrict__ indices, int64_t n_rows, int64_t n_cols,
+                                                  int64_t nnz, partition_params pp, int32_t* __restrict__ cost,
                                                   int32_t* __restrict__ hubflag, int32_t* __restrict__ nseg,
                                                   build_counters* __restrict__ ctr) {
   __shared__ unsigned long long s_rows[5], s_nnz[5], s_max;
@@ -74,7 +120,11 @@ __global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ in
     long long deg = b - a;
     if (deg < 0 || a < 0 || b > nnz || (i == 0 && a != 0) || (i == n_rows - 1 && b != nnz)) { my_err = 1; deg = 0; }
     const bool hub = deg > pp.hub_t;
-    const int ns = hub ? (int)((deg + pp.seg_len - 1) / pp.seg_len) : 0;
+    int ns = 0;
+    if (hub)
+      for_each_piece(indices, a, b, n_cols, pp, [&](int, int64_t first, int64_t last) {
+        ns += (int)((last - first + pp.seg_len - 1) / pp.seg_len);
+      });
     cost[i] = hub ? 0 : (int32_t)deg + 1;
     hubflag[i] = hub ? 1 : 0;
     nseg[i] = ns;
@@ -140,12 +190,15 @@ __global__ void __launch_bounds__(256) k_mark_balanced(const int64_t* __restrict
   if (lo < n_rows) mark[lo] = 1;
 }
 
-__global__ void __launch_bounds__(256) k_compact(const int32_t* __restrict__ mark, const int32_t* __restrict__ mpos,
+__global__ void __launch_bounds__(256) k_compact(const int64_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+                                                 int64_t n_cols, partition_params pp,
+                                                 const int32_t* __restrict__ mark, const int32_t* __restrict__ mpos,
                                                  const int32_t* __restrict__ hubflag, const int32_t* __restrict__ hpos,
-                                                 const int32_t* __restrict__ nseg, const int32_t* __restrict__ segbase,
+                                                 const int32_t* __restrict__ segbase,
                                                  int64_t n_rows, int32_t* __restrict__ blk_row,
                                                  int32_t* __restrict__ hub_rows, int32_t* __restrict__ hub_seg_ptr,
-                                                 int32_t* __restrict__ seg_hub, build_counters* __restrict__ ctr,
+                                                 int32_t* __restrict__ seg_hub, int32_t* __restrict__ seg_begin,
+                                                 int32_t* __restrict__ seg_key, build_counters* __restrict__ ctr,
                                                  int64_t max_blocks, int64_t max_hub, int64_t max_seg) {
   // The bounds only bite for a malformed indptr (the host then reports ISP_EBADCSR); they keep
   // every write inside the workspace in that case too.
@@ -160,18 +213,56 @@ __global__ void __launch_bounds__(256) k_compact(const int32_t* __restrict__ mar
   if (i >= n_rows) return;
   if (mark[i] && mpos[i] < max_blocks) blk_row[mpos[i]] = (int32_t)i;
   if (hubflag[i]) {
-    const int h = hpos[i], s0 = segbase[i], ns = nseg[i];
+    const int h = hpos[i], s0 = segbase[i];
     if (h < max_hub) {
       hub_rows[h] = (int32_t)i;
       hub_seg_ptr[h] = s0;
     }
-    for (int s = 0; s < ns && s0 + s < max_seg; ++s) seg_hub[s0 + s] = h;
+    // the row's segments, in order of position: piece by piece, each piece in runs of seg_len
+    int64_t s = s0;
+    for_each_piece(indices, indptr[i], indptr[i + 1], n_cols, pp, [&](int fine, int64_t first, int64_t last) {
+      for (int64_t q = first; q < last; q += pp.seg_len, ++s) {
+        if (s >= max_seg) continue;
+        seg_hub[s] = h;
+        seg_begin[s] = (int32_t)q;
+        seg_key[s] = fine;
+      }
+    });
   }
+}
+
+// ---- schedule order of the segments: stable counting sort by band ------------------------------------
+constexpr int SO_TILE = 256;
+
+__global__ void __launch_bounds__(SO_TILE) k_seg_hist(const int32_t* __restrict__ key, int n_seg, int n_tiles,
+                                                      int32_t* __restrict__ table) {
+  __shared__ int hist[MAX_BANDS];
+  if (threadIdx.x < MAX_BANDS) hist[threadIdx.x] = 0;
+  __syncthreads();
+  const int s = blockIdx.x * SO_TILE + threadIdx.x;
+  if (s < n_seg) atomicAdd(&hist[key[s]], 1);
+  __syncthreads();
+  if (threadIdx.x < MAX_BANDS) table[threadIdx.x * n_tiles + blockIdx.x] = hist[threadIdx.x];
+}
+
+__global__ void __launch_bounds__(SO_TILE) k_seg_scatter(const int32_t* __restrict__ key, int n_seg, int n_tiles,
+                                                         const int32_t* __restrict__ table_scanned,
+                                                         int32_t* __restrict__ seg_order) {
+  __shared__ int keys[SO_TILE];
+  const int s = blockIdx.x * SO_TILE + threadIdx.x;
+  const int k = s < n_seg ? key[s] : -1;
+  keys[threadIdx.x] = k;
+  __syncthreads();
+  if (k < 0) return;
+  int rank = 0;  // earlier segments of this tile in the same band
+  for (int t = 0; t < (int)threadIdx.x; ++t) rank += (keys[t] == k);
+  seg_order[table_scanned[k * n_tiles + blockIdx.x] + rank] = s;
 }
 
 struct ws_layout {
   size_t counters, cost, hubflag, nseg, cum_cost, mark, mpos, hpos, segbase, scan_tmp;
-  size_t blk_row, hub_rows, hub_seg_ptr, seg_hub, partials, total;
+  size_t blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin, seg_key, seg_order, so_table, so_scanned, so_tmp;
+  size_t partials, total;
   int64_t max_blocks, max_hub, max_seg;
 };
 
@@ -184,7 +275,9 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
   if (max_hub > n_rows) max_hub = n_rows;
   int64_t max_blocks = n_bal + 2 * max_hub + 2;
   if (max_blocks > n_rows + 1) max_blocks = n_rows + 1;
-  const int64_t max_seg = nnz / pp.seg_len + max_hub + 1;
+  // a row of degree deg has at most deg / min_piece pieces, and a piece of len entries at most
+  // len / seg_len + 1 segments
+  const int64_t max_seg = nnz / pp.seg_len + (pp.bands > 1 ? nnz / pp.min_piece : 0) + max_hub + 1;
   L.max_blocks = max_blocks; L.max_hub = max_hub; L.max_seg = max_seg;
   L.counters = take(sizeof(build_counters));
   L.cost = take((size_t)(n_rows + 1) * 4);
@@ -200,6 +293,13 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
   L.hub_rows = take((size_t)(max_hub + 1) * 4);
   L.hub_seg_ptr = take((size_t)(max_hub + 2) * 4);
   L.seg_hub = take((size_t)(max_seg + 1) * 4);
+  L.seg_begin = take((size_t)(max_seg + 1) * 4);
+  L.seg_key = take((size_t)(max_seg + 1) * 4);
+  L.seg_order = take((size_t)(max_seg + 1) * 4);
+  const int64_t so_tbl = (int64_t)MAX_BANDS * ((max_seg + SO_TILE - 1) / SO_TILE + 1);
+  L.so_table = take((size_t)(so_tbl + 1) * 4);
+  L.so_scanned = take((size_t)(so_tbl + 1) * 4);
+  L.so_tmp = take(isp_scan_tmp_bytes(so_tbl + 1));
   L.partials = take((size_t)(max_seg + 1) * ISP_PARTIAL_TILE * sizeof(float));
   L.total = off;
   return L;
@@ -231,12 +331,16 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   int32_t* hub_rows = (int32_t*)(base + L.hub_rows);
   int32_t* hub_seg_ptr = (int32_t*)(base + L.hub_seg_ptr);
   int32_t* seg_hub = (int32_t*)(base + L.seg_hub);
+  int32_t* seg_begin = (int32_t*)(base + L.seg_begin);
+  int32_t* seg_key = (int32_t*)(base + L.seg_key);
+  int32_t* seg_order = (int32_t*)(base + L.seg_order);
 
   k_zero_counters<<<1, 64, 0, s>>>(ctr);
   ISP_LAUNCH_CHECK();
   const unsigned row_grid = (unsigned)((n_rows + 255) / 256);
   if (n_rows > 0) {
-    k_row_pass<<<row_grid < 2048 ? row_grid : 2048, 256, 0, s>>>(indptr, n_rows, nnz, pp, cost, hubflag, nseg, ctr);
+    k_row_pass<<<row_grid < 2048 ? row_grid : 2048, 256, 0, s>>>(indptr, indices, n_rows, n_cols, nnz, pp, cost,
+                                                                 hubflag, nseg, ctr);
     ISP_LAUNCH_CHECK();
   }
   if (validate && nnz > 0) {
@@ -256,9 +360,9 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   if ((st = isp_scan_i32_to_i32(mark, mpos, n_rows, scan_tmp, s)) != ISP_OK) return st;
   if ((st = isp_scan_i32_to_i32(hubflag, hpos, n_rows, scan_tmp, s)) != ISP_OK) return st;
   if ((st = isp_scan_i32_to_i32(nseg, segbase, n_rows, scan_tmp, s)) != ISP_OK) return st;
-  k_compact<<<row_grid > 0 ? row_grid : 1, 256, 0, s>>>(mark, mpos, hubflag, hpos, nseg, segbase, n_rows, blk_row,
-                                                       hub_rows, hub_seg_ptr, seg_hub, ctr, L.max_blocks,
-                                                       L.max_hub, L.max_seg);
+  k_compact<<<row_grid > 0 ? row_grid : 1, 256, 0, s>>>(indptr, indices, n_cols, pp, mark, mpos, hubflag, hpos, segbase,
+                                                       n_rows, blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin,
+                                                       seg_key, ctr, L.max_blocks, L.max_hub, L.max_seg);
   ISP_LAUNCH_CHECK();
   build_counters h;
   ISP_HIP(hipMemcpyAsync(&h, ctr, sizeof(h), hipMemcpyDeviceToHost, s));
@@ -268,6 +372,16 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   if (h.n_blocks > L.max_blocks || h.n_hub > L.max_hub || h.n_seg > L.max_seg)
     return isp_fail(ISP_EINVAL, "internal: partition exceeds its bounds (%d/%lld blocks, %d/%lld hubs, %d/%lld segs)",
                     h.n_blocks, (long long)L.max_blocks, h.n_hub, (long long)L.max_hub, h.n_seg, (long long)L.max_seg);
+  if (h.n_seg > 0) {  // schedule order: band by band, inside a band in order of position (stable)
+    const int n_tiles = (h.n_seg + SO_TILE - 1) / SO_TILE;
+    int32_t* table = (int32_t*)(base + L.so_table);
+    int32_t* scanned = (int32_t*)(base + L.so_scanned);
+    k_seg_hist<<<n_tiles, SO_TILE, 0, s>>>(seg_key, h.n_seg, n_tiles, table);
+    ISP_LAUNCH_CHECK();
+    if ((st = isp_scan_i32_to_i32(table, scanned, (int64_t)MAX_BANDS * n_tiles, base + L.so_tmp, s)) != ISP_OK) return st;
+    k_seg_scatter<<<n_tiles, SO_TILE, 0, s>>>(seg_key, h.n_seg, n_tiles, scanned, seg_order);
+    ISP_LAUNCH_CHECK();
+  }
 
   int device = 0;
   ISP_HIP(hipGetDevice(&device));
@@ -278,6 +392,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->v.indptr = indptr; A->v.indices = indices; A->v.values = values;
   A->v.blk_row = blk_row; A->v.n_blocks = h.n_blocks;
   A->v.hub_rows = hub_rows; A->v.hub_seg_ptr = hub_seg_ptr; A->v.seg_hub = seg_hub;
+  A->v.seg_begin = seg_begin; A->v.seg_order = seg_order;
   A->v.n_hub = h.n_hub; A->v.n_seg = h.n_seg;
   A->v.hub_t = pp.hub_t; A->v.seg_len = pp.seg_len;
   A->v.partials = (float*)(base + L.partials);

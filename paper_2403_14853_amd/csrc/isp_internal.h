@@ -17,12 +17,16 @@ struct isp_view {
   const int32_t* indices;
   const float* values;     // may be NULL
   // work items: [0, n_blocks) are row blocks [blk_row[b], blk_row[b+1]) made of whole short rows;
-  // [n_blocks, n_blocks + n_seg) are segments of hub rows.
+  // [n_blocks, n_blocks + n_seg) are segments of hub rows.  Segments are numbered row by row in order of
+  // position (that number also names the segment's partial row); they are scheduled in seg_order.
   const int32_t* blk_row;  // n_blocks + 1
   int32_t n_blocks;
   const int32_t* hub_rows; // n_hub row ids, ascending
   const int32_t* hub_seg_ptr;  // n_hub + 1: first segment of each hub row
   const int32_t* seg_hub;  // n_seg: index into hub_rows of each segment
+  const int32_t* seg_begin;  // n_seg: position of each segment's first nonzero; a segment ends where the
+                             // row's next one begins, the row's last one at the end of the row
+  const int32_t* seg_order;  // n_seg: work item n_blocks + k processes segment seg_order[k] (band by band)
   int32_t n_hub, n_seg;
   int32_t hub_t, seg_len;
   float* partials;         // n_seg * ISP_PARTIAL_TILE floats

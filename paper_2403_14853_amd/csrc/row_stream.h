@@ -78,12 +78,11 @@ __device__ inline item_range locate_item(const isp_view& A, const int64_t* __res
     // a block made of one hub row is empty here: its nonzeros are covered by segment items
     r.skip = (r.row_last == r.row + 1) && (r.p_end - r.p > A.hub_t);
   } else {
-    const int s = item - A.n_blocks;
+    const int s = A.seg_order[item - A.n_blocks];
     const int h = A.seg_hub[s];
     const int hr = A.hub_rows[h];
-    const int64_t rs = indptr[hr], re = indptr[hr + 1];
-    r.p = rs + (int64_t)(s - A.hub_seg_ptr[h]) * A.seg_len;
-    r.p_end = (r.p + A.seg_len < re) ? r.p + A.seg_len : re;
+    r.p = A.seg_begin[s];
+    r.p_end = (s + 1 < A.hub_seg_ptr[h + 1]) ? (int64_t)A.seg_begin[s + 1] : indptr[hr + 1];
     r.row = s;
     r.row_last = s + 1;
     r.src_row = hr;

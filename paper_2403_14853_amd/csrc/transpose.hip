@@ -3,11 +3,11 @@
 //
 // "Stable" = entries of one column keep their order of appearance in A, which makes the result
 // unique and lets it be compared bit for bit.  It is computed as a least-significant-digit radix
-// sort of the column indices (8-bit digits) that carries the source position as payload; every
-// pass is a stable counting sort: per-tile digit histograms -> exclusive scan over
+// sort of the column indices (8-bit digits) that carries source position, source row and value as
+// payload; every pass is a stable counting sort: per-tile digit histograms -> exclusive scan over
 // (digit, tile) -> scatter with ranks taken in source order.  Integer work only, no atomics on
 // anything order-dependent.
-#include "isp_internal.h"
+#include "row_stream.h"
 
 namespace {
 
@@ -24,23 +24,17 @@ __global__ void __launch_bounds__(ISP_WG) k_row_of(isp_view A, int2* __restrict_
   const int lane = threadIdx.x & (ISP_WAVE - 1);
   const int item = blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6);
   if (item >= A.n_blocks + A.n_seg) return;
-  if (item < A.n_blocks) {
-    const int r0 = A.blk_row[item], r1 = A.blk_row[item + 1];
-    if (r1 == r0 + 1 && A.indptr[r1] - A.indptr[r0] > A.hub_t) return;  // hub row: written by its segments
-    for (int r = r0; r < r1; ++r) {
+  const isp_dev::item_range it = isp_dev::locate_item(A, A.indptr, item);
+  if (it.skip) return;  // a hub row's block: written by its segments
+  if (it.is_seg) {
+    for (int64_t p = it.p + lane; p < it.p_end; p += ISP_WAVE)
+      row_of[p] = make_int2(it.src_row, A.values ? __float_as_int(A.values[p]) : 0);
+  } else {
+    for (int r = it.row; r < it.row_last; ++r) {
       const int64_t e = A.indptr[r + 1];
       for (int64_t p = A.indptr[r] + lane; p < e; p += ISP_WAVE)
         row_of[p] = make_int2(r, A.values ? __float_as_int(A.values[p]) : 0);
     }
-  } else {
-    const int s = item - A.n_blocks;
-    const int h = A.seg_hub[s];
-    const int hr = A.hub_rows[h];
-    const int64_t re = A.indptr[hr + 1];
-    const int64_t b = A.indptr[hr] + (int64_t)(s - A.hub_seg_ptr[h]) * A.seg_len;
-    const int64_t e = (b + A.seg_len < re) ? b + A.seg_len : re;
-    for (int64_t p = b + lane; p < e; p += ISP_WAVE)
-      row_of[p] = make_int2(hr, A.values ? __float_as_int(A.values[p]) : 0);
   }
 }
 
@@ -59,30 +53,53 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t* __rest
   table[(int64_t)threadIdx.x * n_tiles + blockIdx.x] = hist[threadIdx.x];
 }
 
-// Stable scatter of one pass.  Wave w of a workgroup owns the contiguous keys
-// [tile + w * RS_WAVE_KEYS, +RS_WAVE_KEYS) and walks them 64 at a time in source order, so a
-// key's rank among equal digits = (equal digits in earlier tiles: scanned table) + (in earlier
-// waves of the tile) + (earlier rounds of this wave) + (lower lanes of this round).
-template <bool FIRST>
-__global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(const int32_t* __restrict__ keys_in,
-                                                              const int32_t* __restrict__ pay_in, int64_t n, int shift,
-                                                              int n_tiles, const int32_t* __restrict__ table_scanned,
-                                                              int32_t* __restrict__ keys_out,
-                                                              int32_t* __restrict__ pay_out) {
+// Stable scatter of one pass; the records travel as four parallel arrays (column key, source position,
+// source row, value), so the last pass leaves perm, the source rows and the values of A^T where they
+// belong and nothing has to be gathered afterwards.
+// Wave w of a workgroup owns the contiguous keys [tile + w * RS_WAVE_KEYS, +RS_WAVE_KEYS) and walks them
+// 64 at a time in source order, so a key's rank among equal digits = (equal digits in earlier tiles:
+// scanned table) + (in earlier waves of the tile) + (earlier rounds of this wave) + (lower lanes of this
+// round).  The tile is first put in digit order in LDS and written out from there, which turns the
+// scattered 4-byte stores into contiguous runs per digit.
+// FIRST: the input is the CSR itself: keys = indices, source position = index, (row, value) from row_of.
+template <bool FIRST, bool HAS_VAL>
+__global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(
+    const int32_t* __restrict__ keys_in, const int32_t* __restrict__ src_in, const int32_t* __restrict__ row_in,
+    const int32_t* __restrict__ val_in, const int2* __restrict__ row_of, int64_t n, int shift, int n_tiles,
+    const int32_t* __restrict__ table_scanned, int32_t* __restrict__ keys_out, int32_t* __restrict__ src_out,
+    int32_t* __restrict__ row_out, int32_t* __restrict__ val_out) {
   __shared__ volatile int wave_cnt[RS_WAVES][RS_RADIX];
-  __shared__ int wave_base[RS_WAVES][RS_RADIX];
+  __shared__ int wave_base[RS_WAVES][RS_RADIX];  // tile-local sorted position of each wave's first key of a digit
+  __shared__ int delta[RS_RADIX];                // output position minus tile-local position, per digit
+  __shared__ int wave_tot[RS_WAVES];
+  __shared__ int buf[RS_TILE];
   const int lane = threadIdx.x & (ISP_WAVE - 1), w = threadIdx.x / ISP_WAVE;
   for (int i = threadIdx.x; i < RS_WAVES * RS_RADIX; i += RS_THREADS) (&wave_cnt[0][0])[i] = 0;
   __syncthreads();
-  const int64_t wbase = (int64_t)blockIdx.x * RS_TILE + (int64_t)w * RS_WAVE_KEYS;
+  const int64_t tile_base = (int64_t)blockIdx.x * RS_TILE;
+  const int tile_count = (int)((n - tile_base < RS_TILE) ? n - tile_base : RS_TILE);
+  const int64_t wbase = tile_base + (int64_t)w * RS_WAVE_KEYS;
   const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  int key[RS_ROUNDS], pay[RS_ROUNDS], rank[RS_ROUNDS];
+  int key[RS_ROUNDS], src[RS_ROUNDS], row[RS_ROUNDS], val[RS_ROUNDS], pos[RS_ROUNDS];
 #pragma unroll
   for (int r = 0; r < RS_ROUNDS; ++r) {
     const int64_t q = wbase + r * ISP_WAVE + lane;
     const bool valid = q < n;
     key[r] = valid ? keys_in[q] : 0;
-    pay[r] = valid ? (FIRST ? (int32_t)q : pay_in[q]) : 0;
+    if (FIRST) {
+      const int2 rv = valid ? row_of[q] : make_int2(0, 0);
+      src[r] = (int32_t)q;
+      row[r] = rv.x;
+      val[r] = rv.y;
+    } else {
+      src[r] = valid ? src_in[q] : 0;
+      row[r] = valid ? row_in[q] : 0;
+      val[r] = (HAS_VAL && valid) ? val_in[q] : 0;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < RS_ROUNDS; ++r) {
+    const bool valid = wbase + r * ISP_WAVE + lane < n;
     const int dg = (key[r] >> shift) & (RS_RADIX - 1);
     unsigned long long m = __ballot(valid);
 #pragma unroll
@@ -92,49 +109,73 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(const int32_t* __r
     }
     // m = valid lanes of this round holding the same digit as this lane
     const int before = valid ? wave_cnt[w][dg] : 0;
-    rank[r] = before + __popcll(m & lt_mask);
+    pos[r] = before + __popcll(m & lt_mask);
     if (valid && (m & lt_mask) == 0) wave_cnt[w][dg] = before + __popcll(m);  // lowest lane of the group
   }
   __syncthreads();
-  {  // thread t owns digit t: where each wave's keys of that digit start in the output
+  {  // thread t owns digit t: exclusive scan of the tile's digit counts -> where each digit starts in the tile
     const int dg = threadIdx.x;
-    int run = table_scanned[(int64_t)dg * n_tiles + blockIdx.x];
+    int cnt[RS_WAVES], tot = 0;
 #pragma unroll
-    for (int ww = 0; ww < RS_WAVES; ++ww) {
-      wave_base[ww][dg] = run;
-      run += wave_cnt[ww][dg];
+    for (int ww = 0; ww < RS_WAVES; ++ww) { cnt[ww] = wave_cnt[ww][dg]; tot += cnt[ww]; }
+    int inc = tot;
+#pragma unroll
+    for (int o = 1; o < ISP_WAVE; o <<= 1) {
+      const int t = __shfl_up(inc, o);
+      if (lane >= o) inc += t;
     }
+    if (lane == ISP_WAVE - 1) wave_tot[w] = inc;
+    __syncthreads();
+    int start = inc - tot;
+    for (int ww = 0; ww < w; ++ww) start += wave_tot[ww];
+    delta[dg] = table_scanned[(int64_t)dg * n_tiles + blockIdx.x] - start;
+    int run = start;
+#pragma unroll
+    for (int ww = 0; ww < RS_WAVES; ++ww) { wave_base[ww][dg] = run; run += cnt[ww]; }
   }
   __syncthreads();
+  // keys: into digit order in LDS, then out; remember both positions for the other arrays
 #pragma unroll
   for (int r = 0; r < RS_ROUNDS; ++r) {
-    const int64_t q = wbase + r * ISP_WAVE + lane;
-    if (q < n) {
-      const int dg = (key[r] >> shift) & (RS_RADIX - 1);
-      const int dst = wave_base[w][dg] + rank[r];
-      keys_out[dst] = key[r];
-      pay_out[dst] = pay[r];
+    const bool valid = wbase + r * ISP_WAVE + lane < n;
+    const int dg = (key[r] >> shift) & (RS_RADIX - 1);
+    pos[r] = valid ? wave_base[w][dg] + pos[r] : -1;
+    if (valid) buf[pos[r]] = key[r];
+  }
+  __syncthreads();
+  int dst[RS_ROUNDS];
+#pragma unroll
+  for (int k = 0; k < RS_ROUNDS; ++k) {
+    const int i = k * RS_THREADS + threadIdx.x;
+    dst[k] = -1;
+    if (i < tile_count) {
+      const int kk = buf[i];
+      dst[k] = delta[(kk >> shift) & (RS_RADIX - 1)] + i;
+      keys_out[dst[k]] = kk;
     }
   }
+  auto move = [&](const int (&v)[RS_ROUNDS], int32_t* __restrict__ out) {
+    __syncthreads();  // everyone has read the previous array out of buf
+#pragma unroll
+    for (int r = 0; r < RS_ROUNDS; ++r)
+      if (pos[r] >= 0) buf[pos[r]] = v[r];
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < RS_ROUNDS; ++k)
+      if (dst[k] >= 0) out[dst[k]] = buf[k * RS_THREADS + threadIdx.x];
+  };
+  move(src, src_out);
+  move(row, row_out);
+  if (HAS_VAL) move(val, val_out);
 }
 
-// From the sorted (column, source position) pairs: perm, source rows, values and the row offsets
-// of A^T (found where the sorted column changes; empty columns get the next offset).
-__global__ void __launch_bounds__(256) k_transpose_finish(const int32_t* __restrict__ skey,
-                                                          const int32_t* __restrict__ spay, int64_t nnz,
-                                                          int64_t n_cols, const int2* __restrict__ row_of,
-                                                          bool has_values,
-                                                          int64_t* __restrict__ t_indptr,
-                                                          int32_t* __restrict__ t_indices, int32_t* __restrict__ perm,
-                                                          float* __restrict__ t_values) {
+// Row offsets of A^T from the sorted column keys: an offset changes where the sorted column changes;
+// empty columns get the next offset.
+__global__ void __launch_bounds__(256) k_col_offsets(const int32_t* __restrict__ skey, int64_t nnz, int64_t n_cols,
+                                                     int64_t* __restrict__ t_indptr) {
   const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (q >= nnz) return;
   const int32_t c = skey[q];
-  const int32_t src = spay[q];
-  const int2 rv = row_of[src];
-  perm[q] = src;
-  t_indices[q] = rv.x;
-  if (has_values) t_values[q] = __int_as_float(rv.y);
   const int32_t prev = q > 0 ? skey[q - 1] : -1;
   // (the clamp only matters for an unvalidated CSR with a column >= n_cols)
   const int64_t c_hi = c < n_cols ? (int64_t)c : n_cols - 1;
@@ -149,8 +190,7 @@ __global__ void __launch_bounds__(256) k_fill_i64(int64_t* __restrict__ a, int64
 }
 
 struct t_layout {
-  size_t t_indptr, t_indices, perm, t_values, row_of, key_a, key_b, pay_a, pay_b, table, table_scanned, scan_tmp,
-      part, total;
+  size_t t_indptr, t_indices, perm, t_values, set[2][4], row_of, table, table_scanned, scan_tmp, part, total;
   int64_t n_tiles;
 };
 
@@ -165,11 +205,12 @@ t_layout make_layout(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_value
   L.t_indices = take(e);
   L.perm = take(e);
   L.t_values = take(has_values ? e : 0);
-  L.row_of = take(2 * e);
-  L.key_a = take(e);
-  L.key_b = take(e);
-  L.pay_a = take(e);
-  L.pay_b = take(e);
+  // two sets of record arrays (key, source position, source row, value) that the passes alternate between
+  for (int k = 0; k < 2; ++k)
+    for (int a = 0; a < 4; ++a) L.set[k][a] = take(a == 3 && !has_values ? 0 : e);
+  // (row, value) per entry feeds the first pass only; the second set is first written by the second pass
+  L.row_of = L.set[1][0];
+  if (off < L.row_of + isp_align(2 * e)) off = L.row_of + isp_align(2 * e);
   const int64_t tbl = (int64_t)RS_RADIX * L.n_tiles;
   L.table = take((size_t)(tbl + 1) * 4);
   L.table_scanned = take((size_t)(tbl + 1) * 4);
@@ -199,8 +240,6 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   int32_t* perm = (int32_t*)(base + L.perm);
   float* t_values = has_values ? (float*)(base + L.t_values) : nullptr;
   int2* row_of = (int2*)(base + L.row_of);
-  int32_t* key[2] = {(int32_t*)(base + L.key_a), (int32_t*)(base + L.key_b)};
-  int32_t* pay[2] = {(int32_t*)(base + L.pay_a), (int32_t*)(base + L.pay_b)};
   int32_t* table = (int32_t*)(base + L.table);
   int32_t* table_scanned = (int32_t*)(base + L.table_scanned);
   void* scan_tmp = base + L.scan_tmp;
@@ -216,26 +255,30 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
     while (bits < 31 && ((int64_t)1 << bits) < n_cols) ++bits;
     const int n_pass = (bits + 7) / 8;
     const int n_tiles = (int)L.n_tiles;
-    const int32_t* kin = v.indices;
-    const int32_t* pin = nullptr;
+    const int32_t* in[4] = {v.indices, nullptr, nullptr, nullptr};
     for (int pass = 0; pass < n_pass; ++pass) {
       const int shift = 8 * pass;
-      k_radix_hist<<<n_tiles, RS_THREADS, 0, s>>>(kin, nnz, shift, n_tiles, table);
+      k_radix_hist<<<n_tiles, RS_THREADS, 0, s>>>(in[0], nnz, shift, n_tiles, table);
       ISP_LAUNCH_CHECK();
       isp_status st = isp_scan_i32_to_i32(table, table_scanned, (int64_t)RS_RADIX * n_tiles, scan_tmp, s);
       if (st != ISP_OK) return st;
-      int32_t* kout = key[pass & 1];
-      int32_t* pout = pay[pass & 1];
-      if (pass == 0)
-        k_radix_scatter<true><<<n_tiles, RS_THREADS, 0, s>>>(kin, pin, nnz, shift, n_tiles, table_scanned, kout, pout);
-      else
-        k_radix_scatter<false><<<n_tiles, RS_THREADS, 0, s>>>(kin, pin, nnz, shift, n_tiles, table_scanned, kout, pout);
+      int32_t* out[4];
+      for (int a = 0; a < 4; ++a) out[a] = (int32_t*)(base + L.set[pass & 1][a]);
+      if (pass == n_pass - 1) {  // the last pass writes A^T's arrays; its keys still go to the set (for the offsets)
+        out[1] = perm;
+        out[2] = t_indices;
+        out[3] = (int32_t*)t_values;
+      }
+#define ISP_GO(F, HV)                                                                                             \
+  k_radix_scatter<F, HV><<<n_tiles, RS_THREADS, 0, s>>>(in[0], in[1], in[2], in[3], row_of, nnz, shift, n_tiles, \
+                                                        table_scanned, out[0], out[1], out[2], out[3])
+      if (pass == 0) { if (has_values) ISP_GO(true, true); else ISP_GO(true, false); }
+      else { if (has_values) ISP_GO(false, true); else ISP_GO(false, false); }
+#undef ISP_GO
       ISP_LAUNCH_CHECK();
-      kin = kout;
-      pin = pout;
+      for (int a = 0; a < 4; ++a) in[a] = out[a];
     }
-    k_transpose_finish<<<(unsigned)((nnz + 255) / 256), 256, 0, s>>>(kin, pin, nnz, n_cols, row_of, has_values, t_indptr,
-                                                                    t_indices, perm, t_values);
+    k_col_offsets<<<(unsigned)((nnz + 255) / 256), 256, 0, s>>>(in[0], nnz, n_cols, t_indptr);
     ISP_LAUNCH_CHECK();
   }
   isp_csr* At = nullptr;
