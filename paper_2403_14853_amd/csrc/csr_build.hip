@@ -6,8 +6,9 @@
 // (degree > hub_t) never share a block; each is cut into segments of at most seg_len nonzeros whose
 // partial sums are combined later in a fixed order.  A hub row is cut first where its (sorted) columns
 // cross the boundaries of column bands, so that a segment gathers dense rows from one band only, and the
-// segments are scheduled band by band: the whole chip then works on one band of the dense operand at a
-// time and the L2 caches hold that band's frequently used rows instead of a sample of all of them.
+// segments are scheduled in order of their first column: the whole chip then works on one band of the
+// dense operand at a time and the L2 caches hold that band's frequently used rows instead of a sample
+// of all of them.
 // Everything here is integer work and runs once per graph (balanced scheduling: paper Section 1(b); CSR
 // operand: Section 3.5).
 #include <stdlib.h>
@@ -49,7 +50,7 @@ partition_params get_params() {
   p.block_cost = env_int("ISP_BLOCK_COST", 256, 16, 256);
   p.hub_t = env_int("ISP_HUB_THRESHOLD", 512, 8, 512);
   p.seg_len = env_int("ISP_SEGMENT_LEN", 512, 8, 768);
-  int b = env_int("ISP_BANDS", 16, 1, MAX_BANDS);
+  int b = env_int("ISP_BANDS", 32, 1, MAX_BANDS);
   while (b & (b - 1)) b &= b - 1;  // round down to a power of two
   p.bands = b;
   // (the lower limit bounds the number of segments, hence the partial-sum rows the workspace must hold)
@@ -66,8 +67,8 @@ __global__ void k_zero_counters(build_counters* c) {
 // deg is cut into br = the largest power of two <= min(bands, deg / min_piece) coarse bands, each made of
 // bands / br fine bands of width ceil(n_cols / bands).  The cut positions are found by binary search, which
 // assumes ascending columns; on a row that is not sorted they are still valid cut positions (monotone, inside
-// the row), so only the scheduling benefit is lost, never correctness.  f(fine band, first, last) is called
-// for every non-empty piece, in order.
+// the row), so only the scheduling benefit is lost, never correctness.  f(first, last) is called for every
+// non-empty piece, in order.
 template <class F>
 __device__ inline void for_each_piece(const int32_t* __restrict__ indices, int64_t a, int64_t b, int64_t n_cols,
                                       const partition_params& pp, F f) {
@@ -88,7 +89,7 @@ __device__ inline void for_each_piece(const int32_t* __restrict__ indices, int64
       }
       last = lo;
     }
-    if (last > first) f((j - 1) * step, first, last);
+    if (last > first) f(first, last);
     first = last;
   }
 }
@@ -122,7 +123,7 @@ __global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ in
     const bool hub = deg > pp.hub_t;
     int ns = 0;
     if (hub)
-      for_each_piece(indices, a, b, n_cols, pp, [&](int, int64_t first, int64_t last) {
+      for_each_piece(indices, a, b, n_cols, pp, [&](int64_t first, int64_t last) {
         ns += (int)((last - first + pp.seg_len - 1) / pp.seg_len);
       });
     cost[i] = hub ? 0 : (int32_t)deg + 1;
@@ -220,48 +221,54 @@ __global__ void __launch_bounds__(256) k_compact(const int64_t* __restrict__ ind
     }
     // the row's segments, in order of position: piece by piece, each piece in runs of seg_len
     int64_t s = s0;
-    for_each_piece(indices, indptr[i], indptr[i + 1], n_cols, pp, [&](int fine, int64_t first, int64_t last) {
+    for_each_piece(indices, indptr[i], indptr[i + 1], n_cols, pp, [&](int64_t first, int64_t last) {
       for (int64_t q = first; q < last; q += pp.seg_len, ++s) {
         if (s >= max_seg) continue;
         seg_hub[s] = h;
         seg_begin[s] = (int32_t)q;
-        seg_key[s] = fine;
+        seg_key[s] = indices[q];
       }
     });
   }
 }
 
-// ---- schedule order of the segments: stable counting sort by band ------------------------------------
+// ---- schedule order of the segments: stable radix sort (8-bit digits) by first column -----------------
 constexpr int SO_TILE = 256;
+constexpr int SO_RADIX = 256;
 
-__global__ void __launch_bounds__(SO_TILE) k_seg_hist(const int32_t* __restrict__ key, int n_seg, int n_tiles,
+__global__ void __launch_bounds__(SO_TILE) k_seg_hist(const int32_t* __restrict__ key, int n_seg, int shift, int n_tiles,
                                                       int32_t* __restrict__ table) {
-  __shared__ int hist[MAX_BANDS];
-  if (threadIdx.x < MAX_BANDS) hist[threadIdx.x] = 0;
+  __shared__ int hist[SO_RADIX];
+  hist[threadIdx.x] = 0;
   __syncthreads();
   const int s = blockIdx.x * SO_TILE + threadIdx.x;
-  if (s < n_seg) atomicAdd(&hist[key[s]], 1);
+  if (s < n_seg) atomicAdd(&hist[(key[s] >> shift) & (SO_RADIX - 1)], 1);
   __syncthreads();
-  if (threadIdx.x < MAX_BANDS) table[threadIdx.x * n_tiles + blockIdx.x] = hist[threadIdx.x];
+  table[threadIdx.x * n_tiles + blockIdx.x] = hist[threadIdx.x];
 }
 
-__global__ void __launch_bounds__(SO_TILE) k_seg_scatter(const int32_t* __restrict__ key, int n_seg, int n_tiles,
-                                                         const int32_t* __restrict__ table_scanned,
-                                                         int32_t* __restrict__ seg_order) {
-  __shared__ int keys[SO_TILE];
+// val_in == NULL: the payload is the element's index (first pass)
+__global__ void __launch_bounds__(SO_TILE) k_seg_scatter(const int32_t* __restrict__ key_in,
+                                                         const int32_t* __restrict__ val_in, int n_seg, int shift,
+                                                         int n_tiles, const int32_t* __restrict__ table_scanned,
+                                                         int32_t* __restrict__ key_out, int32_t* __restrict__ val_out) {
+  __shared__ int digits[SO_TILE];
   const int s = blockIdx.x * SO_TILE + threadIdx.x;
-  const int k = s < n_seg ? key[s] : -1;
-  keys[threadIdx.x] = k;
+  const int key = s < n_seg ? key_in[s] : 0;
+  const int dg = s < n_seg ? (key >> shift) & (SO_RADIX - 1) : -1;
+  digits[threadIdx.x] = dg;
   __syncthreads();
-  if (k < 0) return;
-  int rank = 0;  // earlier segments of this tile in the same band
-  for (int t = 0; t < (int)threadIdx.x; ++t) rank += (keys[t] == k);
-  seg_order[table_scanned[k * n_tiles + blockIdx.x] + rank] = s;
+  if (dg < 0) return;
+  int rank = 0;  // earlier elements of this tile with the same digit
+  for (int t = 0; t < (int)threadIdx.x; ++t) rank += (digits[t] == dg);
+  const int dst = table_scanned[dg * n_tiles + blockIdx.x] + rank;
+  key_out[dst] = key;
+  val_out[dst] = val_in ? val_in[s] : s;
 }
 
 struct ws_layout {
   size_t counters, cost, hubflag, nseg, cum_cost, mark, mpos, hpos, segbase, scan_tmp;
-  size_t blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin, seg_key, seg_order, so_table, so_scanned, so_tmp;
+  size_t blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin, seg_key[2], seg_order[2], so_table, so_scanned, so_tmp;
   size_t partials, total;
   int64_t max_blocks, max_hub, max_seg;
 };
@@ -294,9 +301,11 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
   L.hub_seg_ptr = take((size_t)(max_hub + 2) * 4);
   L.seg_hub = take((size_t)(max_seg + 1) * 4);
   L.seg_begin = take((size_t)(max_seg + 1) * 4);
-  L.seg_key = take((size_t)(max_seg + 1) * 4);
-  L.seg_order = take((size_t)(max_seg + 1) * 4);
-  const int64_t so_tbl = (int64_t)MAX_BANDS * ((max_seg + SO_TILE - 1) / SO_TILE + 1);
+  for (int k = 0; k < 2; ++k) {
+    L.seg_key[k] = take((size_t)(max_seg + 1) * 4);
+    L.seg_order[k] = take((size_t)(max_seg + 1) * 4);
+  }
+  const int64_t so_tbl = (int64_t)SO_RADIX * ((max_seg + SO_TILE - 1) / SO_TILE + 1);
   L.so_table = take((size_t)(so_tbl + 1) * 4);
   L.so_scanned = take((size_t)(so_tbl + 1) * 4);
   L.so_tmp = take(isp_scan_tmp_bytes(so_tbl + 1));
@@ -332,8 +341,9 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   int32_t* hub_seg_ptr = (int32_t*)(base + L.hub_seg_ptr);
   int32_t* seg_hub = (int32_t*)(base + L.seg_hub);
   int32_t* seg_begin = (int32_t*)(base + L.seg_begin);
-  int32_t* seg_key = (int32_t*)(base + L.seg_key);
-  int32_t* seg_order = (int32_t*)(base + L.seg_order);
+  int32_t* seg_key[2] = {(int32_t*)(base + L.seg_key[0]), (int32_t*)(base + L.seg_key[1])};
+  int32_t* seg_ord[2] = {(int32_t*)(base + L.seg_order[0]), (int32_t*)(base + L.seg_order[1])};
+  const int32_t* seg_order = seg_ord[0];
 
   k_zero_counters<<<1, 64, 0, s>>>(ctr);
   ISP_LAUNCH_CHECK();
@@ -362,7 +372,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   if ((st = isp_scan_i32_to_i32(nseg, segbase, n_rows, scan_tmp, s)) != ISP_OK) return st;
   k_compact<<<row_grid > 0 ? row_grid : 1, 256, 0, s>>>(indptr, indices, n_cols, pp, mark, mpos, hubflag, hpos, segbase,
                                                        n_rows, blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin,
-                                                       seg_key, ctr, L.max_blocks, L.max_hub, L.max_seg);
+                                                       seg_key[0], ctr, L.max_blocks, L.max_hub, L.max_seg);
   ISP_LAUNCH_CHECK();
   build_counters h;
   ISP_HIP(hipMemcpyAsync(&h, ctr, sizeof(h), hipMemcpyDeviceToHost, s));
@@ -372,15 +382,24 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   if (h.n_blocks > L.max_blocks || h.n_hub > L.max_hub || h.n_seg > L.max_seg)
     return isp_fail(ISP_EINVAL, "internal: partition exceeds its bounds (%d/%lld blocks, %d/%lld hubs, %d/%lld segs)",
                     h.n_blocks, (long long)L.max_blocks, h.n_hub, (long long)L.max_hub, h.n_seg, (long long)L.max_seg);
-  if (h.n_seg > 0) {  // schedule order: band by band, inside a band in order of position (stable)
+  if (h.n_seg > 0) {  // schedule order: by first column, equal ones in order of position (stable)
     const int n_tiles = (h.n_seg + SO_TILE - 1) / SO_TILE;
     int32_t* table = (int32_t*)(base + L.so_table);
     int32_t* scanned = (int32_t*)(base + L.so_scanned);
-    k_seg_hist<<<n_tiles, SO_TILE, 0, s>>>(seg_key, h.n_seg, n_tiles, table);
-    ISP_LAUNCH_CHECK();
-    if ((st = isp_scan_i32_to_i32(table, scanned, (int64_t)MAX_BANDS * n_tiles, base + L.so_tmp, s)) != ISP_OK) return st;
-    k_seg_scatter<<<n_tiles, SO_TILE, 0, s>>>(seg_key, h.n_seg, n_tiles, scanned, seg_order);
-    ISP_LAUNCH_CHECK();
+    int bits = 1;  // the keys are columns (< n_cols)
+    while (bits < 31 && ((int64_t)1 << bits) < n_cols) ++bits;
+    const int n_pass = (bits + 7) / 8;
+    for (int pass = 0; pass < n_pass; ++pass) {
+      const int32_t* kin = seg_key[pass & 1];
+      const int32_t* vin = pass == 0 ? nullptr : seg_ord[pass & 1];
+      k_seg_hist<<<n_tiles, SO_TILE, 0, s>>>(kin, h.n_seg, 8 * pass, n_tiles, table);
+      ISP_LAUNCH_CHECK();
+      if ((st = isp_scan_i32_to_i32(table, scanned, (int64_t)SO_RADIX * n_tiles, base + L.so_tmp, s)) != ISP_OK) return st;
+      k_seg_scatter<<<n_tiles, SO_TILE, 0, s>>>(kin, vin, h.n_seg, 8 * pass, n_tiles, scanned, seg_key[(pass + 1) & 1],
+                                                seg_ord[(pass + 1) & 1]);
+      ISP_LAUNCH_CHECK();
+    }
+    seg_order = seg_ord[n_pass & 1];
   }
 
   int device = 0;

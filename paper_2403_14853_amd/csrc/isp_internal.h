@@ -26,7 +26,7 @@ struct isp_view {
   const int32_t* seg_hub;  // n_seg: index into hub_rows of each segment
   const int32_t* seg_begin;  // n_seg: position of each segment's first nonzero; a segment ends where the
                              // row's next one begins, the row's last one at the end of the row
-  const int32_t* seg_order;  // n_seg: work item n_blocks + k processes segment seg_order[k] (band by band)
+  const int32_t* seg_order;  // n_seg: work item n_blocks + k processes segment seg_order[k] (in order of first column)
   int32_t n_hub, n_seg;
   int32_t hub_t, seg_len;
   float* partials;         // n_seg * ISP_PARTIAL_TILE floats

@@ -163,10 +163,10 @@ isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const
                           A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT &&
                           !getenv("ISP_NO_GROUPED");
   if (grouped_ok) {
-    // Large graphs, 128-wide rows: two passes over 64-column halves, the second adding its partial dot
-    // products.  Every L2 then holds half-rows of twice as many hot columns (the same effect as the two
-    // column slices of SpMM), which outweighs staging the CSR arrays twice and one more sweep over out.
-    if (av.nnz >= ((int64_t)8 << 20) && d == 2 * ISP_WAVE && !getenv("ISP_SDDMM_ONE_PASS")) {
+    // Large graphs with many columns, 128-wide rows: two passes over 64-column halves, the second adding
+    // its partial dot products.  Every L2 then holds half-rows of twice as many hot columns (the same
+    // effect, under the same conditions, as the two column slices of SpMM).
+    if (av.nnz >= ((int64_t)8 << 20) && av.n_cols >= (1 << 19) && d == 2 * ISP_WAVE && !getenv("ISP_SDDMM_ONE_PASS")) {
       isp_status st = launch_grouped<16>(A, U, ldu, V, ldv, 0, ISP_WAVE, false, scale, out, s);
       if (st != ISP_OK) return st;
       return launch_grouped<16>(A, U, ldu, V, ldv, ISP_WAVE, d, true, scale, out, s);

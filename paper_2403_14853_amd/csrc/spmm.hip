@@ -269,11 +269,12 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
   }
   // float4 lanes: 4 / 8 / 16 / 32 / 64 lanes per group <-> column slices of 16 / 32 / 64 / 128 / 256 floats.
   // Measured on R-MAT graphs (2.4 M and 124 M nonzeros, d = 8..256): the slice that just covers
-  // the row wins up to d = 128; on large graphs two 64-float slices per 128-float row win
-  // (dealt to alternating XCDs, each L2 then keeps half-rows of twice as many hot columns,
-  // which outweighs reading the CSR arrays twice) provided both halves are whole 128-byte lines;
-  // wider rows run as 128-float slices.  ISP_SPMM_LPG overrides the choice for tuning.
-  const bool large = av.nnz >= (int64_t)8 << 20;
+  // the row wins up to d = 128; on large graphs with many columns two 64-float slices per 128-float
+  // row win (dealt to alternating XCDs, each L2 then keeps half-rows of twice as many hot columns,
+  // which outweighs staging the CSR arrays twice) provided both halves are whole 128-byte lines.  With
+  // few columns (233 k measured) a column band's hot rows fit an L2 whole and one slice is faster.
+  // Wider rows run as 128-float slices.  ISP_SPMM_LPG overrides the choice for tuning.
+  const bool large = av.nnz >= (int64_t)8 << 20 && av.n_cols >= (1 << 19);
   int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : 32);
   if (large && d > 64 && d <= 128 && d % 64 == 0) lpg = 16;
   if (const char* e = getenv("ISP_SPMM_LPG")) {
