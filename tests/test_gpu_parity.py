@@ -289,3 +289,49 @@ def test_trusted_build_skips_validation_only():
     assert torch.equal(Ya, Yb)
     A.destroy()
     B.destroy()
+
+
+@pytest.mark.parametrize("bands,min_piece", [(1, None), (2, 4), (32, 4), (32, 64), (16, None)])
+@pytest.mark.parametrize("sorted_cols", [True, False])
+def test_hub_rows_cut_at_column_bands(bands, min_piece, sorted_cols):
+    """Hub rows are cut where their columns cross band boundaries and their segments run in order of
+    first column; the cuts are binary searches that assume sorted rows.  Whatever the band settings and
+    whether or not the rows are sorted (or repeat columns), every result must be the oracle's."""
+    _partition_env(hub=16, seg=16, block=32)
+    os.environ["ISP_BANDS"] = str(bands)
+    if min_piece is not None:
+        os.environ["ISP_MIN_PIECE"] = str(min_piece)
+    try:
+        n_rows, n_cols = 96, 700
+        rng = np.random.default_rng(1000 * bands + (min_piece or 0) + int(sorted_cols))
+        # a few rows far above the hub threshold (some spanning all bands, one confined to a narrow column
+        # range, one hitting a single column many times), the rest short or empty
+        deg = rng.integers(0, 6, size=n_rows)
+        deg[[3, 40, 41, 77, 95]] = [500, 233, 17, 64, 300]
+        cols = []
+        for i, k in enumerate(deg):
+            if i == 40:
+                c = rng.integers(300, 330, size=k)        # narrow range, many repeats
+            elif i == 77:
+                c = np.full(k, 699)                        # one column only, the last one
+            else:
+                c = rng.integers(0, n_cols, size=k)        # repeats allowed
+            cols.append(np.sort(c) if sorted_cols else c)
+        indptr = np.zeros(n_rows + 1, dtype=np.int64)
+        np.cumsum(deg, out=indptr[1:])
+        indices = np.concatenate(cols).astype(np.int32)
+        values = rng.standard_normal(len(indices)).astype(np.float32)
+        A = build(indptr, indices, values, n_cols=n_cols)
+        info = A.info()
+        assert info["n_hub_rows"] == int((deg > 16).sum())
+        plain = int(sum(-(-k // 16) for k in deg if k > 16))  # segments without band cuts
+        assert info["n_segments"] >= plain
+        if bands == 1:
+            assert info["n_segments"] == plain
+        A.destroy()
+        for d in (4, 32, 128):
+            _run_all_ops(indptr, indices, values, n_rows, n_cols, d, seed=d, fused=False)
+    finally:
+        _partition_env()
+        os.environ.pop("ISP_BANDS", None)
+        os.environ.pop("ISP_MIN_PIECE", None)
