@@ -65,7 +65,7 @@ typedef struct {
   int64_t bin_rows[5]; /* degree 0 | 1..4 | 5..32 | 33..hub_threshold | > hub_threshold (hub) */
   int64_t bin_nnz[5];
   int32_t hub_threshold;  /* rows longer than this are split by nnz                */
-  int32_t segment_len;    /* nonzeros per hub segment                              */
+  int32_t segment_len;    /* most nonzeros a hub segment holds                     */
   int32_t block_cost;     /* target (nnz + rows) per wavefront work item            */
   int32_t n_row_blocks;   /* wavefront work items made of whole short rows          */
   int32_t n_hub_rows;
@@ -80,8 +80,9 @@ isp_status isp_csr_build_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz, 
 /*
  * Wrap the caller's CSR arrays in a handle and prepare the work partition: rows are classed by
  * degree; short rows are grouped into contiguous row blocks of about equal (nnz + rows); hub rows
- * (degree > hub threshold) are cut into fixed-length nonzero segments (Section 1(b): balanced
- * scheduling; Section 3.5: CSR operand).  Integer work only.
+ * (degree > hub threshold) are cut into segments of bounded length, at column-band boundaries first,
+ * which are scheduled in column order (Section 1(b): balanced scheduling; Section 3.5: CSR operand).
+ * Integer work only.  Rows with ascending columns schedule best; any order is accepted.
  *   indptr/indices/values: borrowed device arrays (values may be NULL).
  *   workspace: device memory, 256-byte aligned, >= isp_csr_build_workspace() bytes; borrowed
  *              until isp_csr_destroy.

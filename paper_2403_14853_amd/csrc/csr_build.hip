@@ -65,33 +65,38 @@ __global__ void k_zero_counters(build_counters* c) {
 
 // Pieces of a hub row: its entries [a, b) cut where the columns cross band boundaries.  A row of degree
 // deg is cut into br = the largest power of two <= min(bands, deg / min_piece) coarse bands, each made of
-// bands / br fine bands of width ceil(n_cols / bands).  The cut positions are found by binary search, which
-// assumes ascending columns; on a row that is not sorted they are still valid cut positions (monotone, inside
-// the row), so only the scheduling benefit is lost, never correctness.  f(first, last) is called for every
-// non-empty piece, in order.
-template <class F>
-__device__ inline void for_each_piece(const int32_t* __restrict__ indices, int64_t a, int64_t b, int64_t n_cols,
-                                      const partition_params& pp, F f) {
+// bands / br fine bands of width ceil(n_cols / bands).  The whole wavefront calls this with the same row
+// (a, b wave-uniform): lane j < br gets piece j as [*first, *last), the other lanes an empty piece.  Every
+// lane finds one cut position by binary search, which assumes ascending columns; on a row that is not
+// sorted the positions are made monotone, so they are still valid cuts (inside the row, in order) and only
+// the scheduling benefit is lost, never correctness.
+__device__ inline void wave_hub_pieces(const int32_t* __restrict__ indices, int64_t a, int64_t b, int64_t n_cols,
+                                       const partition_params& pp, int lane, int64_t* first, int64_t* last) {
   const int64_t deg = b - a;
   int br = 1;
   while (br * 2 <= pp.bands && (int64_t)(br * 2) * pp.min_piece <= deg) br *= 2;
   const int64_t bw = (n_cols + pp.bands - 1) / pp.bands;
   const int step = pp.bands / br;
-  int64_t first = a;
-  for (int j = 1; j <= br; ++j) {
-    int64_t last = b;
-    if (j < br) {
-      const int64_t target = (int64_t)j * step * bw;
-      int64_t lo = first, hi = b;  // first position in [first, b) whose column is >= target
-      while (lo < hi) {
-        const int64_t mid = (lo + hi) >> 1;
-        if ((int64_t)indices[mid] < target) lo = mid + 1; else hi = mid;
-      }
-      last = lo;
+  // cut j = first position whose column is >= j * step * bw; cut 0 = a, cuts >= br = b
+  int64_t lo = a, hi = b;
+  if (lane == 0) hi = a;
+  if (lane >= br) lo = b;
+  const int64_t target = (int64_t)lane * step * bw;
+  while (__any(lo < hi)) {
+    if (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if ((int64_t)indices[mid] < target) lo = mid + 1; else hi = mid;
     }
-    if (last > first) f(first, last);
-    first = last;
   }
+  int64_t cut = lo;
+#pragma unroll
+  for (int o = 1; o < ISP_WAVE; o <<= 1) {  // running maximum over the lanes: monotone cuts
+    const int64_t t = __shfl_up(cut, o);
+    if (lane >= o && t > cut) cut = t;
+  }
+  const int64_t next = __shfl_down(cut, 1);
+  *first = lane < br ? cut : b;
+  *last = lane < br ? next : b;
 }
 
 __device__ inline int degree_bin(long long deg, int hub_t) {
@@ -116,16 +121,28 @@ __global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ in
   __syncthreads();
   unsigned long long my_rows[5] = {0, 0, 0, 0, 0}, my_nnz[5] = {0, 0, 0, 0, 0}, my_max = 0;
   int my_err = 0, my_seg = 0;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_rows; i += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t a = indptr[i], b = indptr[i + 1];
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  // every wavefront walks whole chunks of 64 rows (one per lane), so that it can turn to a hub row together
+  for (int64_t base = (int64_t)blockIdx.x * blockDim.x + (threadIdx.x - lane); base < n_rows;
+       base += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i = base + lane;
+    const bool valid = i < n_rows;
+    const int64_t a = valid ? indptr[i] : 0, b = valid ? indptr[i + 1] : 0;
     long long deg = b - a;
-    if (deg < 0 || a < 0 || b > nnz || (i == 0 && a != 0) || (i == n_rows - 1 && b != nnz)) { my_err = 1; deg = 0; }
+    if (valid && (deg < 0 || a < 0 || b > nnz || (i == 0 && a != 0) || (i == n_rows - 1 && b != nnz))) { my_err = 1; deg = 0; }
     const bool hub = deg > pp.hub_t;
     int ns = 0;
-    if (hub)
-      for_each_piece(indices, a, b, n_cols, pp, [&](int64_t first, int64_t last) {
-        ns += (int)((last - first + pp.seg_len - 1) / pp.seg_len);
-      });
+    for (unsigned long long hm = __ballot(hub); hm; hm &= hm - 1) {  // the chunk's hub rows, one at a time
+      const int src = __ffsll((long long)hm) - 1;
+      const int64_t ha = __shfl(a, src), hb = __shfl(b, src);
+      int64_t first, last;
+      wave_hub_pieces(indices, ha, hb, n_cols, pp, lane, &first, &last);
+      int cnt = (int)((last - first + pp.seg_len - 1) / pp.seg_len);
+#pragma unroll
+      for (int o = 1; o < ISP_WAVE; o <<= 1) cnt += __shfl_xor(cnt, o);
+      if (lane == src) ns = cnt;
+    }
+    if (!valid) continue;
     cost[i] = hub ? 0 : (int32_t)deg + 1;
     hubflag[i] = hub ? 1 : 0;
     nseg[i] = ns;
@@ -204,6 +221,7 @@ __global__ void __launch_bounds__(256) k_compact(const int64_t* __restrict__ ind
   // The bounds only bite for a malformed indptr (the host then reports ISP_EBADCSR); they keep
   // every write inside the workspace in that case too.
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
   if (i == 0) {
     const int nb = mpos[n_rows], nh = hpos[n_rows];
     if (nb <= max_blocks) blk_row[nb] = (int32_t)n_rows;
@@ -211,24 +229,36 @@ __global__ void __launch_bounds__(256) k_compact(const int64_t* __restrict__ ind
     ctr->n_blocks = nb;
     ctr->n_hub = nh;
   }
-  if (i >= n_rows) return;
-  if (mark[i] && mpos[i] < max_blocks) blk_row[mpos[i]] = (int32_t)i;
-  if (hubflag[i]) {
-    const int h = hpos[i], s0 = segbase[i];
-    if (h < max_hub) {
-      hub_rows[h] = (int32_t)i;
-      hub_seg_ptr[h] = s0;
+  const bool valid = i < n_rows;  // (no early exit: the wavefront handles its hub rows together)
+  if (valid && mark[i] && mpos[i] < max_blocks) blk_row[mpos[i]] = (int32_t)i;
+  const bool hub = valid && hubflag[i];
+  const int h = hub ? hpos[i] : 0, s0 = hub ? segbase[i] : 0;
+  const int64_t a = hub ? indptr[i] : 0, b = hub ? indptr[i + 1] : 0;
+  if (hub && h < max_hub) {
+    hub_rows[h] = (int32_t)i;
+    hub_seg_ptr[h] = s0;
+  }
+  for (unsigned long long hm = __ballot(hub); hm; hm &= hm - 1) {
+    const int src = __ffsll((long long)hm) - 1;
+    const int64_t ha = __shfl(a, src), hb = __shfl(b, src);
+    const int hh = __shfl(h, src), hs0 = __shfl(s0, src);
+    int64_t first, last;
+    wave_hub_pieces(indices, ha, hb, n_cols, pp, lane, &first, &last);
+    // the row's segments, in order of position: piece by piece (lane by lane), each piece in runs of seg_len
+    const int cnt = (int)((last - first + pp.seg_len - 1) / pp.seg_len);
+    int inc = cnt;
+#pragma unroll
+    for (int o = 1; o < ISP_WAVE; o <<= 1) {
+      const int t = __shfl_up(inc, o);
+      if (lane >= o) inc += t;
     }
-    // the row's segments, in order of position: piece by piece, each piece in runs of seg_len
-    int64_t s = s0;
-    for_each_piece(indices, indptr[i], indptr[i + 1], n_cols, pp, [&](int64_t first, int64_t last) {
-      for (int64_t q = first; q < last; q += pp.seg_len, ++s) {
-        if (s >= max_seg) continue;
-        seg_hub[s] = h;
-        seg_begin[s] = (int32_t)q;
-        seg_key[s] = indices[q];
-      }
-    });
+    int64_t s = (int64_t)hs0 + inc - cnt;
+    for (int64_t q = first; q < last; q += pp.seg_len, ++s) {
+      if (s >= max_seg) continue;
+      seg_hub[s] = hh;
+      seg_begin[s] = (int32_t)q;
+      seg_key[s] = indices[q];
+    }
   }
 }
 
