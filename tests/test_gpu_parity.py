@@ -335,3 +335,34 @@ def test_hub_rows_cut_at_column_bands(bands, min_piece, sorted_cols):
         _partition_env()
         os.environ.pop("ISP_BANDS", None)
         os.environ.pop("ISP_MIN_PIECE", None)
+
+
+def test_caller_owned_workspaces():
+    """csr_build / csr_transpose_cached accept the caller's workspace tensors (as the C boundary does);
+    a workspace below the queried size is refused; results equal those with library-side allocation."""
+    w = graphgen.make_config(1, shrink=64)
+    ip, ix, va = dev(w.indptr), dev(w.indices), dev(w.values)
+    need = isp.csr_build_workspace(w.n, w.n, w.nnz)
+    assert need > 0 and need % 256 == 0
+    with pytest.raises(AssertionError):
+        isp.csr_build(ip, ix, va, workspace=torch.empty(need - 256, dtype=torch.uint8, device="cuda"))
+    ws_a = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda")  # stale contents must not matter
+    A = isp.csr_build(ip, ix, va, workspace=ws_a)
+    need_t = isp.csr_transpose_workspace(A)
+    ws_t = torch.full((need_t,), 0xCD, dtype=torch.uint8, device="cuda")
+    At, was = isp.csr_transpose_cached(A, workspace=ws_t)
+    assert not was
+    B = isp.csr_build(ip, ix, va)
+    Bt, _ = isp.csr_transpose_cached(B)
+    for x, y in zip(At.export(), Bt.export()):
+        assert (x is None and y is None) or torch.equal(x, y)
+    X = dev(w.X)
+    Y1, Y2 = torch.empty_like(X), torch.empty_like(X)
+    isp.spmm(A, X, Y1)
+    isp.spmm(B, X, Y2)
+    assert torch.equal(Y1, Y2)
+    isp.spmm(At, X, Y1)
+    isp.spmm(Bt, X, Y2)
+    assert torch.equal(Y1, Y2)
+    A.destroy()
+    B.destroy()
