@@ -3,11 +3,11 @@
 //
 // "Stable" = entries of one column keep their order of appearance in A, which makes the result
 // unique and lets it be compared bit for bit.  It is computed as a least-significant-digit radix
-// sort of the column indices (8-bit digits) that carries source position, source row and value as
+// sort of the column indices (digits of up to 8 bits) that carries source position, source row and value as
 // payload; every pass is a stable counting sort: per-tile digit histograms -> exclusive scan over
 // (digit, tile) -> scatter with ranks taken in source order.  Integer work only, no atomics on
 // anything order-dependent.
-#include "row_stream.h"
+#include "isp_internal.h"
 
 namespace {
 
@@ -18,36 +18,30 @@ constexpr int RS_WAVE_KEYS = RS_ROUNDS * ISP_WAVE;  // contiguous keys owned by 
 constexpr int RS_TILE = RS_WAVE_KEYS * RS_WAVES;    // keys per workgroup
 constexpr int RS_RADIX = 256;
 
-// (source row, value bits) of every stored entry, written by the same work items the compute
-// kernels use; the final gather then needs one 8-byte read per entry instead of two 4-byte ones.
-__global__ void __launch_bounds__(ISP_WG) k_row_of(isp_view A, int2* __restrict__ row_of) {
-  const int lane = threadIdx.x & (ISP_WAVE - 1);
-  const int item = blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6);
-  if (item >= A.n_blocks + A.n_seg) return;
-  const isp_dev::item_range it = isp_dev::locate_item(A, A.indptr, item);
-  if (it.skip) return;  // a hub row's block: written by its segments
-  if (it.is_seg) {
-    for (int64_t p = it.p + lane; p < it.p_end; p += ISP_WAVE)
-      row_of[p] = make_int2(it.src_row, A.values ? __float_as_int(A.values[p]) : 0);
-  } else {
-    for (int r = it.row; r < it.row_last; ++r) {
-      const int64_t e = A.indptr[r + 1];
-      for (int64_t p = A.indptr[r] + lane; p < e; p += ISP_WAVE)
-        row_of[p] = make_int2(r, A.values ? __float_as_int(A.values[p]) : 0);
-    }
+// Row that owns the first entry of every sort tile: the smallest r with indptr[r + 1] > tile * RS_TILE.
+__global__ void __launch_bounds__(256) k_tile_rows(const int64_t* __restrict__ indptr, int64_t n_rows, int n_tiles,
+                                                   int32_t* __restrict__ tile_row) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_tiles) return;
+  const int64_t q = (int64_t)t * RS_TILE;
+  int64_t lo = 0, hi = n_rows - 1;  // q < nnz = indptr[n_rows], so the answer exists
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (indptr[mid + 1] > q) hi = mid; else lo = mid + 1;
   }
+  tile_row[t] = (int32_t)lo;
 }
 
 // Per-tile digit histogram; table is digit-major: table[digit * n_tiles + tile].
 __global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t* __restrict__ keys, int64_t n, int shift,
-                                                           int n_tiles, int32_t* __restrict__ table) {
+                                                           int mask, int n_tiles, int32_t* __restrict__ table) {
   __shared__ int hist[RS_RADIX];
   hist[threadIdx.x] = 0;
   __syncthreads();
   const int64_t base = (int64_t)blockIdx.x * RS_TILE;
   for (int i = threadIdx.x; i < RS_TILE; i += RS_THREADS) {
     const int64_t q = base + i;
-    if (q < n) atomicAdd(&hist[(keys[q] >> shift) & (RS_RADIX - 1)], 1);
+    if (q < n) atomicAdd(&hist[(keys[q] >> shift) & mask], 1);
   }
   __syncthreads();
   table[(int64_t)threadIdx.x * n_tiles + blockIdx.x] = hist[threadIdx.x];
@@ -61,11 +55,14 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_hist(const int32_t* __rest
 // scanned table) + (in earlier waves of the tile) + (earlier rounds of this wave) + (lower lanes of this
 // round).  The tile is first put in digit order in LDS and written out from there, which turns the
 // scattered 4-byte stores into contiguous runs per digit.
-// FIRST: the input is the CSR itself: keys = indices, source position = index, (row, value) from row_of.
+// FIRST: the input is the CSR itself: keys = indices, source position = index, value = values (val_in), and
+// the source rows are rebuilt per tile from the row offsets: every row that starts inside the tile marks its
+// first position in LDS, a running maximum spreads the marks (tile_row = the row owning the tile's first entry).
 template <bool FIRST, bool HAS_VAL>
 __global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(
     const int32_t* __restrict__ keys_in, const int32_t* __restrict__ src_in, const int32_t* __restrict__ row_in,
-    const int32_t* __restrict__ val_in, const int2* __restrict__ row_of, int64_t n, int shift, int n_tiles,
+    const int32_t* __restrict__ val_in, const int64_t* __restrict__ indptr, int64_t n_rows,
+    const int32_t* __restrict__ tile_row, int64_t n, int shift, int mask, int n_tiles,
     const int32_t* __restrict__ table_scanned, int32_t* __restrict__ keys_out, int32_t* __restrict__ src_out,
     int32_t* __restrict__ row_out, int32_t* __restrict__ val_out) {
   __shared__ volatile int wave_cnt[RS_WAVES][RS_RADIX];
@@ -75,9 +72,44 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(
   __shared__ int buf[RS_TILE];
   const int lane = threadIdx.x & (ISP_WAVE - 1), w = threadIdx.x / ISP_WAVE;
   for (int i = threadIdx.x; i < RS_WAVES * RS_RADIX; i += RS_THREADS) (&wave_cnt[0][0])[i] = 0;
-  __syncthreads();
   const int64_t tile_base = (int64_t)blockIdx.x * RS_TILE;
   const int tile_count = (int)((n - tile_base < RS_TILE) ? n - tile_base : RS_TILE);
+  if (FIRST) {
+    for (int i = threadIdx.x; i < RS_TILE; i += RS_THREADS) buf[i] = 0;
+    __syncthreads();
+    const int r_first = tile_row[blockIdx.x];
+    if (threadIdx.x == 0) buf[0] = r_first;
+    // rows after r_first that start inside the tile (of several empty rows sharing a start, the last one -
+    // the owner of the entry there - wins)
+    for (int64_t r = (int64_t)r_first + 1 + threadIdx.x; r < n_rows; r += RS_THREADS) {
+      const int64_t o = indptr[r] - tile_base;
+      if (o >= tile_count) break;
+      atomicMax(&buf[o], (int)r);
+    }
+    __syncthreads();
+    // running maximum over the tile: thread t owns positions [16 t, 16 t + 16)
+    int loc[RS_ROUNDS], run = 0;
+#pragma unroll
+    for (int k = 0; k < RS_ROUNDS; ++k) {
+      const int v = buf[threadIdx.x * RS_ROUNDS + k];
+      run = v > run ? v : run;
+      loc[k] = run;
+    }
+    int inc = run;
+#pragma unroll
+    for (int o = 1; o < ISP_WAVE; o <<= 1) {
+      const int t = __shfl_up(inc, o);
+      if (lane >= o && t > inc) inc = t;
+    }
+    if (lane == ISP_WAVE - 1) wave_tot[w] = inc;
+    __syncthreads();
+    int before = __shfl_up(inc, 1);  // maximum over the lower lanes of this wave
+    if (lane == 0) before = 0;
+    for (int ww = 0; ww < w; ++ww) before = wave_tot[ww] > before ? wave_tot[ww] : before;
+#pragma unroll
+    for (int k = 0; k < RS_ROUNDS; ++k) buf[threadIdx.x * RS_ROUNDS + k] = loc[k] > before ? loc[k] : before;
+  }
+  __syncthreads();
   const int64_t wbase = tile_base + (int64_t)w * RS_WAVE_KEYS;
   const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   int key[RS_ROUNDS], src[RS_ROUNDS], row[RS_ROUNDS], val[RS_ROUNDS], pos[RS_ROUNDS];
@@ -87,10 +119,9 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(
     const bool valid = q < n;
     key[r] = valid ? keys_in[q] : 0;
     if (FIRST) {
-      const int2 rv = valid ? row_of[q] : make_int2(0, 0);
       src[r] = (int32_t)q;
-      row[r] = rv.x;
-      val[r] = rv.y;
+      row[r] = valid ? buf[w * RS_WAVE_KEYS + r * ISP_WAVE + lane] : 0;
+      val[r] = (HAS_VAL && valid) ? val_in[q] : 0;
     } else {
       src[r] = valid ? src_in[q] : 0;
       row[r] = valid ? row_in[q] : 0;
@@ -100,7 +131,7 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(
 #pragma unroll
   for (int r = 0; r < RS_ROUNDS; ++r) {
     const bool valid = wbase + r * ISP_WAVE + lane < n;
-    const int dg = (key[r] >> shift) & (RS_RADIX - 1);
+    const int dg = (key[r] >> shift) & mask;
     unsigned long long m = __ballot(valid);
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
@@ -138,7 +169,7 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(
 #pragma unroll
   for (int r = 0; r < RS_ROUNDS; ++r) {
     const bool valid = wbase + r * ISP_WAVE + lane < n;
-    const int dg = (key[r] >> shift) & (RS_RADIX - 1);
+    const int dg = (key[r] >> shift) & mask;
     pos[r] = valid ? wave_base[w][dg] + pos[r] : -1;
     if (valid) buf[pos[r]] = key[r];
   }
@@ -150,7 +181,7 @@ __global__ void __launch_bounds__(RS_THREADS) k_radix_scatter(
     dst[k] = -1;
     if (i < tile_count) {
       const int kk = buf[i];
-      dst[k] = delta[(kk >> shift) & (RS_RADIX - 1)] + i;
+      dst[k] = delta[(kk >> shift) & mask] + i;
       keys_out[dst[k]] = kk;
     }
   }
@@ -190,7 +221,7 @@ __global__ void __launch_bounds__(256) k_fill_i64(int64_t* __restrict__ a, int64
 }
 
 struct t_layout {
-  size_t t_indptr, t_indices, perm, t_values, set[2][4], row_of, table, table_scanned, scan_tmp, part, total;
+  size_t t_indptr, t_indices, perm, t_values, set[2][4], tile_row, table, table_scanned, scan_tmp, part, total;
   int64_t n_tiles;
 };
 
@@ -208,9 +239,7 @@ t_layout make_layout(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_value
   // two sets of record arrays (key, source position, source row, value) that the passes alternate between
   for (int k = 0; k < 2; ++k)
     for (int a = 0; a < 4; ++a) L.set[k][a] = take(a == 3 && !has_values ? 0 : e);
-  // (row, value) per entry feeds the first pass only; the second set is first written by the second pass
-  L.row_of = L.set[1][0];
-  if (off < L.row_of + isp_align(2 * e)) off = L.row_of + isp_align(2 * e);
+  L.tile_row = take((size_t)(L.n_tiles + 1) * 4);
   const int64_t tbl = (int64_t)RS_RADIX * L.n_tiles;
   L.table = take((size_t)(tbl + 1) * 4);
   L.table_scanned = take((size_t)(tbl + 1) * 4);
@@ -239,7 +268,7 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   int32_t* t_indices = (int32_t*)(base + L.t_indices);
   int32_t* perm = (int32_t*)(base + L.perm);
   float* t_values = has_values ? (float*)(base + L.t_values) : nullptr;
-  int2* row_of = (int2*)(base + L.row_of);
+  int32_t* tile_row = (int32_t*)(base + L.tile_row);
   int32_t* table = (int32_t*)(base + L.table);
   int32_t* table_scanned = (int32_t*)(base + L.table_scanned);
   void* scan_tmp = base + L.scan_tmp;
@@ -248,17 +277,18 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
     k_fill_i64<<<(unsigned)((n_cols + 1 + 255) / 256), 256, 0, s>>>(t_indptr, n_cols + 1, 0);
     ISP_LAUNCH_CHECK();
   } else {
-    const int n_items = v.n_blocks + v.n_seg;
-    k_row_of<<<(unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG), ISP_WG, 0, s>>>(v, row_of);
-    ISP_LAUNCH_CHECK();
     int bits = 1;
     while (bits < 31 && ((int64_t)1 << bits) < n_cols) ++bits;
-    const int n_pass = (bits + 7) / 8;
+    const int n_pass = (bits + 7) / 8;  // digits of at most 8 bits (5-, 6- and 7-bit digits measured slower)
     const int n_tiles = (int)L.n_tiles;
-    const int32_t* in[4] = {v.indices, nullptr, nullptr, nullptr};
+    k_tile_rows<<<(n_tiles + 255) / 256, 256, 0, s>>>(v.indptr, n_rows, n_tiles, tile_row);
+    ISP_LAUNCH_CHECK();
+    const int32_t* in[4] = {v.indices, nullptr, nullptr, (const int32_t*)v.values};
     for (int pass = 0; pass < n_pass; ++pass) {
-      const int shift = 8 * pass;
-      k_radix_hist<<<n_tiles, RS_THREADS, 0, s>>>(in[0], nnz, shift, n_tiles, table);
+      // digits of about equal width: pass p takes bits [p * bits / n_pass, (p + 1) * bits / n_pass)
+      const int shift = pass * bits / n_pass;
+      const int mask = (1 << ((pass + 1) * bits / n_pass - shift)) - 1;
+      k_radix_hist<<<n_tiles, RS_THREADS, 0, s>>>(in[0], nnz, shift, mask, n_tiles, table);
       ISP_LAUNCH_CHECK();
       isp_status st = isp_scan_i32_to_i32(table, table_scanned, (int64_t)RS_RADIX * n_tiles, scan_tmp, s);
       if (st != ISP_OK) return st;
@@ -270,8 +300,8 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
         out[3] = (int32_t*)t_values;
       }
 #define ISP_GO(F, HV)                                                                                             \
-  k_radix_scatter<F, HV><<<n_tiles, RS_THREADS, 0, s>>>(in[0], in[1], in[2], in[3], row_of, nnz, shift, n_tiles, \
-                                                        table_scanned, out[0], out[1], out[2], out[3])
+  k_radix_scatter<F, HV><<<n_tiles, RS_THREADS, 0, s>>>(in[0], in[1], in[2], in[3], v.indptr, n_rows, tile_row, nnz, shift, mask, \
+                                                        n_tiles, table_scanned, out[0], out[1], out[2], out[3])
       if (pass == 0) { if (has_values) ISP_GO(true, true); else ISP_GO(true, false); }
       else { if (has_values) ISP_GO(false, true); else ISP_GO(false, false); }
 #undef ISP_GO
