@@ -107,3 +107,26 @@ def test_fusedmm_config4_full():
     ref, mag = oracle.fusedmm_backward(w.indptr, w.indices, None, w.X, w.dY)
     assert_close(dX, ref, mag, "fusedmm backward")
     A.destroy()
+
+
+def test_sddmm_config3_full_two_column_passes():
+    """Config 3 is large and has many columns, so SDDMM at d = 128 runs as two passes over 64-column halves
+    (the second adds its partial dot products): every output against the oracle, and bitwise repeatable."""
+    _say("config 3: generating")
+    w = graphgen.make_config(3)
+    A = build(w.indptr, w.indices, w.values)
+    X, dY = dev(w.X), dev(w.dY)
+    dA = torch.full((w.nnz,), float("nan"), device="cuda")
+    isp.sddmm(A, dY, X, dA)
+    _say("sddmm: oracle")
+    ref, mag = oracle.sddmm(w.indptr, w.indices, w.values, w.dY, w.X)
+    assert_close(dA, ref, mag, "sddmm")
+    del ref, mag
+    dA2 = torch.empty_like(dA)
+    isp.sddmm(A, dY, X, dA2)
+    assert torch.equal(dA, dA2)
+    isp.sddmm(A, dY, X, dA, scale_by_a=True)
+    _say("sddmm scaled: oracle")
+    ref, mag = oracle.sddmm(w.indptr, w.indices, w.values, w.dY, w.X, scale_by_a=True)
+    assert_close(dA, ref, mag, "sddmm scaled")
+    A.destroy()
