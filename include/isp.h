@@ -24,6 +24,8 @@
  *   - Outputs are overwritten (Y = A X, not +=).  n_rows = 0 and nnz = 0 are valid.
  *   - Every function returns a status; nothing throws or aborts across this boundary.  After a
  *     failure isp_last_error() returns a thread-local message.
+ *   - A handle belongs to the HIP device that was current when it was built; using it with another device
+ *     current yields ISP_EINVAL.
  *   - Calls that use the same handle (or a handle and its cached transpose) on different streams
  *     at the same time race on the handle's scratch (hub-row partial sums); serialise them.
  *   - Results are run-to-run bitwise deterministic: no floating-point atomics are used.
