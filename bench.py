@@ -47,6 +47,9 @@ def main():
                          "autograd wrappers, dense GEMMs through torch) with hidden width d")
     ap.add_argument("--reductions", action="store_true",
                     help="instead of the benchmark line: forward and backward time of the mean / min / max reductions")
+    ap.add_argument("--flushed", action="store_true",
+                    help="instead of the benchmark line: per-op time when a 1 GiB copy has swept L2 and the "
+                         "Infinity Cache before every op (the small workloads otherwise run cache-warm)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain device copies of X (known size) before the timed region, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
@@ -145,6 +148,26 @@ def main():
         graph_ms = _time_ms(g.replay, args.steps)
         print(json.dumps({"what": "one step launched eagerly vs replayed from a captured HIP graph", "workload": w.name,
                           "ops": ops, "eager_ms_per_step": round(eager_ms, 4), "graph_ms_per_step": round(graph_ms, 4)}))
+        return
+    if args.flushed:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        warm, cold = [[] for _ in ops], [[] for _ in ops]
+        for k in range(args.steps):
+            for flush, acc in ((False, warm), (True, cold)):
+                for i, op in enumerate(ops):
+                    if flush:
+                        dst.copy_(src)  # 1 GiB read + 1 GiB written: four times the Infinity Cache
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(stream)
+                    run_of[op]()
+                    b.record(stream)
+                    b.synchronize()
+                    acc[i].append(a.elapsed_time(b))
+        print(json.dumps({"what": "per-op time, back to back vs after a 1 GiB copy has flushed the caches",
+                          "workload": w.name, "steps": args.steps,
+                          "warm_ms": {("%d:%s" % (i, o)): round(float(np.median(warm[i])), 4) for i, o in enumerate(ops)},
+                          "flushed_ms": {("%d:%s" % (i, o)): round(float(np.median(cold[i])), 4) for i, o in enumerate(ops)}}))
         return
     if args.copy_calibration:
         for _ in range(3):
