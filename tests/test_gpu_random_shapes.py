@@ -27,12 +27,17 @@ def _case(seed):
     env = dict(ISP_HUB_THRESHOLD=str(int(rng.choice([8, 24, 100, 512]))),
                ISP_SEGMENT_LEN=str(int(rng.choice([8, 16, 64, 512]))),
                ISP_BLOCK_COST=str(int(rng.choice([16, 32, 100, 256]))))
-    return dict(square=square, n_rows=n_rows, n_cols=n_cols, nnz=nnz, d=d, env=env,
-                sorted_cols=bool(rng.integers(0, 2)), allow_dup=bool(rng.integers(0, 2)),
-                has_values=bool(rng.integers(0, 4)), pad=int(rng.choice([0, 0, 4, 12])), skew=bool(rng.integers(0, 2)))
+    c = dict(square=square, n_rows=n_rows, n_cols=n_cols, nnz=nnz, d=d, env=env,
+             sorted_cols=bool(rng.integers(0, 2)), allow_dup=bool(rng.integers(0, 2)),
+             has_values=bool(rng.integers(0, 4)), pad=int(rng.choice([0, 0, 4, 12])), skew=bool(rng.integers(0, 2)))
+    # column bands of the hub rows (drawn last, so the fields above keep their values per seed)
+    env["ISP_BANDS"] = str(int(rng.choice([1, 2, 8, 32])))
+    env["ISP_MIN_PIECE"] = str(int(rng.choice([4, 16, 64, 256])))
+    return c
 
 
-@pytest.mark.parametrize("seed", range(48))
+# ISP_RANDOM_SHAPES=N widens the sweep for a one-off soak of the host and partition logic
+@pytest.mark.parametrize("seed", range(int(os.environ.get("ISP_RANDOM_SHAPES", "48"))))
 def test_random_shape(seed):
     c = _case(seed)
     print("[random-shape] seed=%d %s" % (seed, {k: v for k, v in c.items()}), flush=True)
