@@ -208,6 +208,9 @@ def main():
         "gather_model_bytes": gather_bytes,
         "gather_model_GBps": round(gather_bytes / (dom_ms * 1e-3) / 1e9, 1),
     }
+    if roofline["traffic"]:  # counter bytes of the stored profile over this run's launch time
+        roofline["traffic_GBps"] = round(roofline["traffic"] / (dom_ms * 1e-3) / 1e9, 1)
+        roofline["traffic_frac_of_peak"] = round(roofline["traffic_GBps"] / HBM_PEAK_GBPS, 4)
 
     cpu = None
     if not args.no_cpu_baseline and not args.ops:  # the oracle leg checks the workload's own dominant output
