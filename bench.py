@@ -32,6 +32,9 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--shrink", type=int, default=1, help="divide the graph size (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-relabel", action="store_true",
+                    help="keep the R-MAT generator's own vertex ids instead of the random relabelling (a point of "
+                         "comparison, not a benchmark configuration; the workload name says so)")
     ap.add_argument("--ops", default="", help="comma-separated operations to time in place of the workload's own "
                                               "(spmm, spmm_t, sddmm, fusedmm, fusedmm_bwd); not the headline line")
     ap.add_argument("--epoch-ablation", type=int, default=0, metavar="E",
@@ -67,7 +70,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     isp.load_library()  # fails loudly when the HIP library is missing
     t0 = time.time()
-    w = graphgen.make_config(args.config, shrink=args.shrink)
+    w = graphgen.make_config(args.config, shrink=args.shrink, relabel=not args.no_relabel)
     gen_s = time.time() - t0
     n, d, nnz = w.n, w.d, w.nnz
     dev = lambda a: torch.from_numpy(a).cuda()
@@ -203,7 +206,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": {"fusedmm": "k_fused_grouped<g_fwd>", "spmm": "k_spmm_grouped"}.get(dom, dom),
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC_BYTES.get((args.config, args.shrink)),
+        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None if args.no_relabel else TRAFFIC_BYTES.get((args.config, args.shrink)),
         "algorithmic_bytes": alg_bytes, "launch_ms": round(dom_ms, 4),
         "gather_model_bytes": gather_bytes,
         "gather_model_GBps": round(gather_bytes / (dom_ms * 1e-3) / 1e9, 1),

@@ -183,16 +183,20 @@ def config_recipe(k: int, shrink: int = 1) -> dict:
 
 
 def make_config(k: int, *, shrink: int = 1, graph_seed: int = 0, x_seed: int = 1, dy_seed: int = 2,
-                d: int | None = None) -> Workload:
-    """Build benchmark configuration k (0..4).  Seeds: graph 0, X 1, dY 2 unless overridden."""
+                d: int | None = None, relabel: bool = True) -> Workload:
+    """Build benchmark configuration k (0..4).  Seeds: graph 0, X 1, dY 2 unless overridden.
+    relabel=False keeps the R-MAT generator's own vertex ids (hubs at ids with few one-bits): not a
+    benchmark configuration, only a point of comparison."""
     r = config_recipe(k, shrink)
+    if not relabel:
+        r["name"] += "-unrelabelled"
     n = r["n"]
     if r["kind"] == "er":
         indptr, indices = er_graph(n, r["avg_degree"], graph_seed, self_loops=r["self_loops"],
                                    symmetrise=r["symmetrise"])
     else:
         indptr, indices = rmat_graph(n, r["m"], graph_seed, symmetrise=r["symmetrise"],
-                                     self_loops=r["self_loops"])
+                                     self_loops=r["self_loops"], relabel=relabel)
     # unit edge values are represented by "no value array" (the kernels then read no values)
     vals = None if r["values"] == "unit" else edge_values(indptr, indices, r["values"])
     dd = d if d is not None else r["d"]

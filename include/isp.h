@@ -17,7 +17,9 @@
  *   - CSR: indptr int64[n_rows+1], indices int32[nnz], values fp32[nnz] or NULL (all ones).
  *     Columns inside a row may be unsorted and may repeat; a repeated column is a separate
  *     stored entry (SpMM adds them, SDDMM emits one output per stored entry).
- *   - Dense matrices are fp32 row-major; ld* is the distance between rows in elements (>= d).
+ *   - Dense matrices are fp32 row-major; ld* is the distance between rows in elements (>= d).  Any ld and
+ *     alignment is accepted; rows that start on 128-byte lines (ld a multiple of 32, base pointer aligned)
+ *     gather fastest.
  *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Compute calls are
  *     asynchronous on it.  isp_csr_build and a cache-missing isp_csr_transpose_cached
  *     synchronise the stream once, to read a few counters back.

@@ -276,7 +276,7 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
   // Wider rows run as 128-float slices.  ISP_SPMM_LPG overrides the choice for tuning.
   const bool large = av.nnz >= (int64_t)8 << 20 && av.n_cols >= (1 << 19);
   int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : 32);
-  if (large && d > 64 && d <= 128 && d % 64 == 0) lpg = 16;
+  if (large && d > 64 && d <= 128 && d % 64 == 0 && ldx % 32 == 0) lpg = 16;  // rows start on 128-byte lines
   if (const char* e = getenv("ISP_SPMM_LPG")) {
     const int v = atoi(e);
     if (v == 4 || v == 8 || v == 16 || v == 32 || v == 64) lpg = v;
