@@ -68,7 +68,7 @@ typedef struct {
   int64_t max_degree;
   int64_t bin_rows[5]; /* degree 0 | 1..4 | 5..32 | 33..hub_threshold | > hub_threshold (hub) */
   int64_t bin_nnz[5];
-  int32_t hub_threshold;  /* rows longer than this are split by nnz                */
+  int32_t hub_threshold;  /* rows longer than this are split by nnz (64..512, by size)*/
   int32_t segment_len;    /* most nonzeros a hub segment holds                     */
   int32_t block_cost;     /* target (nnz + rows) per wavefront work item            */
   int32_t n_row_blocks;   /* wavefront work items made of whole short rows          */

@@ -42,14 +42,21 @@ int env_int(const char* name, int dflt, int lo, int hi) {
   return (int)v;
 }
 
-partition_params get_params() {
+partition_params get_params(int64_t n_rows, int64_t nnz) {
   partition_params p;
   // Upper limits = what the grouped kernels' per-wave LDS tables hold (block_cost + hub_t <= 768
   // entries, block_cost <= 256 rows, seg_len <= 768 entries).  The environment overrides exist for
   // tuning and for tests that want many small work items.
-  p.block_cost = env_int("ISP_BLOCK_COST", 256, 16, 256);
-  p.hub_t = env_int("ISP_HUB_THRESHOLD", 512, 8, 512);
-  p.seg_len = env_int("ISP_SEGMENT_LEN", 512, 8, 768);
+  // Small matrices get smaller row blocks, about as many as the chip has wavefront slots (256 CUs x 16):
+  // a wavefront's work is a chain of dependent memory round trips, and a short chain on every slot
+  // finishes sooner than a long one on a few (4,096 rows x 9 entries: 16 -> 7 us per SpMM).
+  int64_t auto_cost = (nnz + n_rows + 4095) / 4096;
+  auto_cost = auto_cost < 16 ? 16 : (auto_cost > 256 ? 256 : auto_cost);
+  p.block_cost = env_int("ISP_BLOCK_COST", (int)auto_cost, 16, 256);
+  // ... and shorter hub segments for the same reason (a 512-entry segment is a chain of 32 gather groups)
+  const int auto_seg = 2 * auto_cost < 64 ? 64 : (int)(2 * auto_cost);
+  p.hub_t = env_int("ISP_HUB_THRESHOLD", auto_seg, 8, 512);
+  p.seg_len = env_int("ISP_SEGMENT_LEN", auto_seg, 8, 768);
   int b = env_int("ISP_BANDS", 32, 1, MAX_BANDS);
   while (b & (b - 1)) b &= b - 1;  // round down to a power of two
   p.bands = b;
@@ -346,12 +353,14 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
 
 }  // namespace
 
-size_t isp_partition_workspace(int64_t n_rows, int64_t nnz) { return make_layout(n_rows, nnz, get_params()).total; }
+size_t isp_partition_workspace(int64_t n_rows, int64_t nnz) {
+  return make_layout(n_rows, nnz, get_params(n_rows, nnz)).total;
+}
 
 isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
                             const int32_t* indices, const float* values, void* ws, size_t ws_bytes, bool validate,
                             hipStream_t s, isp_csr** out) {
-  const partition_params pp = get_params();
+  const partition_params pp = get_params(n_rows, nnz);
   const ws_layout L = make_layout(n_rows, nnz, pp);
   if (ws_bytes < L.total) return isp_fail(ISP_EINVAL, "workspace too small: %zu < %zu bytes", ws_bytes, L.total);
   if (((uintptr_t)ws & 255) != 0) return isp_fail(ISP_EINVAL, "workspace must be 256-byte aligned");
