@@ -366,3 +366,30 @@ def test_caller_owned_workspaces():
     assert torch.equal(Y1, Y2)
     A.destroy()
     B.destroy()
+
+
+@pytest.mark.parametrize("layout", ["ends", "one_row", "stripes", "tile_edges"])
+def test_transpose_with_long_runs_of_empty_rows(layout):
+    """The first sort pass rebuilds each tile's source rows from the row offsets: rows mark their first
+    entry, a running maximum spreads the marks.  Long runs of empty rows put thousands of row starts on one
+    position; rows that begin exactly on a sort-tile boundary (4096 entries) are the other edge."""
+    rng = np.random.default_rng(7)
+    n_rows, n_cols = 30_000, 900
+    deg = np.zeros(n_rows, dtype=np.int64)
+    if layout == "ends":          # entries only in the first and the last row
+        deg[0], deg[-1] = 6000, 7000
+    elif layout == "one_row":     # a single row in the middle owns every entry (several tiles)
+        deg[17_123] = 20_000
+    elif layout == "stripes":     # one row in a thousand is occupied
+        deg[::1000] = rng.integers(1, 3000, size=len(deg[::1000]))
+    else:                         # rows of exactly one tile, separated by runs of empty rows
+        deg[[5, 2000, 2001, 29_999]] = 4096
+    indptr = np.zeros(n_rows + 1, dtype=np.int64)
+    np.cumsum(deg, out=indptr[1:])
+    nnz = int(indptr[-1])
+    indices = rng.integers(0, n_cols, size=nnz).astype(np.int32)
+    values = rng.standard_normal(nnz).astype(np.float32)
+    A = build(indptr, indices, values, n_cols=n_cols)
+    _check_transpose(A, indptr, indices, values, n_rows, n_cols)
+    A.destroy()
+    _run_all_ops(indptr, indices, values, n_rows, n_cols, 8, seed=3, fused=False)
