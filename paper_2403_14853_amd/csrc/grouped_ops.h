@@ -113,7 +113,16 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
           if (live && q == 0) L.ent[gs_off(dsc[u]) + g].y = __float_as_int(val);
         } else {
           P::template edge<LPG>(pa, a[u], x[u], rr, acc, lane_on, live && lane_on);
-          if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
+          const unsigned ud = __builtin_amdgcn_readfirstlane(dsc[u]);
+          if (ud & GS_LAST) {
+            // an empty row (only its step ends a row without entries) adds nothing; acc is zero already
+            if (gs_cnt(ud) == 0) {
+              if (!P::ACCUMULATE && g == 0 && lane_on) store_vec<4>(out + (int64_t)row * ldo, acc);
+              ++row;
+            } else {
+              finish_row();
+            }
+          }
         }
       }
     };

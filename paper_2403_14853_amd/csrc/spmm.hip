@@ -170,7 +170,15 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] = fmaf(a[u], x[u][v], acc[v]);
       }
-      if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
+      const unsigned ud = __builtin_amdgcn_readfirstlane(dsc[u]);
+      if (ud & GS_LAST) {
+        if (gs_cnt(ud) == 0) {  // an empty row (only its step ends a row without entries): acc is zero already
+          if (g == 0 && lane_on) store_vec<VEC>(out + (int64_t)row * ldo, acc);
+          ++row;
+        } else {
+          finish_row();
+        }
+      }
     }
   };
 
