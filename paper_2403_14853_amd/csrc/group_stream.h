@@ -6,8 +6,9 @@
 // lanes; a group gathers one dense row slice of 4 * LPG floats with one float4 per lane, so a
 // single load instruction serves G nonzeros.  The item's (column, value) pairs are staged once
 // in LDS; a per-item step table, also in LDS, says for every step which G consecutive entries
-// it covers and whether it ends a row (a step never crosses a row boundary, every row - even
-// an empty one - owns at least one step).  The main loop is therefore flat: U steps are issued
+// it covers and whether it ends a row (a step never crosses a row boundary; an empty row owns one
+// step without entries or, in the kernels that ask for it, none: they zero its output beforehand, and a
+// list of the non-empty rows says which row each row end of the table belongs to).  The main loop is therefore flat: U steps are issued
 // back to back (LDS read -> address -> gather) before the first is consumed, independent of
 // where rows begin and end, which keeps short rows from serialising on memory latency.  When
 // a step ends a row the G group accumulators are summed with lane shuffles and group 0 writes
@@ -30,7 +31,7 @@ struct __attribute__((aligned(16))) gs_wave_lds {
   int2 ent[GS_MAX_ENT + 8];               // (column, value bits) of the item's nonzeros
   gs_u16 step[GS_MAX_STEPS + GS_U];       // step descriptors, padded with null steps
   gs_u16 rp[GS_MAX_ROWS + 8];             // row start offsets relative to the item
-  gs_u16 ss[GS_MAX_ROWS + 8];             // first step of each row
+  gs_u16 ss[GS_MAX_ROWS + 8];             // first step of each row; afterwards the list of non-empty rows
 };
 struct gs_lds { gs_wave_lds w[ISP_WAVES_PER_WG]; };
 
@@ -61,14 +62,18 @@ __device__ inline int wave_exclusive_scan_i(int v, int lane, int* total) {
 }
 
 // Stage the item's entries and build its step table.  Returns the number of steps, rounded up to
-// a multiple of GS_U with null steps (no live entry, not a row end).
+// a multiple of GS_U with null steps (no live entry, not a row end); 0 when the item has no entries.
+// SPARSE_ROWS: empty rows own no step, and ss ends up holding the local indices of the non-empty rows, in
+// order (the kernel zeroes the empty rows' outputs itself); otherwise an empty row owns one step without
+// entries.  rp holds the rows' start offsets.
 // entry_scale (optional): row offsets of another matrix; entry p is staged with its value divided by
 // the length of row indices[p] of that matrix (the backward of the mean reduction runs over the
 // transpose and needs the source rows' lengths).
-template <int G, bool HAS_VAL>
+template <int G, bool HAS_VAL, bool SPARSE_ROWS = false>
 __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict__ indptr,
                                  const int32_t* __restrict__ indices, const float* __restrict__ values,
                                  gs_wave_lds& L, int lane, const int64_t* __restrict__ entry_scale = nullptr) {
+  constexpr bool sparse_rows = SPARSE_ROWS;
   int2* __restrict__ ent = L.ent;
   gs_u16* __restrict__ step = L.step;
   gs_u16* __restrict__ rp = L.rp;
@@ -96,27 +101,37 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   }
   for (int r = lane; r <= n_rows; r += ISP_WAVE) rp[r] = (gs_u16)(indptr[it.row + r] - it.p);
   wave_lds_sync();
-  int carry = 0;
-  for (int c = 0; c < n_rows; c += ISP_WAVE) {
-    const int r = c + lane;
-    int ns = 0;
+  // steps per row (an empty row owns none) and the row's rank among the non-empty rows, scanned together:
+  // low half = steps, high half = non-empty rows
+  constexpr int CHUNKS = GS_MAX_ROWS / ISP_WAVE;
+  int carry = 0, rank[CHUNKS];
+#pragma unroll
+  for (int ci = 0; ci < CHUNKS; ++ci) rank[ci] = -1;
+#pragma unroll
+  for (int ci = 0; ci < CHUNKS; ++ci) {
+    if (ci * ISP_WAVE >= n_rows) break;  // (most items hold fewer than 64 rows: one scan)
+    const int r = ci * ISP_WAVE + lane;
+    int v = 0;
     if (r < n_rows) {
       const int len = (int)rp[r + 1] - (int)rp[r];
-      ns = len > 0 ? (len + G - 1) / G : 1;
+      // (without the list an empty row owns one step that ends it and has no entry)
+      v = len > 0 ? ((len + G - 1) / G) | (1 << 16) : (sparse_rows ? 0 : 1 | (1 << 16));
     }
     int tot;
-    const int ex = wave_exclusive_scan_i(ns, lane, &tot);
-    if (r < n_rows) ss[r] = (gs_u16)(carry + ex);
+    const int ex = wave_exclusive_scan_i(v, lane, &tot);
+    if (r < n_rows) ss[r] = (gs_u16)((carry + ex) & 0xffff);
+    rank[ci] = v ? (carry + ex) >> 16 : -1;
     carry += tot;
   }
-  const int n_steps = carry;
+  const int n_steps = carry & 0xffff;
+  const int n_live = carry >> 16;
   if (lane == 0) ss[n_rows] = (gs_u16)n_steps;
   wave_lds_sync();
   const int n_padded = (n_steps + GS_U - 1) / GS_U * GS_U;
   for (int s = lane; s < n_padded; s += ISP_WAVE) {
     gs_u16 dsc = 0;  // null step
     if (s < n_steps) {
-      int lo = 0, hi = n_rows;  // last row r with ss[r] <= s
+      int lo = 0, hi = n_rows;  // last row r with ss[r] <= s: the non-empty row that owns step s
       while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if ((int)ss[mid] <= s) lo = mid; else hi = mid;
@@ -129,6 +144,16 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
     step[s] = dsc;
   }
   wave_lds_sync();
+  // the step table is built: ss now lists the non-empty rows in order (ss[k] = local index of the k-th),
+  // which is where the k-th row end of the table belongs; one more entry for the null steps past the end.
+  // Without SPARSE_ROWS every row owns a step and the k-th row end belongs to row k.
+  if constexpr (sparse_rows) {
+#pragma unroll
+    for (int ci = 0; ci < CHUNKS; ++ci)
+      if (rank[ci] >= 0) ss[rank[ci]] = (gs_u16)(ci * ISP_WAVE + lane);
+    if (lane == 0) ss[n_live] = 0;
+    wave_lds_sync();
+  }
   return n_padded;
 }
 

@@ -31,7 +31,11 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   const item_range it = locate_item(A, indptr, item);
   if (it.skip) return;
   gs_wave_lds& L = lds.w[w];
-  const int n_steps = gs_prepare<G, HAS_VAL>(it, indptr, indices, values, L, lane);
+  // The policies with row results skip empty rows altogether (no step; the list of non-empty rows in L.ss
+  // says where each row end belongs): directed graphs leave many rows empty (half of them in the FusedMM
+  // benchmark graph).  The per-entry policy has no row results and keeps the plain table.
+  constexpr bool sparse_rows = !P::PER_ENTRY;
+  const int n_steps = gs_prepare<G, HAS_VAL, sparse_rows>(it, indptr, indices, values, L, lane);
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_lo + q * 4;
@@ -39,11 +43,23 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   const int coff = lane_on ? col : 0;
   float* __restrict__ out = it.is_seg ? A.partials + col : Y + col;
   const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
-  int row = it.row;          // output row (segment index for hub segments), advanced by consume
-  int irow = it.src_row;     // matrix row of the next step to issue
+  // An empty row owns no step.  The k-th row end of the step table belongs to the k-th non-empty row of the
+  // item, whose local index is L.ss[k] (a hub segment is its one row).
+  int k_done = 0;            // row ends consumed
+  const bool listed = sparse_rows && !it.is_seg;  // else the k-th row end belongs to row k
+  int r_next = listed ? (int)L.ss[0] : 0;      // read one row ahead (the list ends with a spare entry)
+  int k_issued = 0;          // row ends passed by the steps issued so far
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (!P::PER_ENTRY && !P::ACCUMULATE && listed && lane_on) {  // outputs of the empty rows
+    const int n_rows = it.row_last - it.row;
+    for (int r = g; r < n_rows; r += G)
+      if (L.rp[r + 1] == L.rp[r]) store_vec<4>(out + (int64_t)(it.row + r) * ldo, acc);
+  }
 
   auto finish_row = [&]() {
+    const int row = it.row + r_next;
+    ++k_done;
+    r_next = listed ? (int)L.ss[k_done] : k_done;
 #pragma unroll
     for (int v = 0; v < 4; ++v) acc[v] = group_sum<LPG>(acc[v]);
     if (g == 0 && lane_on) {
@@ -58,7 +74,6 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
     }
 #pragma unroll
     for (int v = 0; v < 4; ++v) acc[v] = 0.f;
-    ++row;
   };
   // SEG (a hub segment: one matrix row for the whole item): the row operand is loaded once and stays in
   // registers.  Row blocks re-read it with every step, which keeps their loop free of row-change stalls.
@@ -68,7 +83,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
     float rS[NROW][4];
     if constexpr (SEG) {
 #pragma unroll
-      for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + (int64_t)irow * pa.ldr[k] + coff, rS[k]);
+      for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + (int64_t)it.src_row * pa.ldr[k] + coff, rS[k]);
     }
     auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][NSRC][4], float (&r)[U][NR + 1][4], float (&a)[U]) {
       int2 e[U];
@@ -77,8 +92,9 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
       for (int u = 0; u < U; ++u) {
         dsc[u] = L.step[s0 + u];
         e[u] = L.ent[gs_off(dsc[u]) + g];
-        srow[u] = irow;
-        irow += (int)((dsc[u] >> 15) & 1u);  // a row end moves the following steps to the next row
+        // (null steps past the end read the spare 0 after the list, or name the row after the item's last)
+        if constexpr (!SEG) srow[u] = it.src_row + (sparse_rows ? (int)L.ss[k_issued] : k_issued);
+        k_issued += (int)((dsc[u] >> 15) & 1u);  // a row end moves the following steps to the next non-empty row
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -88,7 +104,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
 #pragma unroll
         for (int k = 0; k < NSRC; ++k) load_vec<4>(pa.src[k] + cj * pa.lds_[k] + coff, x[u][k]);
         if constexpr (!SEG) {
-          const int64_t ri = srow[u] < A.n_rows ? srow[u] : 0;  // null steps after the last row
+          const int64_t ri = srow[u] < A.n_rows ? srow[u] : 0;  // null steps after the matrix's last row
 #pragma unroll
           for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + ri * pa.ldr[k] + coff, r[u][k]);
         }
@@ -113,16 +129,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
           if (live && q == 0) L.ent[gs_off(dsc[u]) + g].y = __float_as_int(val);
         } else {
           P::template edge<LPG>(pa, a[u], x[u], rr, acc, lane_on, live && lane_on);
-          const unsigned ud = __builtin_amdgcn_readfirstlane(dsc[u]);
-          if (ud & GS_LAST) {
-            // an empty row (only its step ends a row without entries) adds nothing; acc is zero already
-            if (gs_cnt(ud) == 0) {
-              if (!P::ACCUMULATE && g == 0 && lane_on) store_vec<4>(out + (int64_t)row * ldo, acc);
-              ++row;
-            } else {
-              finish_row();
-            }
-          }
+          if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
         }
       }
     };
