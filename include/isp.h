@@ -113,6 +113,15 @@ isp_status isp_csr_transpose_workspace(const isp_csr_t* A, size_t* bytes);
 isp_status isp_csr_transpose_cached(isp_csr_t* A, void* workspace, size_t workspace_bytes,
                                     void* stream, const isp_csr_t** At, int* was_cached);
 
+/*
+ * Tell the handle that the caller has overwritten A's values array in place (same pointer, same structure),
+ * as happens every epoch when the edge values are trained from the SDDMM gradients.  What Section 3.3 caches
+ * stays cached - A^T's structure, its permutation and both work partitions - and only the transposed values
+ * are gathered again: t_values[q] = values[perm[q]], one asynchronous pass on `stream`.  A no-op for a handle
+ * without values or without a cached transpose.  A must be the source handle, not its transpose.
+ */
+isp_status isp_csr_values_changed(isp_csr_t* A, void* stream);
+
 /* Device pointers of a handle's CSR arrays (perm is NULL for a handle that is not a transpose;
  * values is NULL when absent).  Any out pointer may be NULL.  For inspection and tests. */
 isp_status isp_csr_export(const isp_csr_t* A, const int64_t** indptr, const int32_t** indices,

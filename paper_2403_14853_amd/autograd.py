@@ -21,8 +21,18 @@ class SparseGraph:
         self.indptr, self.indices, self.values = indptr, indices, values
         self.handle = _b.csr_build(indptr, indices, None if values is None else values.detach(), n_cols=n_cols)
         self.n_rows, self.n_cols, self.nnz = self.handle.n_rows, self.handle.n_cols, self.handle.nnz
+        self._values_version = None if values is None else values._version
+
+    def sync_values(self):
+        """The handle reads ``values``' storage directly.  When an optimizer step has rewritten it in place
+        since the last call, the cached transpose has to pick the new values up (its structure, permutation
+        and partition stay cached)."""
+        if self.values is not None and self.values._version != self._values_version:
+            _b.csr_values_changed(self.handle)
+            self._values_version = self.values._version
 
     def transpose(self):
+        self.sync_values()
         return _b.csr_transpose_cached(self.handle)[0]
 
 

@@ -14,7 +14,7 @@ _lib = None
 
 EXPORTED_SYMBOLS = [
     "isp_csr_build_workspace", "isp_csr_build", "isp_csr_transpose_workspace", "isp_csr_transpose_cached",
-    "isp_csr_export", "isp_csr_info", "isp_spmm", "isp_sddmm", "isp_fusedmm", "isp_fusedmm_backward",
+    "isp_csr_values_changed", "isp_csr_export", "isp_csr_info", "isp_spmm", "isp_sddmm", "isp_fusedmm", "isp_fusedmm_backward",
     "isp_spmm_reduce", "isp_spmm_reduce_backward", "isp_csr_destroy", "isp_last_error", "isp_version",
 ]
 
@@ -60,6 +60,7 @@ def load_library():
     lib.isp_csr_transpose_workspace.argtypes = [vp, P(sz)]
     lib.isp_csr_transpose_cached.argtypes = [vp, vp, sz, vp, P(vp), P(ctypes.c_int)]
     lib.isp_csr_export.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
+    lib.isp_csr_values_changed.argtypes = [vp, vp]
     lib.isp_csr_info.argtypes = [vp, P(CsrInfo)]
     lib.isp_spmm.argtypes = [vp, vp, i64, i32, vp, i64, vp]
     lib.isp_sddmm.argtypes = [vp, vp, i64, vp, i64, i32, u32, vp, vp]
@@ -233,6 +234,12 @@ def csr_transpose_cached(A: CSR, *, stream=None, workspace=None):
     A._keep.append(ws)
     A._At = CSR(At_h, A.n_cols, A.n_rows, A.nnz, [ws], owner=A)
     return A._At, bool(was.value)
+
+
+def csr_values_changed(A: CSR, *, stream=None):
+    """isp_csr_values_changed: the caller has rewritten A's values tensor in place; the cached transpose's
+    values are gathered again, everything else stays cached."""
+    _check(load_library().isp_csr_values_changed(A._h, _stream(stream)))
 
 
 def _ld(t):

@@ -454,7 +454,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->v.n_hub = h.n_hub; A->v.n_seg = h.n_seg;
   A->v.hub_t = pp.hub_t; A->v.seg_len = pp.seg_len;
   A->v.partials = (float*)(base + L.partials);
-  A->perm = nullptr; A->At = nullptr; A->is_transpose = false;
+  A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false;
   isp_csr_info_t& I = A->info;
   I.n_rows = n_rows; I.n_cols = n_cols; I.nnz = nnz; I.max_degree = (int64_t)h.max_degree;
   for (int b = 0; b < 5; ++b) { I.bin_rows[b] = (int64_t)h.bin_rows[b]; I.bin_nnz[b] = (int64_t)h.bin_nnz[b]; }

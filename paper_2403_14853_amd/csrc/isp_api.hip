@@ -85,6 +85,14 @@ isp_status isp_csr_transpose_cached(isp_csr_t* A, void* workspace, size_t worksp
   return ISP_OK;
 }
 
+isp_status isp_csr_values_changed(isp_csr_t* A, void* stream) {
+  if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");
+  if (A->is_transpose) return isp_fail(ISP_EINVAL, "pass the source handle, not its transpose");
+  isp_status st = check_device(A);
+  if (st != ISP_OK) return st;
+  return isp_transpose_refresh_values(A, (hipStream_t)stream);
+}
+
 isp_status isp_csr_export(const isp_csr_t* A, const int64_t** indptr, const int32_t** indices, const float** values,
                           const int32_t** perm) {
   if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");

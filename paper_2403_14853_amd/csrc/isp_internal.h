@@ -35,6 +35,7 @@ struct isp_view {
 struct isp_csr {
   isp_view v;
   const int32_t* perm;     // transposes only
+  float* t_values_rw;      // transposes only: the values array (in the workspace), writable
   isp_csr_info_t info;
   int device;
   isp_csr* At;             // cached transpose (owned), or NULL
@@ -69,6 +70,8 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
 // ---- transpose (transpose.hip) ---------------------------------------------------------------
 size_t isp_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_values);
 isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_t s);
+// Gather the cached transpose's values again from A's (rewritten) values.
+isp_status isp_transpose_refresh_values(isp_csr* A, hipStream_t s);
 
 // ---- compute (spmm.hip, sddmm.hip, fusedmm.hip) ------------------------------------------------
 isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,

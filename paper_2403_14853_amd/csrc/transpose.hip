@@ -215,6 +215,13 @@ __global__ void __launch_bounds__(256) k_col_offsets(const int32_t* __restrict__
     for (int64_t cc = (int64_t)c + 1; cc <= n_cols; ++cc) t_indptr[cc] = nnz;
 }
 
+// t_values[q] = values[perm[q]]
+__global__ void __launch_bounds__(256) k_gather_values(const int32_t* __restrict__ perm, const float* __restrict__ values,
+                                                       int64_t nnz, float* __restrict__ t_values) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q < nnz) t_values[q] = values[perm[q]];
+}
+
 __global__ void __launch_bounds__(256) k_fill_i64(int64_t* __restrict__ a, int64_t n, int64_t v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) a[i] = v;
@@ -316,9 +323,18 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
                                    ws_bytes - L.part, false, s, &At);
   if (st != ISP_OK) return st;
   At->perm = perm;
+  At->t_values_rw = t_values;
   At->is_transpose = true;
   At->info.is_transpose = 1;
   A->At = At;
   A->info.has_cached_transpose = 1;
+  return ISP_OK;
+}
+
+isp_status isp_transpose_refresh_values(isp_csr* A, hipStream_t s) {
+  isp_csr* At = A->At;
+  if (!At || !A->v.values || !At->t_values_rw || A->v.nnz == 0) return ISP_OK;
+  k_gather_values<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(At->perm, A->v.values, A->v.nnz, At->t_values_rw);
+  ISP_LAUNCH_CHECK();
   return ISP_OK;
 }

@@ -64,3 +64,32 @@ def test_fusedmm_autograd():
     (Y * dev(w.dY)).sum().backward()
     assert_close(Y.detach(), *oracle.fusedmm(w.indptr, w.indices, None, w.X), "fusedmm")
     assert_close(X.grad, *oracle.fusedmm_backward(w.indptr, w.indices, None, w.X, w.dY), "fusedmm dX")
+
+
+def test_trained_edge_values_reach_the_cached_transpose():
+    """Edge values as a trainable leaf: an in-place update between epochs must show up in the next
+    epoch's forward (the handle reads the tensor's storage) and backward (the cached transpose's values are
+    gathered again; structure and permutation stay cached)."""
+    from paper_2403_14853_amd import autograd as ag
+    w = graphgen.make_config(1, shrink=32)
+    values = dev(w.values).requires_grad_(True)
+    g = ag.SparseGraph(dev(w.indptr), dev(w.indices), values)
+    X = dev(w.X).requires_grad_(True)
+    W = dev(w.dY)
+    cur = w.values.copy()
+    for epoch in range(3):
+        values.grad = None
+        X.grad = None
+        Y = ag.spmm(g, X)
+        (Y * W).sum().backward()
+        ti, tj, perm, tv = oracle.transpose(w.n, w.n, w.indptr, w.indices, cur)
+        assert_close(Y.detach(), *oracle.spmm(w.indptr, w.indices, cur, w.X), "Y epoch %d" % epoch)
+        assert_close(X.grad, *oracle.spmm(ti, tj, tv, w.dY), "dX epoch %d" % epoch)
+        dA, mag = oracle.sddmm(w.indptr, w.indices, cur, w.dY, w.X)
+        assert_close(values.grad, dA, mag, "dA epoch %d" % epoch)
+        # the gradient step, taken from the oracle's gradient (no expected value may depend on the GPU path)
+        # and written into the leaf tensor in place, as an optimizer would
+        cur = (cur - 1e-3 * dA).astype(np.float32)
+        with torch.no_grad():
+            values.copy_(dev(cur))
+    assert g.handle.info()["has_cached_transpose"] == 1

@@ -393,3 +393,37 @@ def test_transpose_with_long_runs_of_empty_rows(layout):
     _check_transpose(A, indptr, indices, values, n_rows, n_cols)
     A.destroy()
     _run_all_ops(indptr, indices, values, n_rows, n_cols, 8, seed=3, fused=False)
+
+
+def test_values_changed_refreshes_the_cached_transpose(small_partition):
+    """Edge values trained between epochs: the caller rewrites the values in place and tells the handle; the
+    cached transpose keeps its structure, permutation and partition and carries the new values."""
+    w = graphgen.make_config(1, shrink=64)
+    ip, ix = dev(w.indptr), dev(w.indices)
+    va = dev(w.values)
+    A = isp.csr_build(ip, ix, va)
+    At, _ = isp.csr_transpose_cached(A)
+    G = np.random.default_rng(5).standard_normal((w.n, 24)).astype(np.float32)
+    Gd, dX = dev(G), torch.empty(w.n, 24, device="cuda")
+    new_vals = (w.values * 0.5 + 0.25).astype(np.float32)
+    va.copy_(dev(new_vals))            # same tensor, new contents (e.g. a gradient step on the edge values)
+    isp.csr_values_changed(A)
+    At2, was = isp.csr_transpose_cached(A)
+    assert was and At2 is At           # still the cached handle
+    ti, tj, tv, perm = At.export()
+    o_ti, o_tj, o_perm, o_tv = oracle.transpose(w.n, w.n, w.indptr, w.indices, new_vals)
+    assert np.array_equal(tv.cpu().numpy(), o_tv) and np.array_equal(perm.cpu().numpy(), o_perm)
+    isp.spmm(At, Gd, dX)
+    assert_close(dX, *oracle.spmm(o_ti, o_tj, o_tv, G), "spmm backward after the values changed")
+    Y = torch.empty(w.n, 24, device="cuda")
+    isp.spmm(A, Gd, Y)
+    assert_close(Y, *oracle.spmm(w.indptr, w.indices, new_vals, G), "spmm forward after the values changed")
+    with pytest.raises(isp.IspError):
+        isp.csr_values_changed(At)     # the transpose is not a source handle
+    # no values / no cached transpose: accepted, nothing to do
+    B = isp.csr_build(ip, ix, None)
+    isp.csr_values_changed(B)
+    isp.csr_transpose_cached(B)
+    isp.csr_values_changed(B)
+    A.destroy()
+    B.destroy()
