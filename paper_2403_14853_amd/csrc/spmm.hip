@@ -86,7 +86,9 @@ isp_status launch_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int
 // instruction.  Slice s of tile k_base covers columns [k_base + s * 4 * LPG, +4 * LPG).
 // ADDR32: every byte offset into X fits 32 bits and both factors of column * row-pitch fit 24 bits, so
 // the gather address is one full-rate 24-bit multiply-add on top of a scalar base pointer.
-template <int LPG, bool HAS_VAL, bool ADDR32, int VEC = 4>
+// SPARSE_ROWS: empty rows own no step (their output is zeroed up front and a list of the item's non-empty
+// rows says where each row end belongs); chosen for matrices in which many rows are empty.
+template <int LPG, bool HAS_VAL, bool ADDR32, int VEC = 4, bool SPARSE_ROWS = false>
 __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 4))) k_spmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                          const int32_t* __restrict__ indices,
                                                          const float* __restrict__ values,
@@ -106,8 +108,8 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const item_range it = locate_item(A, indptr, item);
   if (it.skip) return;
   gs_wave_lds& L = lds.w[w];
-  const int n_steps = gs_prepare<G, HAS_VAL>(it, indptr, indices, values, L, lane,
-                                             mean_mode == 2 ? src_indptr : nullptr);  // multiple of U
+  const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane,
+                                                          mean_mode == 2 ? src_indptr : nullptr);  // multiple of U
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_base + (slice * LPG + q) * VEC;
@@ -120,16 +122,28 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const unsigned pitch_byte = (unsigned)ldx * 4u;
   float* __restrict__ out = it.is_seg ? A.partials + (col - k_base) : Y + col;
   const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
-  int row = it.row;
   float acc[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+  const bool listed = SPARSE_ROWS && !it.is_seg;  // else every row owns a step and the k-th row end is row k's
+  if (listed && lane_on) {  // the empty rows' outputs (also their mean)
+    const int n_rows = it.row_last - it.row;
+    for (int r = g; r < n_rows; r += G)
+      if (L.rp[r + 1] == L.rp[r]) store_vec<VEC>(out + (int64_t)(it.row + r) * ldo, acc);
+  }
+  // local index of the row the next row end belongs to; with the list it is read one row ahead so that a
+  // row's store does not wait for it (the list ends with a spare entry)
+  int k_done = 0;
+  int r_next = listed ? (int)L.ss[0] : 0;
 
   auto finish_row = [&]() {
+    const int r_local = r_next;
+    const int row = it.row + r_local;
+    ++k_done;
+    r_next = listed ? (int)L.ss[k_done] : k_done;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = group_sum<LPG>(acc[v]);
     if (mean_mode == 1 && !it.is_seg) {  // hub segments keep plain partial sums; their fix-up divides
-      const int r_local = row - it.row;
       const int len = (int)L.rp[r_local + 1] - (int)L.rp[r_local];
       const float inv = len > 0 ? 1.f / (float)len : 0.f;
 #pragma unroll
@@ -138,7 +152,6 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
     if (g == 0 && lane_on) store_vec<VEC>(out + (int64_t)row * ldo, acc);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-    ++row;
   };
   // descriptors of U consecutive steps = one 16-byte LDS read
   auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][VEC], float (&a)[U]) {
@@ -170,15 +183,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] = fmaf(a[u], x[u][v], acc[v]);
       }
-      const unsigned ud = __builtin_amdgcn_readfirstlane(dsc[u]);
-      if (ud & GS_LAST) {
-        if (gs_cnt(ud) == 0) {  // an empty row (only its step ends a row without entries): acc is zero already
-          if (g == 0 && lane_on) store_vec<VEC>(out + (int64_t)row * ldo, acc);
-          ++row;
-        } else {
-          finish_row();
-        }
-      }
+      if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
     }
   };
 
@@ -213,9 +218,17 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * (unsigned)n_slices;
     const bool a32 = v.n_cols < (1 << 24) && ldx * 4 < (1 << 24) &&
                      ((uint64_t)v.n_cols * (uint64_t)ldx + (uint64_t)d) * 4u < ((uint64_t)1 << 32);
-#define ISP_GO(HV, A32) \
-  k_spmm_grouped<LPG, HV, A32, VEC><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, n_slices, Y, ldy, \
-                                                       mean_mode, src_indptr)
+    // the list of non-empty rows pays once a fair share of the rows is empty (directed graphs)
+    const bool sparse_rows = A->info.bin_rows[0] * 16 > A->info.n_rows;
+#define ISP_GO(HV, A32)                                                                                           \
+  do {                                                                                                            \
+    if (sparse_rows)                                                                                              \
+      k_spmm_grouped<LPG, HV, A32, VEC, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, \
+                                                                    k_base, n_slices, Y, ldy, mean_mode, src_indptr); \
+    else                                                                                                          \
+      k_spmm_grouped<LPG, HV, A32, VEC, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, \
+                                                                     k_base, n_slices, Y, ldy, mean_mode, src_indptr); \
+  } while (0)
     if constexpr (VEC < 4) {  // narrow lanes are only dispatched with 32-bit addressing
       if (v.values) ISP_GO(true, true); else ISP_GO(false, true);
     } else {
