@@ -59,3 +59,17 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libisp.so"))
     with pytest.raises(ImportError):
         binding.load_library()
+
+
+def test_header_is_plain_c(repo_root, tmp_path):
+    """include/isp.h is the boundary: it must compile as C99 on its own (no torch, no HIP, no C++)."""
+    import subprocess
+    src = tmp_path / "use_isp.c"
+    src.write_text('#include "isp.h"\n'
+                   "int main(void) {\n"
+                   "  isp_csr_t* a = 0; size_t b = 0; isp_csr_info_t info;\n"
+                   "  (void)info; (void)a;\n"
+                   "  return isp_csr_build_workspace(1, 1, 1, &b) == ISP_OK ? 0 : 1;\n"
+                   "}\n")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(repo_root, "include"), str(src)])
