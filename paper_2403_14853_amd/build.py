@@ -52,6 +52,14 @@ def build(verbose: bool = False) -> str:
     if res.returncode != 0:
         raise RuntimeError("hipcc failed on bw_probe.hip:\n" + res.stdout)
     os.replace(probe + ".tmp", probe)
+    # a consumer of the C ABI without Python or PyTorch (run by the GPU tests)
+    example = os.path.join(HERE, "abi_example")
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", *inc, os.path.join(CSRC, "abi_example.cpp"),
+                          "-L" + HERE, "-lisp", "-Wl,-rpath,$ORIGIN", "-o", example + ".tmp"],
+                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on abi_example.cpp:\n" + res.stdout)
+    os.replace(example + ".tmp", example)
     return LIB
 
 

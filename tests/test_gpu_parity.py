@@ -427,3 +427,14 @@ def test_values_changed_refreshes_the_cached_transpose(small_partition):
     isp.csr_values_changed(B)
     A.destroy()
     B.destroy()
+
+
+def test_c_abi_consumer_without_python():
+    """The stand-alone program built next to the library uses the C ABI with the HIP runtime only (no
+    Python, no PyTorch in its process) and checks SpMM, the cached-transpose backward and SDDMM itself."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(isp.lib_path()), "abi_example")
+    assert os.path.exists(exe), "abi_example is missing: run the build"
+    res = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=100)
+    print(res.stdout)
+    assert res.returncode == 0 and res.stdout.startswith("OK"), res.stdout
