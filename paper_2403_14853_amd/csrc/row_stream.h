@@ -270,4 +270,74 @@ __device__ inline void hub_fixup(const isp_view& A, int d, int k0, float* __rest
   }
 }
 
+// The same combination with one workgroup per hub row, for SpMM: a row cut into more than 32 segments
+// (a vertex adjacent to a large share of the graph) is split four ways, each wavefront adds a contiguous
+// quarter of the partial rows in order and the quarters are added in order - a fixed summation tree, so
+// still deterministic.  Shorter rows are summed by the first wavefront alone, in segment order.
+// MEAN: the sum is divided by the row's length (hub rows are never empty).
+template <int VEC, int T, bool MEAN>
+__device__ inline void hub_fixup_wg(const isp_view& A, int d, int k0, float* __restrict__ Y, int64_t ldy) {
+  __shared__ float part[ISP_WAVES_PER_WG][T][ISP_WAVE][VEC];
+  const int lane = threadIdx.x & (ISP_WAVE - 1), w = threadIdx.x >> 6;
+  const int h = blockIdx.x;
+  const int s0 = A.hub_seg_ptr[h], s1 = A.hub_seg_ptr[h + 1];
+  const bool split = s1 - s0 > 32;  // uniform over the workgroup
+  if (!split && w > 0) return;
+  const int q = split ? (s1 - s0 + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG : s1 - s0;
+  const int a = s0 + w * q, b = (a + q < s1) ? a + q : s1;
+  float acc[T][VEC];
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+    const int rel = (tt * ISP_WAVE + lane) * VEC;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[tt][v] = 0.f;
+    if (k0 + rel >= d) continue;
+    int s = a;
+    for (; s + 8 <= b; s += 8) {  // eight partial rows in flight, added in segment order
+      float t[8][VEC];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) load_vec<VEC>(A.partials + (int64_t)(s + u) * ISP_PARTIAL_TILE + rel, t[u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[tt][v] += t[u][v];
+    }
+    for (; s < b; ++s) {
+      float t[VEC];
+      load_vec<VEC>(A.partials + (int64_t)s * ISP_PARTIAL_TILE + rel, t);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[tt][v] += t[v];
+    }
+  }
+  if (split) {
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) part[w][tt][lane][v] = acc[tt][v];
+    __syncthreads();
+    if (w > 0) return;
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) {
+        float t = part[0][tt][lane][v];
+#pragma unroll
+        for (int ww = 1; ww < ISP_WAVES_PER_WG; ++ww) t += part[ww][tt][lane][v];
+        acc[tt][v] = t;
+      }
+  }
+  const int row = A.hub_rows[h];
+  const float inv = MEAN ? 1.f / (float)(A.indptr[row + 1] - A.indptr[row]) : 1.f;
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+    const int rel = (tt * ISP_WAVE + lane) * VEC;
+    if (k0 + rel >= d) continue;
+    if (MEAN) {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[tt][v] *= inv;
+    }
+    store_vec<VEC>(Y + (int64_t)row * ldy + k0 + rel, acc[tt]);
+  }
+}
+
 }  // namespace isp_dev

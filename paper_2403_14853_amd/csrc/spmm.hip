@@ -37,26 +37,16 @@ __global__ void __launch_bounds__(ISP_WG) k_spmm(isp_view A, const int64_t* __re
   stream_item<P>(A, indptr, indices, values, pa, d, k0, Y, ldy);
 }
 
+// One workgroup per hub row.
 template <int VEC, int T>
 __global__ void __launch_bounds__(ISP_WG) k_spmm_fixup(isp_view A, int d, int k0, float* __restrict__ Y, int64_t ldy) {
-  hub_fixup<VEC, T, false>(A, d, k0, Y, ldy);
+  hub_fixup_wg<VEC, T, false>(A, d, k0, Y, ldy);
 }
 
 // Mean reduction: the fixed-order sum of a hub row's segments, divided by the row's length.
 __global__ void __launch_bounds__(ISP_WG) k_spmm_fixup_mean(isp_view A, int d, int k0, float* __restrict__ Y,
                                                             int64_t ldy) {
-  hub_fixup<4, 1, false>(A, d, k0, Y, ldy);
-  const int lane = threadIdx.x & (ISP_WAVE - 1);
-  const int h = (int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6));
-  if (h >= A.n_hub || k0 + lane * 4 >= d) return;
-  const int row = A.hub_rows[h];
-  const float inv = 1.f / (float)(A.indptr[row + 1] - A.indptr[row]);  // a hub row is never empty
-  float* o = Y + (int64_t)row * ldy + k0 + lane * 4;  // written just above by this same lane
-  float t[4];
-  load_vec<4>(o, t);
-#pragma unroll
-  for (int v = 0; v < 4; ++v) t[v] *= inv;
-  store_vec<4>(o, t);
+  hub_fixup_wg<4, 1, true>(A, d, k0, Y, ldy);
 }
 
 template <int VEC, int T>
@@ -73,8 +63,7 @@ isp_status launch_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
-    const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    k_spmm_fixup<VEC, T><<<grid, ISP_WG, 0, s>>>(v, d, k0, Y, ldy);
+    k_spmm_fixup<VEC, T><<<(unsigned)v.n_hub, ISP_WG, 0, s>>>(v, d, k0, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   return ISP_OK;
@@ -239,9 +228,8 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
-    const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    if (mean_mode == 1) k_spmm_fixup_mean<<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);  // VEC = 4 only
-    else k_spmm_fixup<VEC, 4 / VEC><<<grid, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
+    if (mean_mode == 1) k_spmm_fixup_mean<<<(unsigned)v.n_hub, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);  // VEC = 4 only
+    else k_spmm_fixup<VEC, 4 / VEC><<<(unsigned)v.n_hub, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   return ISP_OK;
