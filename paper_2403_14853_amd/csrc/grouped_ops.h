@@ -1,9 +1,10 @@
 // Grouped kernels for the operations that need a whole dot product per nonzero (SDDMM and the
 // FusedMM passes).  Same work items, LDS staging and step tables as the grouped SpMM; here a
 // group of LPG lanes spans the full feature width (4 * LPG >= d), so G = 64 / LPG dot products
-// are reduced side by side with the same DPP instructions.  The row operand (U's row for SDDMM,
-// x_i / g_i for FusedMM) is re-read with every step instead of being kept across steps: it is an
-// L1 hit after a row's first step and keeps the main loop free of row-change stalls.
+// are reduced side by side with the same DPP instructions.  In row blocks the row operand (U's row
+// for SDDMM, x_i / g_i for FusedMM) is re-read with every step instead of being kept across steps: it
+// is an L1 hit after a row's first step and keeps the main loop free of row-change stalls; a hub
+// segment, which is one row throughout, loads it once.
 #pragma once
 #include <type_traits>
 #include "group_stream.h"
