@@ -7,10 +7,11 @@
 // single load instruction serves G nonzeros.  The item's (column, value) pairs are staged once
 // in LDS; a per-item step table, also in LDS, says for every step which G consecutive entries
 // it covers and whether it ends a row (a step never crosses a row boundary; an empty row owns one
-// step without entries or, in the kernels that ask for it, none: they zero its output beforehand, and a
-// list of the non-empty rows says which row each row end of the table belongs to).  The main loop is therefore flat: U steps are issued
-// back to back (LDS read -> address -> gather) before the first is consumed, independent of
-// where rows begin and end, which keeps short rows from serialising on memory latency.  When
+// step without entries or, in the kernels that ask for it, none: they zero its output beforehand,
+// and a list of the non-empty rows says which row each row end of the table belongs to).  The main
+// loop is therefore flat: U steps are issued back to back (LDS read -> address -> gather) before
+// the first is consumed, independent of where rows begin and end, which keeps short rows from
+// serialising on memory latency.  When
 // a step ends a row the G group accumulators are summed with lane shuffles and group 0 writes
 // the row slice.  Feature columns beyond one slice are covered by further workgroups
 // (blockIdx % n_slices), dealt round-robin to the XCDs.
