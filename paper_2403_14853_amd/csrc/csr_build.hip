@@ -120,7 +120,7 @@ __global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ in
                                                   const int32_t* __restrict__ indices, int64_t n_rows, int64_t n_cols,
                                                   int64_t nnz, partition_params pp, int32_t* __restrict__ cost,
                                                   int32_t* __restrict__ hubflag, int32_t* __restrict__ nseg,
-                                                  build_counters* __restrict__ ctr) {
+                                                  float* __restrict__ inv_len, build_counters* __restrict__ ctr) {
   __shared__ unsigned long long s_rows[5], s_nnz[5], s_max;
   __shared__ int s_err, s_seg;
   if (threadIdx.x < 5) { s_rows[threadIdx.x] = 0; s_nnz[threadIdx.x] = 0; }
@@ -153,6 +153,7 @@ __global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ in
     cost[i] = hub ? 0 : (int32_t)deg + 1;
     hubflag[i] = hub ? 1 : 0;
     nseg[i] = ns;
+    inv_len[i] = deg > 0 ? 1.f / (float)deg : 0.f;
     const int bin = degree_bin(deg, pp.hub_t);
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
@@ -306,7 +307,7 @@ __global__ void __launch_bounds__(SO_TILE) k_seg_scatter(const int32_t* __restri
 struct ws_layout {
   size_t counters, cost, hubflag, nseg, cum_cost, mark, mpos, hpos, segbase, scan_tmp;
   size_t blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin, seg_key[2], seg_order[2], so_table, so_scanned, so_tmp;
-  size_t partials, total;
+  size_t inv_len, partials, total;
   int64_t max_blocks, max_hub, max_seg;
 };
 
@@ -346,6 +347,7 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
   L.so_table = take((size_t)(so_tbl + 1) * 4);
   L.so_scanned = take((size_t)(so_tbl + 1) * 4);
   L.so_tmp = take(isp_scan_tmp_bytes(so_tbl + 1));
+  L.inv_len = take((size_t)(n_rows + 1) * 4);
   L.partials = take((size_t)(max_seg + 1) * ISP_PARTIAL_TILE * sizeof(float));
   L.total = off;
   return L;
@@ -389,7 +391,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   const unsigned row_grid = (unsigned)((n_rows + 255) / 256);
   if (n_rows > 0) {
     k_row_pass<<<row_grid < 2048 ? row_grid : 2048, 256, 0, s>>>(indptr, indices, n_rows, n_cols, nnz, pp, cost,
-                                                                 hubflag, nseg, ctr);
+                                                                 hubflag, nseg, (float*)(base + L.inv_len), ctr);
     ISP_LAUNCH_CHECK();
   }
   if (validate && nnz > 0) {
@@ -454,6 +456,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->v.n_hub = h.n_hub; A->v.n_seg = h.n_seg;
   A->v.hub_t = pp.hub_t; A->v.seg_len = pp.seg_len;
   A->v.partials = (float*)(base + L.partials);
+  A->v.inv_len = (const float*)(base + L.inv_len);
   A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false;
   isp_csr_info_t& I = A->info;
   I.n_rows = n_rows; I.n_cols = n_cols; I.nnz = nnz; I.max_degree = (int64_t)h.max_degree;

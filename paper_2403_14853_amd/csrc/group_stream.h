@@ -67,13 +67,13 @@ __device__ inline int wave_exclusive_scan_i(int v, int lane, int* total) {
 // SPARSE_ROWS: empty rows own no step, and ss ends up holding the local indices of the non-empty rows, in
 // order (the kernel zeroes the empty rows' outputs itself); otherwise an empty row owns one step without
 // entries.  rp holds the rows' start offsets.
-// entry_scale (optional): row offsets of another matrix; entry p is staged with its value divided by
-// the length of row indices[p] of that matrix (the backward of the mean reduction runs over the
-// transpose and needs the source rows' lengths).
+// entry_scale (optional): reciprocal row lengths of another matrix; entry p is staged with its value
+// multiplied by entry_scale[indices[p]] (the backward of the mean reduction runs over the transpose and
+// needs the source rows' lengths).
 template <int G, bool HAS_VAL, bool SPARSE_ROWS = false>
 __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict__ indptr,
                                  const int32_t* __restrict__ indices, const float* __restrict__ values,
-                                 gs_wave_lds& L, int lane, const int64_t* __restrict__ entry_scale = nullptr) {
+                                 gs_wave_lds& L, int lane, const float* __restrict__ entry_scale = nullptr) {
   constexpr bool sparse_rows = SPARSE_ROWS;
   int2* __restrict__ ent = L.ent;
   gs_u16* __restrict__ step = L.step;
@@ -84,7 +84,7 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
     int2 e;
     e.x = __builtin_nontemporal_load(indices + it.p + i);
     float val = HAS_VAL ? __builtin_nontemporal_load(values + it.p + i) : 1.f;
-    if (entry_scale) val /= (float)(entry_scale[e.x + 1] - entry_scale[e.x]);  // >= 1: the entry lies in that row
+    if (entry_scale) val *= entry_scale[e.x];
     e.y = __float_as_int(val);
     ent[i] = e;
   }

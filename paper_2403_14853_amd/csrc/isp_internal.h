@@ -30,6 +30,7 @@ struct isp_view {
   int32_t n_hub, n_seg;
   int32_t hub_t, seg_len;
   float* partials;         // n_seg * ISP_PARTIAL_TILE floats
+  const float* inv_len;    // n_rows: 1 / (stored entries of the row), 0 for an empty row
 };
 
 struct isp_csr {
@@ -78,9 +79,9 @@ isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_
                            hipStream_t s);
 // Grouped fast path of SpMM; *done = false (nothing launched) when the operands do not qualify.
 // mean_mode 0: plain sum; 1: rows divided by their length; 2: entries divided by the length of row
-// indices[p] of the matrix whose row offsets are src_indptr.
+// indices[p] of the source matrix, given as that matrix's reciprocal row lengths src_inv_len.
 isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                                   int mean_mode, const int64_t* src_indptr, hipStream_t s, bool* done);
+                                   int mean_mode, const float* src_inv_len, hipStream_t s, bool* done);
 isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv,
                             int32_t d, bool scale, float* out, hipStream_t s);
 isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,

@@ -83,9 +83,9 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
                                                          const float* __restrict__ values,
                                                          const float* __restrict__ X, int64_t ldx, int d, int k_base,
                                                          int n_slices, float* __restrict__ Y, int64_t ldy, int mean_mode,
-                                                         const int64_t* __restrict__ src_indptr) {
+                                                         const float* __restrict__ src_inv_len) {
   // mean_mode 1: divide every finished row by its length (mean reduction, forward);
-  // mean_mode 2: stage every entry divided by the length of source row indices[p] (its backward)
+  // mean_mode 2: stage every entry times the reciprocal length of source row indices[p] (its backward)
   constexpr int G = ISP_WAVE / LPG;
   constexpr int U = GS_U;
   __shared__ gs_lds lds;
@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   if (it.skip) return;
   gs_wave_lds& L = lds.w[w];
   const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane,
-                                                          mean_mode == 2 ? src_indptr : nullptr);  // multiple of U
+                                                          mean_mode == 2 ? src_inv_len : nullptr);  // multiple of U
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_base + (slice * LPG + q) * VEC;
@@ -200,7 +200,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 
 template <int LPG, int VEC = 4>
 isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, int k_base, int n_slices, float* Y,
-                          int64_t ldy, int mean_mode, const int64_t* src_indptr, hipStream_t s) {
+                          int64_t ldy, int mean_mode, const float* src_inv_len, hipStream_t s) {
   const isp_view& v = A->v;
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
@@ -213,10 +213,10 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
   do {                                                                                                            \
     if (sparse_rows)                                                                                              \
       k_spmm_grouped<LPG, HV, A32, VEC, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, \
-                                                                    k_base, n_slices, Y, ldy, mean_mode, src_indptr); \
+                                                                    k_base, n_slices, Y, ldy, mean_mode, src_inv_len); \
     else                                                                                                          \
       k_spmm_grouped<LPG, HV, A32, VEC, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, \
-                                                                     k_base, n_slices, Y, ldy, mean_mode, src_indptr); \
+                                                                     k_base, n_slices, Y, ldy, mean_mode, src_inv_len); \
   } while (0)
     if constexpr (VEC < 4) {  // narrow lanes are only dispatched with 32-bit addressing
       if (v.values) ISP_GO(true, true); else ISP_GO(false, true);
@@ -240,9 +240,9 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 }  // namespace
 
 // The grouped fast path; *done = false (and nothing launched) when the operands do not qualify.
-// mean_mode / src_indptr: see k_spmm_grouped.
+// mean_mode / src_inv_len: see k_spmm_grouped.
 isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                                   int mean_mode, const int64_t* src_indptr, hipStream_t s, bool* done) {
+                                   int mean_mode, const float* src_inv_len, hipStream_t s, bool* done) {
   const isp_view& av = A->v;
   // Lane width: float4 when width, pitch and pointers allow; float2 / float lanes otherwise (any d),
   // those two only with 32-bit addressing and for the plain sum.
@@ -295,11 +295,11 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
     const int w = (d - k_base < ISP_PARTIAL_TILE) ? d - k_base : ISP_PARTIAL_TILE;
     const int ns = (w + 4 * lpg - 1) / (4 * lpg);
     switch (lpg) {
-      case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
-      case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
-      case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
-      case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
-      default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_indptr, s); break;
+      case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
+      case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
+      case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
+      case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
+      default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
     }
   }
   return st;

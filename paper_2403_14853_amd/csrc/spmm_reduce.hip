@@ -254,7 +254,7 @@ isp_status isp_spmm_reduce_bwd_launch(const isp_csr* A, const float* dY, int64_t
   const isp_csr* At = A->At;
   if (reduce == R_MEAN) {  // the tuned kernel on A^T with every entry divided by its source row's length
     bool done = false;
-    const isp_status st = isp_spmm_grouped_launch(At, dY, lddy, d, dX, lddx, 2, A->v.indptr, s, &done);
+    const isp_status st = isp_spmm_grouped_launch(At, dY, lddy, d, dX, lddx, 2, A->v.inv_len, s, &done);
     if (done || st != ISP_OK) return st;
   }
   const bool hv = At->v.values != nullptr;
