@@ -328,6 +328,20 @@ def test_hub_rows_cut_at_column_bands(bands, min_piece, sorted_cols):
         assert info["n_segments"] >= plain
         if bands == 1:
             assert info["n_segments"] == plain
+        if sorted_cols:  # the cut rule, restated: segments of every band piece of every hub row
+            mp = min_piece if min_piece is not None else 8  # default: half the segment length
+            bw = -(-n_cols // bands)
+            want = 0
+            for i, k in enumerate(deg):
+                if k <= 16:
+                    continue
+                br = 1
+                while br * 2 <= bands and br * 2 * mp <= k:
+                    br *= 2
+                step = bands // br
+                cuts = [0] + [int(np.searchsorted(cols[i], j * step * bw, side="left")) for j in range(1, br)] + [int(k)]
+                want += sum(-(-(b - a) // 16) for a, b in zip(cuts[:-1], cuts[1:]) if b > a)
+            assert info["n_segments"] == want
         A.destroy()
         for d in (4, 32, 128):
             _run_all_ops(indptr, indices, values, n_rows, n_cols, d, seed=d, fused=False)
