@@ -158,23 +158,33 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv, int32_t d,
                             bool scale, float* out, hipStream_t s) {
   const isp_view& av = A->v;
-  const bool grouped_ok = d <= ISP_PARTIAL_TILE && d % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 && aligned(U, 16) &&
+  const bool grouped_ok = d % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 && aligned(U, 16) &&
                           aligned(V, 16) && A->info.block_cost <= GS_MAX_ROWS &&
                           A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT &&
                           !getenv("ISP_NO_GROUPED");
   if (grouped_ok) {
-    // Large graphs with many columns, 128-wide rows: two passes over 64-column halves, the second adding
-    // its partial dot products.  Every L2 then holds half-rows of twice as many hot columns (the same
-    // effect, under the same conditions, as the two column slices of SpMM).
-    if (av.nnz >= ((int64_t)8 << 20) && av.n_cols >= (1 << 19) && d == 2 * ISP_WAVE && !getenv("ISP_SDDMM_ONE_PASS")) {
-      isp_status st = launch_grouped<16>(A, U, ldu, V, ldv, 0, ISP_WAVE, false, scale, out, s);
-      if (st != ISP_OK) return st;
-      return launch_grouped<16>(A, U, ldu, V, ldv, ISP_WAVE, d, true, scale, out, s);
+    // One pass covers a window of the feature columns; later passes add their partial dot products.
+    //  - big graphs with many columns, rows of whole 64-float halves: 64-column passes, so that every L2 holds
+    //    half-rows of twice as many hot columns (the same effect, under the same conditions, as the column
+    //    slices of SpMM);
+    //  - otherwise rows wider than 128 floats go 128 columns at a time on the big graphs, 256 on the others.
+    const bool big = av.nnz >= ((int64_t)8 << 20);
+    int wp = d;
+    if (big && av.n_cols >= (1 << 19) && d > ISP_WAVE && d % ISP_WAVE == 0 && ldu % 32 == 0 && ldv % 32 == 0 &&
+        !getenv("ISP_SDDMM_ONE_PASS"))
+      wp = ISP_WAVE;
+    else if (big && d > 2 * ISP_WAVE) wp = 2 * ISP_WAVE;
+    else if (d > ISP_PARTIAL_TILE) wp = ISP_PARTIAL_TILE;
+    isp_status st = ISP_OK;
+    for (int k_lo = 0; k_lo < d && st == ISP_OK; k_lo += wp) {
+      const int k_hi = k_lo + wp < d ? k_lo + wp : d, w = k_hi - k_lo;
+      const bool add = k_lo > 0;
+      if (w <= 32) st = launch_grouped<8>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+      else if (w <= 64) st = launch_grouped<16>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+      else if (w <= 128) st = launch_grouped<32>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+      else st = launch_grouped<64>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
     }
-    if (d <= 32) return launch_grouped<8>(A, U, ldu, V, ldv, 0, d, false, scale, out, s);
-    if (d <= 64) return launch_grouped<16>(A, U, ldu, V, ldv, 0, d, false, scale, out, s);
-    if (d <= 128) return launch_grouped<32>(A, U, ldu, V, ldv, 0, d, false, scale, out, s);
-    return launch_grouped<64>(A, U, ldu, V, ldv, 0, d, false, scale, out, s);
+    return st;
   }
   int vec = 1;
   if (d > 2 * ISP_WAVE && d % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 && aligned(U, 16) && aligned(V, 16)) vec = 4;

@@ -228,8 +228,10 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
-    if (mean_mode == 1) k_spmm_fixup_mean<<<(unsigned)v.n_hub, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);  // VEC = 4 only
-    else k_spmm_fixup<VEC, 4 / VEC><<<(unsigned)v.n_hub, ISP_WG, 0, s>>>(v, d, k_base, Y, ldy);
+    // the columns this launch covered: [k_base, min(d, k_base + n_slices * LPG * VEC))
+    const int d_hi = (k_base + n_slices * LPG * VEC < d) ? k_base + n_slices * LPG * VEC : d;
+    if (mean_mode == 1) k_spmm_fixup_mean<<<(unsigned)v.n_hub, ISP_WG, 0, s>>>(v, d_hi, k_base, Y, ldy);  // VEC = 4 only
+    else k_spmm_fixup<VEC, 4 / VEC><<<(unsigned)v.n_hub, ISP_WG, 0, s>>>(v, d_hi, k_base, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   return ISP_OK;
@@ -282,17 +284,23 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
   // row win (dealt to alternating XCDs, each L2 then keeps half-rows of twice as many hot columns,
   // which outweighs staging the CSR arrays twice) provided both halves are whole 128-byte lines.  With
   // few columns (233 k measured) a column band's hot rows fit an L2 whole and one slice is faster.
-  // Wider rows run as 128-float slices.  ISP_SPMM_LPG overrides the choice for tuning.
-  const bool large = av.nnz >= (int64_t)8 << 20 && av.n_cols >= (1 << 19);
+  // ISP_SPMM_LPG / ISP_SPMM_TILE override the choices for tuning.
+  const bool big = av.nnz >= (int64_t)8 << 20;
+  const bool large = big && av.n_cols >= (1 << 19);
   int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : 32);
-  if (large && d > 64 && d <= 128 && d % 64 == 0 && ldx % 32 == 0) lpg = 16;  // rows start on 128-byte lines
+  // columns per launch: rows wider than 128 floats are covered 128 columns at a time on the big graphs
+  // (233 k columns, d = 256: 5.7 vs 6.0 ms; 2.4 M columns: 10.8 vs 12.1 ms)
+  const int tile_dflt = big ? 128 : ISP_PARTIAL_TILE;
+  int tile = tile_dflt;
+  if (large && d > 64 && d % 64 == 0 && ldx % 32 == 0) lpg = 16;  // (rows start on 128-byte lines)
   if (const char* e = getenv("ISP_SPMM_LPG")) {
     const int v = atoi(e);
     if (v == 4 || v == 8 || v == 16 || v == 32 || v == 64) lpg = v;
   }
   isp_status st = ISP_OK;
-  for (int k_base = 0; k_base < d && st == ISP_OK; k_base += ISP_PARTIAL_TILE) {
-    const int w = (d - k_base < ISP_PARTIAL_TILE) ? d - k_base : ISP_PARTIAL_TILE;
+  if (const char* e = getenv("ISP_SPMM_TILE")) { const int v = atoi(e); if (v == 64 || v == 128 || v == 256) tile = v; }
+  for (int k_base = 0; k_base < d && st == ISP_OK; k_base += tile) {
+    const int w = (d - k_base < tile) ? d - k_base : tile;
     const int ns = (w + 4 * lpg - 1) / (4 * lpg);
     switch (lpg) {
       case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
