@@ -130,3 +130,29 @@ def test_sddmm_config3_full_two_column_passes():
     ref, mag = oracle.sddmm(w.indptr, w.indices, w.values, w.dY, w.X, scale_by_a=True)
     assert_close(dA, ref, mag, "sddmm scaled")
     A.destroy()
+
+
+def test_wide_features_on_the_big_graph():
+    """Rows wider than 128 floats on a graph of > 8 Mi entries: SpMM covers 128 columns per launch (the last
+    launch 64 here) and SDDMM runs as 64-column passes that add up.  Every output against the oracle."""
+    _say("config 3 at d = 192: generating")
+    w = graphgen.make_config(3, d=192)
+    A = build(w.indptr, w.indices, w.values)
+    X, dY = dev(w.X), dev(w.dY)
+    Y = torch.full_like(X, float("nan"))
+    isp.spmm(A, X, Y)
+    _say("spmm: oracle")
+    ref, mag = oracle.spmm(w.indptr, w.indices, w.values, w.X)
+    assert_close(Y, ref, mag, "spmm d=192")
+    del ref, mag
+    isp.spmm_reduce(A, X, Y, "mean")
+    _say("mean: oracle")
+    ref, _, mag = oracle.spmm_reduce(w.indptr, w.indices, w.values, w.X, "mean")
+    assert_close(Y, ref, mag, "mean d=192")
+    del ref, mag
+    dA = torch.full((w.nnz,), float("nan"), device="cuda")
+    isp.sddmm(A, dY, X, dA)
+    _say("sddmm: oracle")
+    ref, mag = oracle.sddmm(w.indptr, w.indices, w.values, w.dY, w.X)
+    assert_close(dA, ref, mag, "sddmm d=192")
+    A.destroy()
