@@ -94,20 +94,36 @@ __global__ void __launch_bounds__(ISP_WG) k_reduce_fixup(isp_view A, int d, int 
   int where[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) { best[v] = 0.f; where[v] = -1; }
-  for (int s = s0; s < s1; ++s) {
-    const float* pr = A.partials + (int64_t)s * ISP_PARTIAL_TILE + rel;
+  auto combine = [&](const float (&t)[VEC], const float (&wbits)[VEC]) {
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-      const float t = pr[v];
       if (MODE == R_MEAN) {
-        best[v] += t;
+        best[v] += t[v];
       } else {
-        const int w = __float_as_int(pr[ARG_OFF + v]);
-        const bool take = where[v] < 0 || (MODE == R_MIN ? t < best[v] : t > best[v]);
-        best[v] = take ? t : best[v];
-        where[v] = take ? w : where[v];
+        const bool take = where[v] < 0 || (MODE == R_MIN ? t[v] < best[v] : t[v] > best[v]);
+        best[v] = take ? t[v] : best[v];
+        where[v] = take ? __float_as_int(wbits[v]) : where[v];
       }
     }
+  };
+  int s = s0;
+  for (; s + 8 <= s1; s += 8) {  // eight segments' partial rows in flight, combined in segment order
+    float t[8][VEC], wb[8][VEC];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float* pr = A.partials + (int64_t)(s + u) * ISP_PARTIAL_TILE + rel;
+      load_vec<VEC>(pr, t[u]);
+      if (MODE != R_MEAN) load_vec<VEC>(pr + ARG_OFF, wb[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) combine(t[u], wb[u]);
+  }
+  for (; s < s1; ++s) {
+    const float* pr = A.partials + (int64_t)s * ISP_PARTIAL_TILE + rel;
+    float t[VEC], wb[VEC];
+    load_vec<VEC>(pr, t);
+    if (MODE != R_MEAN) load_vec<VEC>(pr + ARG_OFF, wb);
+    combine(t, wb);
   }
   if (MODE == R_MEAN) {
     const int64_t len = A.indptr[row + 1] - A.indptr[row];
