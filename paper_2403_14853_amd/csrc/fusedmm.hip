@@ -159,7 +159,7 @@ struct g_args21 { const float* src[2]; int64_t lds_[2]; const float* rowop[1]; i
 
 template <int OP>
 struct g_fwd {  // gathered x_j, row operand x_i
-  static constexpr int NSRC = 1, NROW = 1;
+  static constexpr int NSRC = 1, NROW = 1, STEPS = 4;
   static constexpr bool PER_ENTRY = false, ACCUMULATE = false;
   using args = g_args1;
   template <int LPG>
@@ -177,7 +177,7 @@ struct g_fwd {  // gathered x_j, row operand x_i
 
 template <int OP>
 struct g_bwd_row {  // gathered x_j, row operands x_i and g_i:  dX_i += dz x_j
-  static constexpr int NSRC = 1, NROW = 2;
+  static constexpr int NSRC = 1, NROW = 2, STEPS = 3;  // (three operand rows per step: three steps per buffer keep four waves resident)
   static constexpr bool PER_ENTRY = false, ACCUMULATE = false;
   using args = g_args12;
   template <int LPG>
@@ -198,7 +198,7 @@ struct g_bwd_row {  // gathered x_j, row operands x_i and g_i:  dX_i += dz x_j
 
 template <int OP>
 struct g_bwd_col {  // over A^T: gathered x_i and g_i, row operand x_j:  dX_j += a s g_i + dz x_i
-  static constexpr int NSRC = 2, NROW = 1;
+  static constexpr int NSRC = 2, NROW = 1, STEPS = 3;
   static constexpr bool PER_ENTRY = false, ACCUMULATE = true;
   using args = g_args21;
   template <int LPG>

@@ -63,18 +63,20 @@ __device__ inline int wave_exclusive_scan_i(int v, int lane, int* total) {
 }
 
 // Stage the item's entries and build its step table.  Returns the number of steps, rounded up to
-// a multiple of GS_U with null steps (no live entry, not a row end); 0 when the item has no entries.
+// a multiple of PAD (the caller's steps per issue, at most GS_U) with null steps (no live entry, not a
+// row end); 0 when the item has no entries.
 // SPARSE_ROWS: empty rows own no step, and ss ends up holding the local indices of the non-empty rows, in
 // order (the kernel zeroes the empty rows' outputs itself); otherwise an empty row owns one step without
 // entries.  rp holds the rows' start offsets.
 // entry_scale (optional): reciprocal row lengths of another matrix; entry p is staged with its value
 // multiplied by entry_scale[indices[p]] (the backward of the mean reduction runs over the transpose and
 // needs the source rows' lengths).
-template <int G, bool HAS_VAL, bool SPARSE_ROWS = false>
+template <int G, bool HAS_VAL, bool SPARSE_ROWS = false, int PAD = GS_U>
 __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict__ indptr,
                                  const int32_t* __restrict__ indices, const float* __restrict__ values,
                                  gs_wave_lds& L, int lane, const float* __restrict__ entry_scale = nullptr) {
   constexpr bool sparse_rows = SPARSE_ROWS;
+  static_assert(PAD >= 1 && PAD <= GS_U, "the step table has room for GS_U null steps");
   int2* __restrict__ ent = L.ent;
   gs_u16* __restrict__ step = L.step;
   gs_u16* __restrict__ rp = L.rp;
@@ -92,7 +94,7 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   if (it.is_seg) {
     // one row, no table to search: step s covers entries [s * G, s * G + G), the last one ends the row
     const int n_steps = (n_ent + G - 1) / G;
-    const int n_padded = (n_steps + GS_U - 1) / GS_U * GS_U;
+    const int n_padded = (n_steps + PAD - 1) / PAD * PAD;
     for (int s = lane; s < n_padded; s += ISP_WAVE) {
       const int left = n_ent - s * G;
       step[s] = s < n_steps ? gs_pack(s * G, left >= G ? G : left, s + 1 == n_steps) : (gs_u16)0;
@@ -128,7 +130,7 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   const int n_live = carry >> 16;
   if (lane == 0) ss[n_rows] = (gs_u16)n_steps;
   wave_lds_sync();
-  const int n_padded = (n_steps + GS_U - 1) / GS_U * GS_U;
+  const int n_padded = (n_steps + PAD - 1) / PAD * PAD;
   for (int s = lane; s < n_padded; s += ISP_WAVE) {
     gs_u16 dsc = 0;  // null step
     if (s < n_steps) {

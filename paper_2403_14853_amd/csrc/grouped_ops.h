@@ -12,7 +12,7 @@
 namespace isp_dev {
 
 // Policy P:  NSRC gathered operands (rows picked by column index), NROW row operands (rows picked
-// by the step's matrix row); args { src[NSRC], lds_[NSRC], rowop[NROW], ldr[NROW], out_entry };
+// by the step's matrix row); STEPS steps issued back to back per buffer (two buffers in flight); args { src[NSRC], lds_[NSRC], rowop[NROW], ldr[NROW], out_entry };
 // either edge<LPG>(args, a, src, rowop, acc, lane_on, live) accumulating into the row's result in live
 // lanes, or (PER_ENTRY) entry<LPG>(a, src, rowop, lane_on) returning the value stored for the entry.
 template <class P, int LPG, bool HAS_VAL>
@@ -24,7 +24,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   // their partial dot products are then added up across passes)
   constexpr int G = ISP_WAVE / LPG;
   constexpr int NSRC = P::NSRC, NROW = P::NROW;
-  constexpr int U = 4;  // steps in flight per buffer; two buffers
+  constexpr int U = P::STEPS;  // steps in flight per buffer; two buffers
   const int lane = threadIdx.x & (ISP_WAVE - 1);
   const int w = threadIdx.x >> 6;
   const int item = __builtin_amdgcn_readfirstlane((int)blockIdx.x * ISP_WAVES_PER_WG + w);
@@ -36,7 +36,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   // says where each row end belongs): directed graphs leave many rows empty (half of them in the FusedMM
   // benchmark graph).  The per-entry policy has no row results and keeps the plain table.
   constexpr bool sparse_rows = !P::PER_ENTRY;
-  const int n_steps = gs_prepare<G, HAS_VAL, sparse_rows>(it, indptr, indices, values, L, lane);
+  const int n_steps = gs_prepare<G, HAS_VAL, sparse_rows, U>(it, indptr, indices, values, L, lane);
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_lo + q * 4;

@@ -94,7 +94,7 @@ __global__ void __launch_bounds__(ISP_WG) k_sddmm(isp_view A, const int64_t* __r
 // ADD: this pass covers a window of the feature columns and adds its partial dot product to out.
 template <bool SCALE, bool ADD_ = false>
 struct sddmm_policy {
-  static constexpr int NSRC = 1, NROW = 1;
+  static constexpr int NSRC = 1, NROW = 1, STEPS = 4;
   static constexpr bool PER_ENTRY = true, ACCUMULATE = false, ADD = ADD_;
   struct args { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
   template <int LPG>
