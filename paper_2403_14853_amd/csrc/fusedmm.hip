@@ -11,7 +11,8 @@
 namespace {
 using namespace isp_dev;
 
-__device__ inline float sigmoidf_fast(float z) { return 1.f / (1.f + __expf(-z)); }
+// (hardware exponential and reciprocal, about 1 ulp each; exp overflow gives 1 / inf = 0)
+__device__ inline float sigmoidf_fast(float z) { return __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
 
 // Edge function s = f(z) and its derivative; op is wave-uniform (ISP_OP_SIGMOID / _DOT / _ONE).
 // The grouped kernels pass it as a compile-time constant, the generic ones at run time.
@@ -218,13 +219,13 @@ struct g_bwd_col {  // over A^T: gathered x_i and g_i, row operand x_j:  dX_j +=
   }
 };
 
-template <class P, int LPG, bool HAS_VAL>
+template <class P, int LPG, bool ADDR32>
 __global__ void __launch_bounds__(ISP_WG) k_fused_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                           const int32_t* __restrict__ indices,
                                                           const float* __restrict__ values, typename P::args pa, int d,
                                                           float* __restrict__ Y, int64_t ldy) {
   __shared__ gs_lds lds;
-  fused_grouped_item<P, LPG, HAS_VAL>(A, indptr, indices, values, pa, d, Y, ldy, lds);
+  fused_grouped_item<P, LPG, ADDR32>(A, indptr, indices, values, pa, d, Y, ldy, lds);
 }
 
 template <class P, int LPG>
@@ -233,7 +234,9 @@ isp_status run_grouped(const isp_csr* A, const typename P::args& pa, int d, floa
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    if (v.values) k_fused_grouped<P, LPG, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
+    bool a32 = true;
+    for (int k = 0; k < P::NSRC; ++k) a32 = a32 && fused_offsets_fit_32(v.n_cols, pa.lds_[k], d);
+    if (a32) k_fused_grouped<P, LPG, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
     else k_fused_grouped<P, LPG, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
     ISP_LAUNCH_CHECK();
   }

@@ -12,10 +12,15 @@
 namespace isp_dev {
 
 // Policy P:  NSRC gathered operands (rows picked by column index), NROW row operands (rows picked
-// by the step's matrix row); STEPS steps issued back to back per buffer (two buffers in flight); args { src[NSRC], lds_[NSRC], rowop[NROW], ldr[NROW], out_entry };
+// by the step's matrix row); STEPS steps issued back to back per buffer (two buffers in flight);
+// args { src[NSRC], lds_[NSRC], rowop[NROW], ldr[NROW], out_entry };
 // either edge<LPG>(args, a, src, rowop, acc, lane_on, live) accumulating into the row's result in live
 // lanes, or (PER_ENTRY) entry<LPG>(a, src, rowop, lane_on) returning the value stored for the entry.
-template <class P, int LPG, bool HAS_VAL>
+// ADDR32: every byte offset into the gathered operands fits 32 bits and both factors of column * row pitch
+// fit 24 bits (fused_offsets_fit_32 below), so a gather address is one full-rate 24-bit multiply-add on a
+// scalar base pointer instead of a 64-bit multiply (three quarter-rate instructions).
+// values may be null (every stored value is 1).
+template <class P, int LPG, bool ADDR32>
 __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                           const int32_t* __restrict__ indices, const float* __restrict__ values,
                                           const typename P::args& pa, int d, float* __restrict__ Y, int64_t ldy,
@@ -36,12 +41,17 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   // says where each row end belongs): directed graphs leave many rows empty (half of them in the FusedMM
   // benchmark graph).  The per-entry policy has no row results and keeps the plain table.
   constexpr bool sparse_rows = !P::PER_ENTRY;
-  const int n_steps = gs_prepare<G, HAS_VAL, sparse_rows, U>(it, indptr, indices, values, L, lane);
+  const int n_steps = values ? gs_prepare<G, true, sparse_rows, U>(it, indptr, indices, values, L, lane)
+                             : gs_prepare<G, false, sparse_rows, U>(it, indptr, indices, values, L, lane);
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_lo + q * 4;
   const bool lane_on = col < d;
   const int coff = lane_on ? col : 0;
+  const unsigned lane_byte = (unsigned)coff * 4u;
+  unsigned src_pitch[NSRC];  // row pitches of the gathered operands in bytes (ADDR32)
+#pragma unroll
+  for (int k = 0; k < NSRC; ++k) src_pitch[k] = (unsigned)pa.lds_[k] * 4u;
   float* __restrict__ out = it.is_seg ? A.partials + col : Y + col;
   const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
   // An empty row owns no step.  The k-th row end of the step table belongs to the k-th non-empty row of the
@@ -58,7 +68,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   }
 
   auto finish_row = [&]() {
-    const int row = it.row + r_next;
+    const int row = it.row + __builtin_amdgcn_readfirstlane(r_next);  // (wave-uniform: scalar address math)
     ++k_done;
     r_next = listed ? (int)L.ss[k_done] : k_done;
 #pragma unroll
@@ -91,21 +101,29 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
       int srow[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        dsc[u] = L.step[s0 + u];
+        dsc[u] = __builtin_amdgcn_readfirstlane((unsigned)L.step[s0 + u]);  // the same in every lane
         e[u] = L.ent[gs_off(dsc[u]) + g];
         // (null steps past the end read the spare 0 after the list, or name the row after the item's last)
-        if constexpr (!SEG) srow[u] = it.src_row + (sparse_rows ? (int)L.ss[k_issued] : k_issued);
+        if constexpr (!SEG)
+          srow[u] = it.src_row + (sparse_rows ? __builtin_amdgcn_readfirstlane((int)L.ss[k_issued]) : k_issued);
         k_issued += (int)((dsc[u] >> 15) & 1u);  // a row end moves the following steps to the next non-empty row
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const bool act = g < gs_cnt(dsc[u]) && lane_on;
         a[u] = __int_as_float(e[u].y);
-        const int64_t cj = act ? e[u].x : 0;  // dead lanes gather row 0; what they fetch is never used
+        const int cj = act ? e[u].x : 0;  // dead lanes gather row 0; what they fetch is never used
 #pragma unroll
-        for (int k = 0; k < NSRC; ++k) load_vec<4>(pa.src[k] + cj * pa.lds_[k] + coff, x[u][k]);
+        for (int k = 0; k < NSRC; ++k) {
+          if constexpr (ADDR32) {
+            const unsigned off = __umul24((unsigned)cj, src_pitch[k]) + lane_byte;
+            load_vec<4>(reinterpret_cast<const float*>(reinterpret_cast<const char*>(pa.src[k]) + off), x[u][k]);
+          } else {
+            load_vec<4>(pa.src[k] + (int64_t)cj * pa.lds_[k] + coff, x[u][k]);
+          }
+        }
         if constexpr (!SEG) {
-          const int64_t ri = srow[u] < A.n_rows ? srow[u] : 0;  // null steps after the matrix's last row
+          const int64_t ri = srow[u] < (int)A.n_rows ? srow[u] : 0;  // null steps after the matrix's last row
 #pragma unroll
           for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + ri * pa.ldr[k] + coff, r[u][k]);
         }
@@ -130,7 +148,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
           if (live && q == 0) L.ent[gs_off(dsc[u]) + g].y = __float_as_int(val);
         } else {
           P::template edge<LPG>(pa, a[u], x[u], rr, acc, lane_on, live && lane_on);
-          if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
+          if (dsc[u] & GS_LAST) finish_row();
         }
       }
     };
@@ -166,6 +184,13 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
       *o = P::ADD ? *o + val : val;
     }
   }
+}
+
+// Host side: true when a kernel over matrix columns [0, n_cols) may gather from rows of pitch ld floats
+// (d columns used) with 32-bit byte offsets formed by a 24-bit multiply.
+inline bool fused_offsets_fit_32(int64_t n_cols, int64_t ld, int d) {
+  return n_cols < (1 << 24) && ld * 4 < (1 << 24) &&
+         ((uint64_t)n_cols * (uint64_t)ld + (uint64_t)d) * 4u < ((uint64_t)1 << 32);
 }
 
 // Partial dot product of a lane's four columns; lanes whose columns lie past d contribute zero.

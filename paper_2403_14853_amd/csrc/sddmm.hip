@@ -90,27 +90,28 @@ __global__ void __launch_bounds__(ISP_WG) k_sddmm(isp_view A, const int64_t* __r
   }
 }
 
-// ---- grouped fast path (d <= 256, 16-byte aligned operands) -------------------------------------
+// ---- grouped fast path (d % 4 == 0, 16-byte aligned operands) ------------------------------------
 // ADD: this pass covers a window of the feature columns and adds its partial dot product to out.
-template <bool SCALE, bool ADD_ = false>
+// The entry's staged value multiplies the dot product; it is 1 when the kernel is given no values
+// (unscaled SDDMM, or a matrix without stored values).
+template <bool ADD_ = false>
 struct sddmm_policy {
   static constexpr int NSRC = 1, NROW = 1, STEPS = 4;
   static constexpr bool PER_ENTRY = true, ACCUMULATE = false, ADD = ADD_;
   struct args { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
   template <int LPG>
   __device__ static inline float entry(float a, const float (&x)[1][4], const float (&r)[1][4], bool lane_on) {
-    const float dot = group_allreduce<LPG>(dot4(r[0], x[0], lane_on));
-    return SCALE ? a * dot : dot;
+    return a * group_allreduce<LPG>(dot4(r[0], x[0], lane_on));
   }
 };
 
-template <int LPG, bool SCALE, bool ADD>
+template <int LPG, bool ADDR32, bool ADD>
 __global__ void __launch_bounds__(ISP_WG) k_sddmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                           const int32_t* __restrict__ indices,
                                                           const float* __restrict__ values,
-                                                          typename sddmm_policy<SCALE, ADD>::args pa, int d, int k_lo) {
+                                                          typename sddmm_policy<ADD>::args pa, int d, int k_lo) {
   __shared__ gs_lds lds;
-  fused_grouped_item<sddmm_policy<SCALE, ADD>, LPG, SCALE>(A, indptr, indices, values, pa, d, nullptr, 0, lds, k_lo);
+  fused_grouped_item<sddmm_policy<ADD>, LPG, ADDR32>(A, indptr, indices, values, pa, d, nullptr, 0, lds, k_lo);
 }
 
 // One pass over the feature columns [k_lo, d_hi) (d_hi - k_lo <= 4 * LPG); add: accumulate into out.
@@ -121,13 +122,15 @@ isp_status launch_grouped(const isp_csr* A, const float* U, int64_t ldu, const f
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items == 0 || v.nnz == 0) return ISP_OK;
   const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-  const bool sc = scale && v.values;
-#define ISP_GO(SC, AD)                                                                                  \
-  do {                                                                                                  \
-    typename sddmm_policy<SC, AD>::args pa{{V}, {ldv}, {U}, {ldu}, out};                                \
-    k_sddmm_grouped<LPG, SC, AD><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d_hi, k_lo); \
+  const float* vals = scale ? v.values : nullptr;
+  const bool a32 = fused_offsets_fit_32(v.n_cols, ldv, d_hi);
+  typename sddmm_policy<false>::args pa{{V}, {ldv}, {U}, {ldu}, out};  // (the same members for either ADD)
+#define ISP_GO(A32, AD)                                                                                  \
+  do {                                                                                                   \
+    typename sddmm_policy<AD>::args pb{{pa.src[0]}, {pa.lds_[0]}, {pa.rowop[0]}, {pa.ldr[0]}, pa.out_entry}; \
+    k_sddmm_grouped<LPG, A32, AD><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, vals, pb, d_hi, k_lo); \
   } while (0)
-  if (sc) { if (add) ISP_GO(true, true); else ISP_GO(true, false); }
+  if (a32) { if (add) ISP_GO(true, true); else ISP_GO(true, false); }
   else { if (add) ISP_GO(false, true); else ISP_GO(false, false); }
 #undef ISP_GO
   ISP_LAUNCH_CHECK();

@@ -126,7 +126,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   int r_next = listed ? (int)L.ss[0] : 0;
 
   auto finish_row = [&]() {
-    const int r_local = r_next;
+    const int r_local = __builtin_amdgcn_readfirstlane(r_next);  // (wave-uniform: scalar address math)
     const int row = it.row + r_local;
     ++k_done;
     r_next = listed ? (int)L.ss[k_done] : k_done;
@@ -145,7 +145,10 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   // descriptors of U consecutive steps = one 16-byte LDS read
   auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][VEC], float (&a)[U]) {
     const uint4 pk = *reinterpret_cast<const uint4*>(L.step + s0);
-    const unsigned raw[4] = {pk.x, pk.y, pk.z, pk.w};
+    // the table is the same in every lane: held in scalar registers, a step's offset, count and row-end flag
+    // cost no vector instructions
+    const unsigned raw[4] = {(unsigned)__builtin_amdgcn_readfirstlane(pk.x), (unsigned)__builtin_amdgcn_readfirstlane(pk.y),
+                             (unsigned)__builtin_amdgcn_readfirstlane(pk.z), (unsigned)__builtin_amdgcn_readfirstlane(pk.w)};
     int2 e[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -172,7 +175,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[v] = fmaf(a[u], x[u][v], acc[v]);
       }
-      if (__builtin_amdgcn_readfirstlane(dsc[u]) & GS_LAST) finish_row();
+      if (dsc[u] & GS_LAST) finish_row();
     }
   };
 
