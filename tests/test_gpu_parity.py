@@ -192,6 +192,41 @@ def test_leading_dimension_larger_than_d(small_partition):
     A.destroy()
 
 
+def test_row_pitch_beyond_24_bits_takes_the_64_bit_gather_addresses(small_partition):
+    """The grouped kernels form gather addresses with a 24-bit multiply when every byte offset fits 32 bits;
+    rows 16 MiB apart (and operands of more than 4 GiB in all) must take the 64-bit variants instead."""
+    n, d, ld = 288, 64, (1 << 22) + 32
+    indptr, indices, values = graphgen.random_csr(n, n, 6000, seed=21)
+    rng = np.random.default_rng(5)
+    X = (0.3 * rng.standard_normal((n, d))).astype(np.float32)
+    G = rng.standard_normal((n, d)).astype(np.float32)
+    big = torch.empty((2, n, ld), device="cuda")  # 2 x 4.8 GB, only the first d columns are ever touched
+    Xd, Gd = big[0, :, :d], big[1, :, :d]
+    Xd.copy_(dev(X)); Gd.copy_(dev(G))
+    assert Xd.stride(0) * 4 >= 1 << 24
+    A = build(indptr, indices, values)
+    Y = torch.full((n, d), float("nan"), device="cuda")
+    isp.spmm(A, Xd, Y)
+    ref, mag = oracle.spmm(indptr, indices, values, X)
+    assert_close(Y, ref, mag, "spmm")
+    out = torch.full((len(indices),), float("nan"), device="cuda")
+    isp.sddmm(A, Gd, Xd, out, scale_by_a=True)
+    ref, mag = oracle.sddmm(indptr, indices, values, G, X, scale_by_a=True)
+    assert_close(out, ref, mag, "sddmm")
+    isp.csr_transpose_cached(A)
+    for op in ("sigmoid", "dot"):
+        isp.fusedmm(A, Xd, Y, op=op)
+        ref, mag = oracle.fusedmm(indptr, indices, values, X, op=op)
+        assert_close(Y, ref, mag, "fusedmm " + op)
+        dX = torch.full((n, d), float("nan"), device="cuda")
+        isp.fusedmm_backward(A, Xd, Gd, dX, op=op)
+        ref, mag = oracle.fusedmm_backward(indptr, indices, values, X, G, op=op)
+        assert_close(dX, ref, mag, "fusedmm backward " + op)
+    A.destroy()
+    del big
+    torch.cuda.empty_cache()
+
+
 def test_malformed_csr_is_rejected():
     w = graphgen.make_config(0)
     bad_ptr = w.indptr.copy()
