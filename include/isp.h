@@ -179,7 +179,8 @@ isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const
  *         and comparison in fp32; arg[i,k] = position p (index into indices / values) of the first entry that
  *         attains it; empty row -> Y = 0, arg = -1.  arg is int32, n_rows x d, row-major, dense (leading
  *         dimension d), required for min / max, ignored otherwise.
- * As in the paper, only the sum reduction has the tuned kernels; the others run on the generic path.
+ * sum has the tuned kernels; mean reuses them when width and alignment allow (d and the leading dimensions
+ * multiples of 4, 16-byte aligned pointers); min / max run on the generic path.
  */
 isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
                            int64_t ldy, int32_t* arg, void* stream);
@@ -187,7 +188,10 @@ isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int3
 /*
  * Backward of isp_spmm_reduce with respect to X, through the cached transpose (Section 3.3), which must
  * have been built (isp_csr_transpose_cached) - otherwise ISP_EINVAL.  dX is n_cols x d and is overwritten.
- *   sum : dX = A^T dY.   mean: dX[j] = sum_{p in column j} (values[p] / len(row(p))) dY[row(p)].
+ *   sum : dX = A^T dY.   mean: dX[j] = sum_{p in column j} (values[p] / len(row(p))) dY[row(p)]; the first
+ *         mean call on a handle (and the first after isp_csr_values_changed) computes values[p] / len(row(p))
+ *         for every entry, on `stream`, into a part of the transpose workspace that the transposition itself
+ *         no longer needs; later calls read it.
  *   min / max: dX[j,k] = sum over entries p in column j with arg[row(p),k] == p of values[p] dY[row(p),k];
  *         arg is the array the forward call filled.
  */

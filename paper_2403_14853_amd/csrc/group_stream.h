@@ -68,13 +68,10 @@ __device__ inline int wave_exclusive_scan_i(int v, int lane, int* total) {
 // SPARSE_ROWS: empty rows own no step, and ss ends up holding the local indices of the non-empty rows, in
 // order (the kernel zeroes the empty rows' outputs itself); otherwise an empty row owns one step without
 // entries.  rp holds the rows' start offsets.
-// entry_scale (optional): reciprocal row lengths of another matrix; entry p is staged with its value
-// multiplied by entry_scale[indices[p]] (the backward of the mean reduction runs over the transpose and
-// needs the source rows' lengths).
 template <int G, bool HAS_VAL, bool SPARSE_ROWS = false, int PAD = GS_U>
 __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict__ indptr,
                                  const int32_t* __restrict__ indices, const float* __restrict__ values,
-                                 gs_wave_lds& L, int lane, const float* __restrict__ entry_scale = nullptr) {
+                                 gs_wave_lds& L, int lane) {
   constexpr bool sparse_rows = SPARSE_ROWS;
   static_assert(PAD >= 1 && PAD <= GS_U, "the step table has room for GS_U null steps");
   int2* __restrict__ ent = L.ent;
@@ -85,8 +82,7 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   for (int i = lane; i < n_ent; i += ISP_WAVE) {
     int2 e;
     e.x = __builtin_nontemporal_load(indices + it.p + i);
-    float val = HAS_VAL ? __builtin_nontemporal_load(values + it.p + i) : 1.f;
-    if (entry_scale) val *= entry_scale[e.x];
+    const float val = HAS_VAL ? __builtin_nontemporal_load(values + it.p + i) : 1.f;
     e.y = __float_as_int(val);
     ent[i] = e;
   }

@@ -37,6 +37,9 @@ struct isp_csr {
   isp_view v;
   const int32_t* perm;     // transposes only
   float* t_values_rw;      // transposes only: the values array (in the workspace), writable
+  float* mean_values;      // transposes only: nnz floats of workspace the transposition no longer needs, for
+                           // value / (length of the entry's source row), filled on first use
+  bool mean_values_valid;  // false until filled and after isp_csr_values_changed
   isp_csr_info_t info;
   int device;
   isp_csr* At;             // cached transpose (owned), or NULL
@@ -73,15 +76,19 @@ size_t isp_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz
 isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_t s);
 // Gather the cached transpose's values again from A's (rewritten) values.
 isp_status isp_transpose_refresh_values(isp_csr* A, hipStream_t s);
+// Values of A's cached transpose divided by the lengths of their source rows of A (what the backward of the
+// mean reduction multiplies dY's rows by): computed on s at the first call and after the values changed,
+// kept in the transpose workspace afterwards.
+isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** out);
 
 // ---- compute (spmm.hip, sddmm.hip, fusedmm.hip) ------------------------------------------------
 isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
                            hipStream_t s);
 // Grouped fast path of SpMM; *done = false (nothing launched) when the operands do not qualify.
-// mean_mode 0: plain sum; 1: rows divided by their length; 2: entries divided by the length of row
-// indices[p] of the source matrix, given as that matrix's reciprocal row lengths src_inv_len.
+// mean_mode 0: plain sum; 1: rows divided by their length.  values_override (optional): nnz values used in
+// place of A's own.
 isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                                   int mean_mode, const float* src_inv_len, hipStream_t s, bool* done);
+                                   int mean_mode, const float* values_override, hipStream_t s, bool* done);
 isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv,
                             int32_t d, bool scale, float* out, hipStream_t s);
 isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,
@@ -90,5 +97,5 @@ isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx,
                                   int32_t d, int op, float* dX, int64_t lddx, hipStream_t s);
 isp_status isp_spmm_reduce_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
                                   int64_t ldy, int32_t* arg, hipStream_t s);
-isp_status isp_spmm_reduce_bwd_launch(const isp_csr* A, const float* dY, int64_t lddy, int32_t d, int reduce,
+isp_status isp_spmm_reduce_bwd_launch(isp_csr* A, const float* dY, int64_t lddy, int32_t d, int reduce,
                                       const int32_t* arg, float* dX, int64_t lddx, hipStream_t s);

@@ -82,10 +82,8 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
                                                          const int32_t* __restrict__ indices,
                                                          const float* __restrict__ values,
                                                          const float* __restrict__ X, int64_t ldx, int d, int k_base,
-                                                         int n_slices, float* __restrict__ Y, int64_t ldy, int mean_mode,
-                                                         const float* __restrict__ src_inv_len) {
-  // mean_mode 1: divide every finished row by its length (mean reduction, forward);
-  // mean_mode 2: stage every entry times the reciprocal length of source row indices[p] (its backward)
+                                                         int n_slices, float* __restrict__ Y, int64_t ldy, int mean_mode) {
+  // mean_mode 1: divide every finished row by its length (mean reduction, forward)
   constexpr int G = ISP_WAVE / LPG;
   constexpr int U = GS_U;
   __shared__ gs_lds lds;
@@ -97,8 +95,7 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const item_range it = locate_item(A, indptr, item);
   if (it.skip) return;
   gs_wave_lds& L = lds.w[w];
-  const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane,
-                                                          mean_mode == 2 ? src_inv_len : nullptr);  // multiple of U
+  const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane);  // multiple of U
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_base + (slice * LPG + q) * VEC;
@@ -203,8 +200,9 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 
 template <int LPG, int VEC = 4>
 isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, int k_base, int n_slices, float* Y,
-                          int64_t ldy, int mean_mode, const float* src_inv_len, hipStream_t s) {
+                          int64_t ldy, int mean_mode, const float* values_override, hipStream_t s) {
   const isp_view& v = A->v;
+  const float* vals = values_override ? values_override : v.values;  // (one value per stored entry, A's order)
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * (unsigned)n_slices;
@@ -215,16 +213,16 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
 #define ISP_GO(HV, A32)                                                                                           \
   do {                                                                                                            \
     if (sparse_rows)                                                                                              \
-      k_spmm_grouped<LPG, HV, A32, VEC, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, \
-                                                                    k_base, n_slices, Y, ldy, mean_mode, src_inv_len); \
+      k_spmm_grouped<LPG, HV, A32, VEC, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, vals, X, ldx, d,     \
+                                                                    k_base, n_slices, Y, ldy, mean_mode);          \
     else                                                                                                          \
-      k_spmm_grouped<LPG, HV, A32, VEC, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, \
-                                                                     k_base, n_slices, Y, ldy, mean_mode, src_inv_len); \
+      k_spmm_grouped<LPG, HV, A32, VEC, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, vals, X, ldx, d,    \
+                                                                     k_base, n_slices, Y, ldy, mean_mode);         \
   } while (0)
     if constexpr (VEC < 4) {  // narrow lanes are only dispatched with 32-bit addressing
-      if (v.values) ISP_GO(true, true); else ISP_GO(false, true);
+      if (vals) ISP_GO(true, true); else ISP_GO(false, true);
     } else {
-      if (v.values) { if (a32) ISP_GO(true, true); else ISP_GO(true, false); }
+      if (vals) { if (a32) ISP_GO(true, true); else ISP_GO(true, false); }
       else { if (a32) ISP_GO(false, true); else ISP_GO(false, false); }
     }
 #undef ISP_GO
@@ -245,9 +243,10 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 }  // namespace
 
 // The grouped fast path; *done = false (and nothing launched) when the operands do not qualify.
-// mean_mode / src_inv_len: see k_spmm_grouped.
+// mean_mode: see k_spmm_grouped.  values_override (optional): nnz values, in A's entry order, used in place of
+// A's own (the backward of the mean reduction passes the transpose's values divided by the source rows' lengths).
 isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                                   int mean_mode, const float* src_inv_len, hipStream_t s, bool* done) {
+                                   int mean_mode, const float* values_override, hipStream_t s, bool* done) {
   const isp_view& av = A->v;
   // Lane width: float4 when width, pitch and pointers allow; float2 / float lanes otherwise (any d),
   // those two only with 32-bit addressing and for the plain sum.
@@ -270,13 +269,13 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
       const int lpg = w <= 16 * vec ? 16 : (w <= 32 * vec ? 32 : 64);
       const int ns = (w + lpg * vec - 1) / (lpg * vec);
       if (vec == 2) {
-        if (lpg == 16) st = launch_grouped<16, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
-        else if (lpg == 32) st = launch_grouped<32, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
-        else st = launch_grouped<64, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
+        if (lpg == 16) st = launch_grouped<16, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
+        else if (lpg == 32) st = launch_grouped<32, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
+        else st = launch_grouped<64, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
       } else {
-        if (lpg == 16) st = launch_grouped<16, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
-        else if (lpg == 32) st = launch_grouped<32, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
-        else st = launch_grouped<64, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, nullptr, s);
+        if (lpg == 16) st = launch_grouped<16, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
+        else if (lpg == 32) st = launch_grouped<32, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
+        else st = launch_grouped<64, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
       }
     }
     return st;
@@ -306,11 +305,11 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
     const int w = (d - k_base < tile) ? d - k_base : tile;
     const int ns = (w + 4 * lpg - 1) / (4 * lpg);
     switch (lpg) {
-      case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
-      case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
-      case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
-      case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
-      default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, src_inv_len, s); break;
+      case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
+      case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
+      case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
+      case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
+      default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
     }
   }
   return st;

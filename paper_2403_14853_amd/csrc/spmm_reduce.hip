@@ -265,12 +265,16 @@ isp_status isp_spmm_reduce_launch(const isp_csr* A, const float* X, int64_t ldx,
   return fwd_all<R_MAX>(A, X, ldx, d, Y, ldy, arg, s);
 }
 
-isp_status isp_spmm_reduce_bwd_launch(const isp_csr* A, const float* dY, int64_t lddy, int32_t d, int reduce,
+isp_status isp_spmm_reduce_bwd_launch(isp_csr* A, const float* dY, int64_t lddy, int32_t d, int reduce,
                                       const int32_t* arg, float* dX, int64_t lddx, hipStream_t s) {
   const isp_csr* At = A->At;
-  if (reduce == R_MEAN) {  // the tuned kernel on A^T with every entry divided by its source row's length
+  if (reduce == R_MEAN && At->v.nnz > 0) {
+    // the tuned kernels on A^T with every value divided by its source row's length (computed once per handle)
+    const float* mv = nullptr;
+    isp_status st = isp_transpose_mean_values(A, s, &mv);
+    if (st != ISP_OK) return st;
     bool done = false;
-    const isp_status st = isp_spmm_grouped_launch(At, dY, lddy, d, dX, lddx, 2, A->v.inv_len, s, &done);
+    st = isp_spmm_grouped_launch(At, dY, lddy, d, dX, lddx, 0, mv, s, &done);
     if (done || st != ISP_OK) return st;
   }
   const bool hv = At->v.values != nullptr;

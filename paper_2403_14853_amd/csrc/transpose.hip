@@ -222,6 +222,16 @@ __global__ void __launch_bounds__(256) k_gather_values(const int32_t* __restrict
   if (q < nnz) t_values[q] = values[perm[q]];
 }
 
+// mean_values[q] = t_values[q] / len_A(t_indices[q])  (t_values absent: 1 / len), as one fp32 product with
+// the reciprocal lengths the build keeps
+__global__ void __launch_bounds__(256) k_mean_values(const int32_t* __restrict__ t_indices,
+                                                     const float* __restrict__ t_values,
+                                                     const float* __restrict__ inv_len, int64_t nnz,
+                                                     float* __restrict__ mean_values) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q < nnz) mean_values[q] = (t_values ? t_values[q] : 1.f) * inv_len[t_indices[q]];
+}
+
 __global__ void __launch_bounds__(256) k_fill_i64(int64_t* __restrict__ a, int64_t n, int64_t v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) a[i] = v;
@@ -324,6 +334,9 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   if (st != ISP_OK) return st;
   At->perm = perm;
   At->t_values_rw = t_values;
+  // the record arrays of the sort are free from here on; one of them later holds the mean reduction's values
+  At->mean_values = (float*)(base + L.set[0][1]);
+  At->mean_values_valid = false;
   At->is_transpose = true;
   At->info.is_transpose = 1;
   A->At = At;
@@ -331,8 +344,22 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   return ISP_OK;
 }
 
+isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** out) {
+  isp_csr* At = A->At;
+  if (!At || !At->mean_values) return isp_fail(ISP_EINVAL, "no cached transpose");
+  if (!At->mean_values_valid && A->v.nnz > 0) {
+    k_mean_values<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(At->v.indices, At->v.values, A->v.inv_len, A->v.nnz,
+                                                                     At->mean_values);
+    ISP_LAUNCH_CHECK();
+    At->mean_values_valid = true;
+  }
+  *out = At->mean_values;
+  return ISP_OK;
+}
+
 isp_status isp_transpose_refresh_values(isp_csr* A, hipStream_t s) {
   isp_csr* At = A->At;
+  if (At) At->mean_values_valid = false;
   if (!At || !A->v.values || !At->t_values_rw || A->v.nnz == 0) return ISP_OK;
   k_gather_values<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(At->perm, A->v.values, A->v.nnz, At->t_values_rw);
   ISP_LAUNCH_CHECK();

@@ -454,6 +454,10 @@ def test_values_changed_refreshes_the_cached_transpose(small_partition):
     At, _ = isp.csr_transpose_cached(A)
     G = np.random.default_rng(5).standard_normal((w.n, 24)).astype(np.float32)
     Gd, dX = dev(G), torch.empty(w.n, 24, device="cuda")
+    # (the mean reduction's backward keeps value / row length per entry of the transpose: filled here with the
+    # old values, it has to be filled again after the change)
+    isp.spmm_reduce_backward(A, Gd, dX, "mean")
+    assert_close(dX, *oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, w.values, G, "mean"), "mean backward")
     new_vals = (w.values * 0.5 + 0.25).astype(np.float32)
     va.copy_(dev(new_vals))            # same tensor, new contents (e.g. a gradient step on the edge values)
     isp.csr_values_changed(A)
@@ -467,6 +471,10 @@ def test_values_changed_refreshes_the_cached_transpose(small_partition):
     Y = torch.empty(w.n, 24, device="cuda")
     isp.spmm(A, Gd, Y)
     assert_close(Y, *oracle.spmm(w.indptr, w.indices, new_vals, G), "spmm forward after the values changed")
+    for _ in range(2):  # (the second call reuses what the first one filled)
+        isp.spmm_reduce_backward(A, Gd, dX, "mean")
+        assert_close(dX, *oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, new_vals, G, "mean"),
+                     "mean backward after the values changed")
     with pytest.raises(isp.IspError):
         isp.csr_values_changed(At)     # the transpose is not a source handle
     # no values / no cached transpose: accepted, nothing to do
@@ -474,6 +482,9 @@ def test_values_changed_refreshes_the_cached_transpose(small_partition):
     isp.csr_values_changed(B)
     isp.csr_transpose_cached(B)
     isp.csr_values_changed(B)
+    isp.spmm_reduce_backward(B, Gd, dX, "mean")
+    assert_close(dX, *oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, None, G, "mean"),
+                 "mean backward without stored values")
     A.destroy()
     B.destroy()
 
