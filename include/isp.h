@@ -193,7 +193,9 @@ isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int3
  *         for every entry, on `stream`, into a part of the transpose workspace that the transposition itself
  *         no longer needs; later calls read it.
  *   min / max: dX[j,k] = sum over entries p in column j with arg[row(p),k] == p of values[p] dY[row(p),k];
- *         arg is the array the forward call filled.
+ *         arg is the array the forward call filled; positions outside [0, nnz) name no entry.  Each call
+ *         first marks the entries arg names (one byte per entry, in spare transpose workspace) and passes
+ *         over the others.
  */
 isp_status isp_spmm_reduce_backward(isp_csr_t* A, const float* dY, int64_t lddy, int32_t d, int reduce,
                                     const int32_t* arg, float* dX, int64_t lddx, void* stream);

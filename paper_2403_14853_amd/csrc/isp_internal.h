@@ -40,6 +40,10 @@ struct isp_csr {
   float* mean_values;      // transposes only: nnz floats of workspace the transposition no longer needs, for
                            // value / (length of the entry's source row), filled on first use
   bool mean_values_valid;  // false until filled and after isp_csr_values_changed
+  uint8_t* sel_flags;      // transposes only: nnz bytes of the same spare workspace; the min / max backward
+                           // marks there which entries its arg array names
+  int32_t* inv_perm;       // transposes only, same spare workspace: inv_perm[perm[q]] = q, filled on first use
+  bool inv_perm_valid;
   isp_csr_info_t info;
   int device;
   isp_csr* At;             // cached transpose (owned), or NULL
@@ -80,6 +84,9 @@ isp_status isp_transpose_refresh_values(isp_csr* A, hipStream_t s);
 // mean reduction multiplies dY's rows by): computed on s at the first call and after the values changed,
 // kept in the transpose workspace afterwards.
 isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** out);
+// Position q in A's cached transpose of every stored entry p of A (the inverse of perm): computed on s at the
+// first call, kept in the transpose workspace afterwards.
+isp_status isp_transpose_inverse_perm(isp_csr* A, hipStream_t s, const int32_t** out);
 
 // ---- compute (spmm.hip, sddmm.hip, fusedmm.hip) ------------------------------------------------
 isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,

@@ -10,6 +10,7 @@
 // nonzero has been added; a hub segment's result goes to the handle's partial-sum scratch and is
 // combined by a second, fixed-order kernel (no floating-point atomics anywhere).
 #pragma once
+#include <type_traits>
 #include "isp_internal.h"
 
 namespace isp_dev {
@@ -89,6 +90,14 @@ __device__ inline item_range locate_item(const isp_view& A, const int64_t* __res
   }
   return r;
 }
+
+// A policy may declare  static constexpr bool HAS_SKIP = true  and carry args::live (one byte per stored
+// entry of the matrix being streamed): entries whose byte live[p] is 0 are passed over - nothing is gathered
+// for them and edge() is not called.
+template <class P, class = void>
+struct policy_has_skip : std::false_type {};
+template <class P>
+struct policy_has_skip<P, std::void_t<decltype(P::HAS_SKIP)>> : std::bool_constant<P::HAS_SKIP> {};
 
 // Policy P supplies:
 //   static constexpr int VEC, T, NG, U;  static constexpr bool HAS_VAL, ACCUMULATE;
@@ -179,17 +188,67 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
     const int cnt = left < ISP_WAVE ? (int)left : ISP_WAVE;
     int c = 0, pm = 0;
     float a = 1.f;
+    bool dead = false;
     if (lane < cnt) {
       c = __builtin_nontemporal_load(indices + p + lane);
       if (P::HAS_VAL) a = __builtin_nontemporal_load(values + p + lane);
       if constexpr (P::NEEDS_PERM) pm = __builtin_nontemporal_load(pa.perm + p + lane);
+      if constexpr (policy_has_skip<P>::value) dead = __builtin_nontemporal_load(pa.live + p + lane) == 0;
+    }
+    const unsigned long long dead_mask = policy_has_skip<P>::value ? __ballot(dead) : 0ull;  // bit t: entry p + t
+    if constexpr (policy_has_skip<P>::value) {
+      if (it.is_seg) {
+        // a hub segment is one row with no row end inside, and nearly all of its entries are passed over:
+        // visit the live ones only, U at a time
+        unsigned long long todo = ~dead_mask & (cnt == ISP_WAVE ? ~0ull : ((1ull << cnt) - 1ull));
+        while (todo) {
+          int idx[U];
+          float x[U][NG][T][VEC];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            idx[u] = todo ? (int)__builtin_ctzll(todo) : -1;
+            todo &= todo - 1ull;  // (0 stays 0)
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            if (idx[u] >= 0) {
+              const int cj = bcast_i(c, idx[u]);
+#pragma unroll
+              for (int g = 0; g < NG; ++g) {
+                const float* __restrict__ src = pa.src[g] + (int64_t)cj * pa.ld[g];
+#pragma unroll
+                for (int tt = 0; tt < T; ++tt) {
+                  if (on[tt]) load_vec<VEC>(src + col[tt], x[u][g][tt]);
+                  else {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) x[u][g][tt][v] = 0.f;
+                  }
+                }
+              }
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            if (idx[u] >= 0) {
+              edge_info ei;
+              ei.col = bcast_i(c, idx[u]);
+              ei.perm = P::NEEDS_PERM ? bcast_i(pm, idx[u]) : 0;
+              ei.pos = p + idx[u];
+              P::edge(pa, rs, P::HAS_VAL ? bcast_f(a, idx[u]) : 1.f, x[u], acc, on, ei);
+            }
+          }
+        }
+        p += cnt;
+        if (p == p_end) write_row();  // the segment's row ends with its last entry
+        continue;
+      }
     }
     for (int t = 0; t < cnt; t += U) {
       float x[U][NG][T][VEC];
       const bool full = t + U <= cnt;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        if (full || t + u < cnt) {
+        if ((full || t + u < cnt) && !((dead_mask >> (t + u)) & 1ull)) {
           const int cj = bcast_i(c, t + u);
 #pragma unroll
           for (int g = 0; g < NG; ++g) {
@@ -208,12 +267,14 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         if (full || t + u < cnt) {
-          const float av = P::HAS_VAL ? bcast_f(a, t + u) : 1.f;
-          edge_info ei;
-          ei.col = bcast_i(c, t + u);
-          ei.perm = P::NEEDS_PERM ? bcast_i(pm, t + u) : 0;
-          ei.pos = p + t + u;
-          P::edge(pa, rs, av, x[u], acc, on, ei);
+          if (!((dead_mask >> (t + u)) & 1ull)) {
+            const float av = P::HAS_VAL ? bcast_f(a, t + u) : 1.f;
+            edge_info ei;
+            ei.col = bcast_i(c, t + u);
+            ei.perm = P::NEEDS_PERM ? bcast_i(pm, t + u) : 0;
+            ei.pos = p + t + u;
+            P::edge(pa, rs, av, x[u], acc, on, ei);
+          }
           if (p + t + u + 1 == row_end) {
             write_row();
             next_row();

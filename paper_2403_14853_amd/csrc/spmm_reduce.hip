@@ -157,12 +157,14 @@ struct mean_bwd_policy {
 };
 
 // min / max: gathers dY[i] and arg[i] (as bit patterns); the entry contributes where arg equals its
-// position p = perm[q] in the source matrix.
+// position p = perm[q] in the source matrix.  An entry that no column of its row selected (live[q] == 0,
+// marked from arg before the pass) is passed over without gathering anything: in a row of many entries at
+// most d of them are selected.
 template <int VEC_, bool HAS_VAL_>
 struct select_bwd_policy {
   static constexpr int VEC = VEC_, T = 1, NG = 2, U = 4;
-  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = true, HAS_FINISH = false;
-  struct args { const float* src[2]; int64_t ld[2]; const int32_t* perm; };
+  static constexpr bool HAS_VAL = HAS_VAL_, ACCUMULATE = false, NEEDS_PERM = true, HAS_FINISH = false, HAS_SKIP = true;
+  struct args { const float* src[2]; int64_t ld[2]; const int32_t* perm; const uint8_t* live; };
   struct row_state {};
   __device__ static inline void row_begin(const args&, row_state&, int, const int (&)[1], const bool (&)[1]) {}
   __device__ static inline void edge(const args&, row_state&, float a, const float (&x)[2][1][VEC],
@@ -181,6 +183,23 @@ __global__ void __launch_bounds__(ISP_WG) k_reduce_bwd(isp_view At, const int64_
                                                        const float* __restrict__ values, typename P::args pa, int d,
                                                        int k0, float* __restrict__ dX, int64_t lddx) {
   stream_item<P>(At, indptr, indices, values, pa, d, k0, dX, lddx);
+}
+
+// live[q] = 1 for every entry q of the transpose whose source position p = perm[q] arg names (positions
+// outside [0, nnz) - the -1 of empty rows, or anything a caller's array may hold - are ignored); live was
+// zeroed before.  A row's columns name positions inside that row, so the lookups in inv_perm stay local.
+__global__ void __launch_bounds__(256) k_mark_selected(const int32_t* __restrict__ arg, int64_t n, int64_t nnz,
+                                                       const int32_t* __restrict__ inv_perm,
+                                                       uint8_t* __restrict__ live) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  const int32_t p = arg[t];
+  if (p >= 0 && p < nnz) live[inv_perm[p]] = 1;
+}
+
+__global__ void __launch_bounds__(256) k_zero_u32(uint32_t* __restrict__ a, int64_t n) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n) a[t] = 0u;
 }
 
 template <int VEC>
@@ -247,7 +266,7 @@ template <int VEC, bool HV>
 isp_status select_bwd(const isp_csr* A, const float* dY, int64_t lddy, const int32_t* arg, int d, int k0, float* dX,
                       int64_t lddx, hipStream_t s) {
   using P = select_bwd_policy<VEC, HV>;
-  typename P::args pa{{dY, reinterpret_cast<const float*>(arg)}, {lddy, (int64_t)d}, A->At->perm};
+  typename P::args pa{{dY, reinterpret_cast<const float*>(arg)}, {lddy, (int64_t)d}, A->At->perm, A->At->sel_flags};
   return bwd_tile<P, VEC>(A->At, pa, d, k0, dX, lddx, s);
 }
 
@@ -281,6 +300,18 @@ isp_status isp_spmm_reduce_bwd_launch(isp_csr* A, const float* dY, int64_t lddy,
   const bool v2 = d % 2 == 0 && lddy % 2 == 0 && lddx % 2 == 0 && aligned(dY, 8) && aligned(dX, 8) &&
                   aligned(arg, 8) && d > ISP_WAVE;
   isp_status st = ISP_OK;
+  if (reduce != R_MEAN && At->v.nnz > 0) {  // which entries of A does arg name at all (any column)?
+    const int64_t nnz = At->v.nnz, words = (nnz + 3) / 4, n_arg = A->v.n_rows * (int64_t)d;
+    const int32_t* inv_perm = nullptr;
+    st = isp_transpose_inverse_perm(A, s, &inv_perm);
+    if (st != ISP_OK) return st;
+    k_zero_u32<<<(unsigned)((words + 255) / 256), 256, 0, s>>>(reinterpret_cast<uint32_t*>(At->sel_flags), words);
+    ISP_LAUNCH_CHECK();
+    if (n_arg > 0) {
+      k_mark_selected<<<(unsigned)((n_arg + 255) / 256), 256, 0, s>>>(arg, n_arg, nnz, inv_perm, At->sel_flags);
+      ISP_LAUNCH_CHECK();
+    }
+  }
   for (int k0 = 0; k0 < d && st == ISP_OK; k0 += (v2 ? 2 : 1) * ISP_WAVE) {
     if (reduce == R_MEAN) {
       if (v2 && hv) st = mean_bwd<2, true>(A, dY, lddy, d, k0, dX, lddx, s);

@@ -232,6 +232,12 @@ __global__ void __launch_bounds__(256) k_mean_values(const int32_t* __restrict__
   if (q < nnz) mean_values[q] = (t_values ? t_values[q] : 1.f) * inv_len[t_indices[q]];
 }
 
+__global__ void __launch_bounds__(256) k_inverse_perm(const int32_t* __restrict__ perm, int64_t nnz,
+                                                      int32_t* __restrict__ inv_perm) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q < nnz) inv_perm[perm[q]] = (int32_t)q;
+}
+
 __global__ void __launch_bounds__(256) k_fill_i64(int64_t* __restrict__ a, int64_t n, int64_t v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) a[i] = v;
@@ -337,6 +343,9 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   // the record arrays of the sort are free from here on; one of them later holds the mean reduction's values
   At->mean_values = (float*)(base + L.set[0][1]);
   At->mean_values_valid = false;
+  At->sel_flags = (uint8_t*)(base + L.set[1][1]);
+  At->inv_perm = (int32_t*)(base + L.set[0][2]);
+  At->inv_perm_valid = false;
   At->is_transpose = true;
   At->info.is_transpose = 1;
   A->At = At;
@@ -354,6 +363,18 @@ isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** ou
     At->mean_values_valid = true;
   }
   *out = At->mean_values;
+  return ISP_OK;
+}
+
+isp_status isp_transpose_inverse_perm(isp_csr* A, hipStream_t s, const int32_t** out) {
+  isp_csr* At = A->At;
+  if (!At || !At->inv_perm) return isp_fail(ISP_EINVAL, "no cached transpose");
+  if (!At->inv_perm_valid && A->v.nnz > 0) {
+    k_inverse_perm<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(At->perm, A->v.nnz, At->inv_perm);
+    ISP_LAUNCH_CHECK();
+    At->inv_perm_valid = true;
+  }
+  *out = At->inv_perm;
   return ISP_OK;
 }
 

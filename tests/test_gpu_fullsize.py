@@ -156,3 +156,37 @@ def test_wide_features_on_the_big_graph():
     ref, mag = oracle.sddmm(w.indptr, w.indices, w.values, w.dY, w.X)
     assert_close(dA, ref, mag, "sddmm d=192")
     A.destroy()
+
+
+def test_max_and_mean_reductions_config3_full():
+    """The benchmark graph at full size: max forward bit for bit (values and positions), max backward (which
+    passes over every entry that no column selected - most entries of the long rows) and mean backward (values
+    divided by the source rows' lengths, kept in the transpose workspace) against the oracle in full."""
+    _say("config 3 reductions: generating")
+    w = graphgen.make_config(3)
+    A = build(w.indptr, w.indices, w.values)
+    isp.csr_transpose_cached(A)
+    X, dY = dev(w.X), dev(w.dY)
+    Y = torch.full_like(X, float("nan"))
+    arg = torch.full((w.n, w.d), -7, dtype=torch.int32, device="cuda")
+    isp.spmm_reduce(A, X, Y, "max", arg)
+    _say("max forward: oracle")
+    ref, ref_arg, _ = oracle.spmm_reduce(w.indptr, w.indices, w.values, w.X, "max", want_mag=False)
+    assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref), "max: values differ"
+    assert np.array_equal(arg.cpu().numpy(), ref_arg), "max: positions differ"
+    del ref
+    named = np.zeros(w.nnz, dtype=bool)
+    named[ref_arg[ref_arg >= 0]] = True
+    _say("entries named by some column: %.1f %%" % (100.0 * named.mean()))
+    assert named.mean() < 0.75  # the pass-over path does real work on this graph
+    dX = torch.full_like(X, float("nan"))
+    isp.spmm_reduce_backward(A, dY, dX, "max", dev(ref_arg))
+    _say("max backward: oracle")
+    ref, mag = oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, w.values, w.dY, "max", ref_arg)
+    assert_close(dX, ref, mag, "max backward")
+    del ref, mag, ref_arg
+    isp.spmm_reduce_backward(A, dY, dX, "mean")
+    _say("mean backward: oracle")
+    ref, mag = oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, w.values, w.dY, "mean")
+    assert_close(dX, ref, mag, "mean backward")
+    A.destroy()

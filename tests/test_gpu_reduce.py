@@ -82,6 +82,29 @@ def test_reduce_default_partition_config1():
     _check(w.indptr, w.indices, w.values, w.n, w.n, 128, seed=4)
 
 
+def test_backward_ignores_positions_outside_the_matrix(small_partition):
+    """The min / max backward first marks which stored entries its arg array names.  arg is the caller's
+    memory: positions outside [0, nnz) (the -1 of empty rows, or junk) must be passed over, not written
+    through, and contribute nothing."""
+    w = graphgen.make_config(1, shrink=128)
+    d, nnz = 40, len(w.indices)
+    rng = np.random.default_rng(11)
+    X = rng.standard_normal((w.n, d)).astype(np.float32)
+    G = rng.standard_normal((w.n, d)).astype(np.float32)
+    _, ref_arg, _ = oracle.spmm_reduce(w.indptr, w.indices, w.values, X, "max")
+    junk = rng.random(ref_arg.shape) < 0.2
+    bad = rng.choice(np.array([-7, -2**31, nnz, nnz + 1000, 2**31 - 1], dtype=np.int64), size=ref_arg.shape)
+    arg_in = np.where(junk, bad, ref_arg).astype(np.int32)
+    arg_ref = np.where(junk, -1, ref_arg).astype(np.int32)   # what the definition makes of them: no entry
+    A = build(w.indptr, w.indices, w.values)
+    isp.csr_transpose_cached(A)
+    dX = torch.full((w.n, d), float("nan"), device="cuda")
+    isp.spmm_reduce_backward(A, dev(G), dX, "max", dev(arg_in))
+    ref, mag = oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, w.values, G, "max", arg_ref)
+    assert_close(dX, ref, mag, "max backward with junk positions")
+    A.destroy()
+
+
 def test_reduce_argument_errors():
     w = graphgen.make_config(0)
     A = build(w.indptr, w.indices, w.values)
