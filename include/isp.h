@@ -179,8 +179,9 @@ isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const
  *         and comparison in fp32; arg[i,k] = position p (index into indices / values) of the first entry that
  *         attains it; empty row -> Y = 0, arg = -1.  arg is int32, n_rows x d, row-major, dense (leading
  *         dimension d), required for min / max, ignored otherwise.
- * sum has the tuned kernels; mean reuses them when width and alignment allow (d and the leading dimensions
- * multiples of 4, 16-byte aligned pointers); min / max run on the generic path.
+ * sum has the tuned kernels; mean reuses them, and min / max have a kernel of the same design, when width and
+ * alignment allow (d and the leading dimensions multiples of 4, 16-byte aligned pointers); other shapes run
+ * on the generic path.
  */
 isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int reduce, float* Y,
                            int64_t ldy, int32_t* arg, void* stream);

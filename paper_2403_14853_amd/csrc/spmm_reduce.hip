@@ -1,8 +1,8 @@
 // Sparse-dense product with the other reductions the paper's matmul offers (Section 3.4, 3.5):
-// mean, min, max - and their backward through the cached transpose.  As in the paper, only the
-// sum reduction has its own tuned kernels; mean reuses them when the operands qualify (rows
-// divided by their length), min / max and everything unaligned run on the generic row-streaming
-// skeleton (one nonzero per wave iteration, any width and alignment).
+// mean, min, max - and their backward through the cached transpose.  The sum reduction has the tuned
+// kernels; mean reuses them when the operands qualify (rows divided by their length), min / max have a
+// grouped forward kernel of the same design for float4-aligned operands, and everything else runs on the
+// generic row-streaming skeleton (one nonzero per wave iteration, any width and alignment).
 //   mean : Y[i] = (sum_p a_p x_j) / len_i
 //   min / max : Y[i,k] = min / max_p a_p x_jk (product and comparison in fp32), arg[i,k] = position p of
 //               the first entry attaining it; empty row -> 0 and -1
@@ -10,7 +10,9 @@
 //   backward min/max : dX[j,k] = sum_{p in column j, arg[row(p),k] == p} a_p dY[row(p),k]
 // Both backward forms are row passes over the cached transpose (whose perm gives p), so no
 // floating-point atomics are needed and results are deterministic.
+#include <stdlib.h>
 #include "row_stream.h"
+#include "group_stream.h"
 
 namespace {
 using namespace isp_dev;
@@ -77,6 +79,148 @@ __global__ void __launch_bounds__(ISP_WG) k_reduce_fwd(isp_view A, const int64_t
   typename P::args pa;
   pa.src[0] = X; pa.ld[0] = ldx; pa.arg = arg; pa.d = d; pa.perm = nullptr;
   stream_item<P>(A, indptr, indices, values, pa, d, k0, Y, ldy);
+}
+
+// ---- grouped forward of min / max ---------------------------------------------------------------------
+// The grouped SpMM's work items, LDS staging, step tables and two-buffer pipeline (group_stream.h) with the
+// accumulation replaced by a running (value, position) pair per column.  A group of LPG lanes covers a slice
+// of 4 * LPG columns and G = 64 / LPG entries share a gather; group g meets entries g, g + G, ... of a row in
+// ascending position, so "replace only if strictly better" keeps the first entry within a group, and the
+// groups' pairs are combined with ties going to the smaller position: the first entry of the row that
+// attains the extremum, as the definition asks.  Hub segments leave (value, position) halves in their
+// partial rows exactly as the generic kernel does, and the same fix-up combines them in segment order.
+// Needs float4 lanes and 32-bit gather offsets; a launch covers at most 128 columns (the partial rows).
+template <int MODE>
+__device__ inline bool mm_better(float t, float best) { return MODE == R_MIN ? t < best : t > best; }
+
+template <int LPG, int MODE, bool HAS_VAL, bool SPARSE_ROWS>
+__global__ void __launch_bounds__(ISP_WG) k_minmax_grouped(isp_view A, const int64_t* __restrict__ indptr,
+                                                           const int32_t* __restrict__ indices,
+                                                           const float* __restrict__ values,
+                                                           const float* __restrict__ X, int64_t ldx, int d, int k_base,
+                                                           int n_slices, float* __restrict__ Y, int64_t ldy,
+                                                           int32_t* __restrict__ arg) {
+  constexpr int G = ISP_WAVE / LPG;
+  constexpr int U = GS_U;
+  __shared__ gs_lds lds;
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int w = threadIdx.x >> 6;
+  const int slice = __builtin_amdgcn_readfirstlane((int)(blockIdx.x % n_slices));
+  const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / n_slices) * ISP_WAVES_PER_WG + w);
+  if (item >= A.n_blocks + A.n_seg) return;
+  const item_range it = locate_item(A, indptr, item);
+  if (it.skip) return;
+  gs_wave_lds& L = lds.w[w];
+  const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane);  // multiple of U
+
+  const int g = lane / LPG, q = lane % LPG;
+  const int col = k_base + (slice * LPG + q) * 4;
+  const bool lane_on = col < d;
+  const unsigned lane_byte = lane_on ? (unsigned)col * 4u : 0u;
+  const unsigned pitch_byte = (unsigned)ldx * 4u;
+  const int p0 = (int)it.p;  // position of the item's first entry (nnz < 2^31)
+
+  float best[4];
+  int where[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) { best[v] = 0.f; where[v] = -1; }
+  const bool listed = SPARSE_ROWS && !it.is_seg;
+  auto store_row = [&](int row) {  // this lane's four columns of one finished row (or segment)
+    if (it.is_seg) {
+      float* pr = A.partials + (int64_t)row * ISP_PARTIAL_TILE + (col - k_base);
+      float wb[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) wb[v] = __int_as_float(where[v]);
+      store_vec<4>(pr, best);
+      store_vec<4>(pr + ARG_OFF, wb);
+    } else {
+      store_vec<4>(Y + (int64_t)row * ldy + col, best);
+      *reinterpret_cast<int4*>(arg + (int64_t)row * d + col) = make_int4(where[0], where[1], where[2], where[3]);
+    }
+  };
+  if (listed && lane_on) {  // empty rows: value 0, position -1
+    const int n_rows = it.row_last - it.row;
+    for (int r = g; r < n_rows; r += G)
+      if (L.rp[r + 1] == L.rp[r]) store_row(it.row + r);
+  }
+  int k_done = 0;
+  int r_next = listed ? (int)L.ss[0] : 0;
+
+  auto finish_row = [&]() {
+    const int row = it.row + __builtin_amdgcn_readfirstlane(r_next);
+    ++k_done;
+    r_next = listed ? (int)L.ss[k_done] : k_done;
+#pragma unroll
+    for (int o = LPG; o < ISP_WAVE; o <<= 1) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float ob = __shfl_xor(best[v], o);
+        const int ow = __shfl_xor(where[v], o);
+        const bool take = ow >= 0 && (where[v] < 0 || mm_better<MODE>(ob, best[v]) || (ob == best[v] && ow < where[v]));
+        best[v] = take ? ob : best[v];
+        where[v] = take ? ow : where[v];
+      }
+    }
+    if (g == 0 && lane_on) store_row(row);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) { best[v] = 0.f; where[v] = -1; }
+  };
+  auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][4], float (&a)[U]) {
+    const uint4 pk = *reinterpret_cast<const uint4*>(L.step + s0);
+    const unsigned raw[4] = {(unsigned)__builtin_amdgcn_readfirstlane(pk.x), (unsigned)__builtin_amdgcn_readfirstlane(pk.y),
+                             (unsigned)__builtin_amdgcn_readfirstlane(pk.z), (unsigned)__builtin_amdgcn_readfirstlane(pk.w)};
+    int2 e[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      dsc[u] = (raw[u >> 1] >> ((u & 1) * 16)) & 0xffffu;
+      e[u] = L.ent[gs_off(dsc[u]) + g];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool act = g < gs_cnt(dsc[u]) && lane_on;
+      a[u] = __int_as_float(e[u].y);
+      const int cj = act ? e[u].x : 0;  // dead lanes gather row 0; what they fetch is never used
+      const unsigned off = __umul24((unsigned)cj, pitch_byte) + lane_byte;
+      load_vec<4>(reinterpret_cast<const float*>(reinterpret_cast<const char*>(X) + off), x[u]);
+    }
+  };
+  auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][4], const float (&a)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (g < gs_cnt(dsc[u]) && lane_on) {
+        const int pos = p0 + gs_off(dsc[u]) + g;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float t = __fmul_rn(a[u], x[u][v]);  // one rounded fp32 multiply, never fused
+          const bool take = where[v] < 0 || mm_better<MODE>(t, best[v]);
+          best[v] = take ? t : best[v];
+          where[v] = take ? pos : where[v];
+        }
+      }
+      if (dsc[u] & GS_LAST) finish_row();
+    }
+  };
+
+  const int n_groups = n_steps / U;
+  if (n_groups == 0) return;
+  unsigned dA[U], dB[U];
+  float xA[U][4], xB[U][4], aA[U], aB[U];
+  issue(0, dA, xA, aA);
+  int gi = 0;
+  while (gi + 2 < n_groups) {
+    issue((gi + 1) * U, dB, xB, aB);
+    consume(dA, xA, aA);
+    issue((gi + 2) * U, dA, xA, aA);
+    consume(dB, xB, aB);
+    gi += 2;
+  }
+  if (gi + 1 < n_groups) {
+    issue((gi + 1) * U, dB, xB, aB);
+    consume(dA, xA, aA);
+    consume(dB, xB, aB);
+  } else {
+    consume(dA, xA, aA);
+  }
 }
 
 // One wave per hub row: combine the segments' partial results in segment order.
@@ -228,9 +372,54 @@ isp_status fwd_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int k0
   return ISP_OK;
 }
 
+template <int LPG, int MODE>
+isp_status minmax_grouped_tile(const isp_csr* A, const float* X, int64_t ldx, int d, int k_base, int n_slices, float* Y,
+                               int64_t ldy, int32_t* arg, hipStream_t s) {
+  const isp_view& v = A->v;
+  const int n_items = v.n_blocks + v.n_seg;
+  if (n_items > 0) {
+    const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * (unsigned)n_slices;
+    const bool sparse_rows = A->info.bin_rows[0] * 16 > A->info.n_rows;  // (as the grouped SpMM chooses)
+#define ISP_GO(HV, SR)                                                                                             \
+  k_minmax_grouped<LPG, MODE, HV, SR><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, X, ldx, d, k_base, \
+                                                              n_slices, Y, ldy, arg)
+    if (v.values) { if (sparse_rows) ISP_GO(true, true); else ISP_GO(true, false); }
+    else { if (sparse_rows) ISP_GO(false, true); else ISP_GO(false, false); }
+#undef ISP_GO
+    ISP_LAUNCH_CHECK();
+  }
+  if (v.n_hub > 0) {
+    k_reduce_fixup<2, MODE><<<hub_grid(v), ISP_WG, 0, s>>>(v, d, k_base, Y, ldy, arg);
+    ISP_LAUNCH_CHECK();
+  }
+  return ISP_OK;
+}
+
 template <int MODE>
 isp_status fwd_all(const isp_csr* A, const float* X, int64_t ldx, int d, float* Y, int64_t ldy, int32_t* arg,
                    hipStream_t s) {
+  const isp_view& av = A->v;
+  if constexpr (MODE != R_MEAN) {
+    // grouped kernel: float4 lanes, 32-bit gather offsets, the partition within the LDS tables' limits
+    const bool a32 = av.n_cols < (1 << 24) && ldx * 4 < (1 << 24) &&
+                     ((uint64_t)av.n_cols * (uint64_t)ldx + (uint64_t)d) * 4u < ((uint64_t)1 << 32);
+    const bool ok = av.nnz > 0 && a32 && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) &&
+                    aligned(Y, 16) && aligned(arg, 16) && A->info.block_cost <= GS_MAX_ROWS &&
+                    A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
+    if (ok) {
+      // 128 columns per launch (a hub partial row holds 128 values and 128 positions), one slice: the two
+      // 64-column slices that pay for the sum on large graphs cost more here than they save, the loop doing
+      // four compare-and-select steps per entry instead of four multiply-adds (config 3: 7.09 vs 6.05 ms)
+      isp_status st = ISP_OK;
+      for (int k_base = 0; k_base < d && st == ISP_OK; k_base += 2 * ISP_WAVE) {
+        const int w = d - k_base < 2 * ISP_WAVE ? d - k_base : 2 * ISP_WAVE;
+        if (w <= 32) st = minmax_grouped_tile<8, MODE>(A, X, ldx, d, k_base, 1, Y, ldy, arg, s);
+        else if (w <= 64) st = minmax_grouped_tile<16, MODE>(A, X, ldx, d, k_base, 1, Y, ldy, arg, s);
+        else st = minmax_grouped_tile<32, MODE>(A, X, ldx, d, k_base, 1, Y, ldy, arg, s);
+      }
+      return st;
+    }
+  }
   // min / max keep (value, position) pairs in the hub partial rows, so their column tiles stop at 128
   const bool v2 = d % 2 == 0 && ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8) && d > ISP_WAVE;
   isp_status st = ISP_OK;

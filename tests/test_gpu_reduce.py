@@ -59,7 +59,9 @@ def _check(indptr, indices, values, n_rows, n_cols, d, seed, integer_inputs=Fals
     A.destroy()
 
 
-@pytest.mark.parametrize("d", [1, 5, 64, 100, 128, 200])
+# widths that are multiples of 4 take the grouped min / max kernel, 102 and 130 the generic one with float2
+# lanes, 1 and 5 with scalar lanes
+@pytest.mark.parametrize("d", [1, 5, 64, 100, 102, 128, 130, 200])
 def test_reduce_small_graph_many_items(small_partition, d):
     w = graphgen.make_config(1, shrink=128)
     _check(w.indptr, w.indices, w.values, w.n, w.n, d, seed=d)
