@@ -192,7 +192,9 @@ isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int3
  *   sum : dX = A^T dY.   mean: dX[j] = sum_{p in column j} (values[p] / len(row(p))) dY[row(p)]; the first
  *         mean call on a handle (and the first after isp_csr_values_changed) computes values[p] / len(row(p))
  *         for every entry, on `stream`, into a part of the transpose workspace that the transposition itself
- *         no longer needs; later calls read it.
+ *         no longer needs; later calls read it.  (A first call made while `stream` is being captured into a
+ *         HIP graph records that pass in the graph and leaves the cache unmarked, so every replay - and the
+ *         next call outside the capture - computes it again; the same holds for the min / max bookkeeping.)
  *   min / max: dX[j,k] = sum over entries p in column j with arg[row(p),k] == p of values[p] dY[row(p),k];
  *         arg is the array the forward call filled; positions outside [0, nnz) name no entry.  Each call
  *         first marks the entries arg names (one byte per entry, in spare transpose workspace) and passes

@@ -353,6 +353,20 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   return ISP_OK;
 }
 
+namespace {
+// While s is being captured into a HIP graph the kernels enqueued here run only when the graph is replayed:
+// the fill is then part of every replay and the cache is not marked filled.
+bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return st == hipStreamCaptureStatusActive;
+}
+
+}  // namespace
+
 isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** out) {
   isp_csr* At = A->At;
   if (!At || !At->mean_values) return isp_fail(ISP_EINVAL, "no cached transpose");
@@ -360,7 +374,7 @@ isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** ou
     k_mean_values<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(At->v.indices, At->v.values, A->v.inv_len, A->v.nnz,
                                                                      At->mean_values);
     ISP_LAUNCH_CHECK();
-    At->mean_values_valid = true;
+    At->mean_values_valid = !stream_is_capturing(s);
   }
   *out = At->mean_values;
   return ISP_OK;
@@ -372,7 +386,7 @@ isp_status isp_transpose_inverse_perm(isp_csr* A, hipStream_t s, const int32_t**
   if (!At->inv_perm_valid && A->v.nnz > 0) {
     k_inverse_perm<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(At->perm, A->v.nnz, At->inv_perm);
     ISP_LAUNCH_CHECK();
-    At->inv_perm_valid = true;
+    At->inv_perm_valid = !stream_is_capturing(s);
   }
   *out = At->inv_perm;
   return ISP_OK;

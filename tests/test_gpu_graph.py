@@ -52,3 +52,40 @@ def test_graph_capture_and_replay_of_a_training_step():
     ref, mag = oracle.spmm(w.indptr, w.indices, w.values, w.X)
     assert_close(Y, ref, mag, "replayed spmm vs oracle")
     A.destroy()
+
+
+def test_first_reduction_backward_inside_a_capture():
+    """The mean and the min / max backward keep per-handle caches (scaled values, the inverse permutation) that
+    the first call fills.  When that first call is being captured the fill must be part of the graph - nothing
+    has run yet - and a later eager call must fill the cache itself."""
+    w = graphgen.make_config(1, shrink=8)
+    A = build(w.indptr, w.indices, w.values)
+    isp.csr_transpose_cached(A)
+    X, dY = dev(w.X), dev(w.dY)
+    _, ref_arg, _ = oracle.spmm_reduce(w.indptr, w.indices, w.values, w.X, "max")
+    arg = dev(ref_arg)
+    dX_mean, dX_max = torch.full_like(X, float("nan")), torch.full_like(X, float("nan"))
+    ref_mean = oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, w.values, w.dY, "mean")
+    ref_max = oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, w.values, w.dY, "max", ref_arg)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):  # no warm-up of these two calls: their first use is captured
+            isp.spmm_reduce_backward(A, dY, dX_mean, "mean")
+            isp.spmm_reduce_backward(A, dY, dX_max, "max", arg)
+    torch.cuda.synchronize()
+    # eager calls before any replay: the captured fills have not run
+    e_mean, e_max = torch.empty_like(X), torch.empty_like(X)
+    isp.spmm_reduce_backward(A, dY, e_mean, "mean")
+    isp.spmm_reduce_backward(A, dY, e_max, "max", arg)
+    torch.cuda.synchronize()
+    assert_close(e_mean, *ref_mean, "eager mean backward after a capture")
+    assert_close(e_max, *ref_max, "eager max backward after a capture")
+    for rep in range(3):
+        dX_mean.fill_(float("nan")); dX_max.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dX_mean, e_mean) and torch.equal(dX_max, e_max), "replay %d" % rep
+    A.destroy()
