@@ -67,6 +67,42 @@ def spmm(graph: SparseGraph, X):
     return _SpMM.apply(graph, graph.values, X)
 
 
+class _SpMMReduce(torch.autograd.Function):
+    """Y = reduce over each row's stored entries of a_p X[col_p] for 'mean', 'min', 'max' (Sections 3.4, 3.5);
+    min / max remember the position of the winning entry per output element for the backward."""
+
+    @staticmethod
+    def forward(ctx, graph, X, reduce):
+        X = X.contiguous()
+        d = X.shape[1]
+        Y = torch.empty(graph.n_rows, d, device=X.device, dtype=torch.float32)
+        arg = None if reduce == "mean" else torch.empty(graph.n_rows, d, device=X.device, dtype=torch.int32)
+        _b.spmm_reduce(graph.handle, X, Y, reduce, arg)
+        ctx.graph, ctx.reduce, ctx.arg = graph, reduce, arg
+        return Y
+
+    @staticmethod
+    def backward(ctx, dY):
+        graph = ctx.graph
+        graph.transpose()  # built on the first backward, cached afterwards
+        dY = dY.contiguous()
+        dX = torch.empty(graph.n_cols, dY.shape[1], device=dY.device, dtype=torch.float32)
+        _b.spmm_reduce_backward(graph.handle, dY, dX, ctx.reduce, ctx.arg)
+        return None, dX, None
+
+
+def matmul(graph: SparseGraph, X, reduce: str = "sum"):
+    """The paper's matmul(sparse, dense, reduce) (Section 3.5): reduce in 'sum' | 'mean' | 'min' | 'max'.
+    Differentiable with respect to X; with respect to the edge values for 'sum' only."""
+    if reduce == "sum":
+        return spmm(graph, X)
+    if reduce not in ("mean", "min", "max"):
+        raise ValueError("reduce must be 'sum', 'mean', 'min' or 'max'")
+    if graph.values is not None and graph.values.requires_grad:
+        raise NotImplementedError("gradients with respect to the edge values exist for reduce='sum' only")
+    return _SpMMReduce.apply(graph, X, reduce)
+
+
 class _FusedMM(torch.autograd.Function):
     @staticmethod
     def forward(ctx, graph, X):

@@ -93,3 +93,31 @@ def test_trained_edge_values_reach_the_cached_transpose():
         with torch.no_grad():
             values.copy_(dev(cur))
     assert g.handle.info()["has_cached_transpose"] == 1
+
+
+@pytest.mark.parametrize("reduce", ["mean", "min", "max"])
+def test_matmul_with_the_other_reductions(reduce):
+    """matmul(graph, X, reduce) as the paper's interface offers it: forward against the oracle (min / max bit
+    for bit), and the gradient with respect to X through the cached transpose."""
+    from paper_2403_14853_amd import autograd as ag
+    w = graphgen.make_config(1, shrink=32)
+    g = ag.SparseGraph(dev(w.indptr), dev(w.indices), dev(w.values))
+    X = dev(w.X).requires_grad_(True)
+    W = dev(w.dY)
+    ref, ref_arg, mag = oracle.spmm_reduce(w.indptr, w.indices, w.values, w.X, reduce)
+    for epoch in range(2):
+        X.grad = None
+        Y = ag.matmul(g, X, reduce)
+        (Y * W).sum().backward()
+        if reduce == "mean":
+            assert_close(Y.detach(), ref, mag, "mean forward")
+        else:
+            assert np.array_equal(Y.detach().cpu().numpy().astype(np.float64), ref)
+        assert_close(X.grad, *oracle.spmm_reduce_backward(w.n, w.indptr, w.indices, w.values, w.dY, reduce, ref_arg),
+                     "%s dX epoch %d" % (reduce, epoch))
+    assert torch.equal(ag.matmul(g, X.detach(), "sum"), ag.spmm(g, X.detach()))
+    with pytest.raises(ValueError):
+        ag.matmul(g, X, "prod")
+    trainable = ag.SparseGraph(dev(w.indptr), dev(w.indices), dev(w.values).requires_grad_(True))
+    with pytest.raises(NotImplementedError):
+        ag.matmul(trainable, X, reduce)
