@@ -53,10 +53,15 @@ partition_params get_params(int64_t n_rows, int64_t nnz) {
   int64_t auto_cost = (nnz + n_rows + 4095) / 4096;
   auto_cost = auto_cost < 16 ? 16 : (auto_cost > 256 ? 256 : auto_cost);
   p.block_cost = env_int("ISP_BLOCK_COST", (int)auto_cost, 16, 256);
-  // ... and shorter hub segments for the same reason (a 512-entry segment is a chain of 32 gather groups)
-  const int auto_seg = 2 * auto_cost < 64 ? 64 : (int)(2 * auto_cost);
-  p.hub_t = env_int("ISP_HUB_THRESHOLD", auto_seg, 8, 512);
-  p.seg_len = env_int("ISP_SEGMENT_LEN", auto_seg, 8, 768);
+  // ... and shorter hub segments, for the same reason and because the segments are the heavy items that the
+  // launch hands out last: a quarter of the per-slot share, between 80 and 512 entries, rows of more than two
+  // segments' worth being hubs (2.4 M entries: segments of 157 instead of 512, 0.512 -> 0.468 ms for four
+  // SpMMs; 0.6 M entries: 0.167 -> 0.155 ms; from 8 M entries up the sizes are 512 / 512 as before).
+  int64_t auto_seg = (nnz + n_rows + 4095) / 4096 / 4;
+  auto_seg = auto_seg < 80 ? 80 : (auto_seg > 512 ? 512 : auto_seg);
+  const int auto_hub = 2 * auto_seg > 512 ? 512 : (int)(2 * auto_seg);
+  p.hub_t = env_int("ISP_HUB_THRESHOLD", auto_hub, 8, 512);
+  p.seg_len = env_int("ISP_SEGMENT_LEN", (int)auto_seg, 8, 768);
   int b = env_int("ISP_BANDS", 32, 1, MAX_BANDS);
   while (b & (b - 1)) b &= b - 1;  // round down to a power of two
   p.bands = b;
