@@ -127,8 +127,8 @@ template <class P>
 __global__ void __launch_bounds__(ISP_WG) k_fused(isp_view A, const int64_t* __restrict__ indptr,
                                                   const int32_t* __restrict__ indices,
                                                   const float* __restrict__ values, typename P::args pa, int d,
-                                                  float* __restrict__ Y, int64_t ldy) {
-  stream_item<P>(A, indptr, indices, values, pa, d, 0, Y, ldy);
+                                                  float* __restrict__ Y, int64_t ldy, int store_group) {
+  stream_item<P>(A, indptr, indices, values, pa, d, 0, Y, ldy, store_group);
 }
 
 template <int VEC, int T, bool ACC>
@@ -136,18 +136,28 @@ __global__ void __launch_bounds__(ISP_WG) k_fused_fixup(isp_view A, int d, float
   hub_fixup<VEC, T, ACC>(A, d, 0, Y, ldy);
 }
 
+template <int VEC, bool ACC>
+__global__ void __launch_bounds__(ISP_WG) k_fused_fixup_group(isp_view A, int d, int k0, float* __restrict__ Y,
+                                                              int64_t ldy) {
+  hub_fixup<VEC, 1, ACC>(A, d, k0, Y, ldy);
+}
+
+// store_group < 0: one launch covers all d <= 256 columns.  Otherwise (wider rows) the launch computes with
+// whole rows but stores column group store_group only, and the fix-up adds that group's partial rows.
 template <class P>
-isp_status run_pass(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s) {
+isp_status run_pass(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s,
+                    int store_group = -1) {
   const isp_view& v = A->v;
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    k_fused<P><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
+    k_fused<P><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy, store_group);
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
     const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    k_fused_fixup<P::VEC, P::T, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, Y, ldy);
+    if (store_group < 0) k_fused_fixup<P::VEC, P::T, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, Y, ldy);
+    else k_fused_fixup_group<P::VEC, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, store_group * ISP_WAVE * P::VEC, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   return ISP_OK;
@@ -287,15 +297,37 @@ isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int
                               int64_t ldy, hipStream_t s) {
   const bool ok4 = ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) && aligned(Y, 16);
   const bool ok2 = ldx % 2 == 0 && ldy % 2 == 0 && aligned(X, 8) && aligned(Y, 8);
-  if (ok4 && d % 4 == 0 && grouped_partition_ok(A)) {
+  if (ok4 && d % 4 == 0 && d <= ISP_PARTIAL_TILE && grouped_partition_ok(A)) {
     g_args1 pa{{X}, {ldx}, {X}, {ldx}, nullptr, op};
     if (op == ISP_OP_SIGMOID) return run_grouped_d<g_fwd<ISP_OP_SIGMOID>>(A, pa, d, Y, ldy, s);
     if (op == ISP_OP_DOT) return run_grouped_d<g_fwd<ISP_OP_DOT>>(A, pa, d, Y, ldy, s);
     return run_grouped_d<g_fwd<ISP_OP_ONE>>(A, pa, d, Y, ldy, s);
   }
-  const int shape = pick_shape(d, ok4, ok2);
   const bool hv = A->v.values != nullptr;
   isp_status st = ISP_OK;
+  if (d > ISP_PARTIAL_TILE) {
+    // wider than a hub partial row: whole rows in the arithmetic (the score needs them), 256 columns stored
+    // per launch (the caller has checked d <= 1024)
+    if (!(ok4 && d % 4 == 0))
+      return isp_fail(ISP_EUNSUPPORTED, "FusedMM with d > %d needs d %% 4 == 0 and 16-byte aligned rows", ISP_PARTIAL_TILE);
+    const int n_groups = (d + ISP_PARTIAL_TILE - 1) / ISP_PARTIAL_TILE;
+    for (int w = 0; w < n_groups && st == ISP_OK; ++w) {
+#define ISP_WIDE(T, HV)                             \
+  {                                                 \
+    using P = fwd_policy<4, T, HV>;                 \
+    P::args pa;                                     \
+    pa.src[0] = X;                                  \
+    pa.ld[0] = ldx;                                 \
+    pa.op = op;                                     \
+    st = run_pass<P>(A, pa, d, Y, ldy, s, w);       \
+  }
+      if (n_groups <= 2) { if (hv) ISP_WIDE(2, true) else ISP_WIDE(2, false) }
+      else { if (hv) ISP_WIDE(4, true) else ISP_WIDE(4, false) }
+#undef ISP_WIDE
+    }
+    return st;
+  }
+  const int shape = pick_shape(d, ok4, ok2);
 #define ISP_FWD(V, T, HV)                         \
   {                                               \
     using P = fwd_policy<V, T, HV>;               \
@@ -314,7 +346,7 @@ isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx,
                                   int32_t d, int op, float* dX, int64_t lddx, hipStream_t s) {
   const bool ok4 = ldx % 4 == 0 && ldg % 4 == 0 && lddx % 4 == 0 && aligned(X, 16) && aligned(G, 16) && aligned(dX, 16);
   const bool ok2 = ldx % 2 == 0 && ldg % 2 == 0 && lddx % 2 == 0 && aligned(X, 8) && aligned(G, 8) && aligned(dX, 8);
-  if (ok4 && d % 4 == 0 && grouped_partition_ok(A) && grouped_partition_ok(A->At)) {
+  if (ok4 && d % 4 == 0 && d <= ISP_PARTIAL_TILE && grouped_partition_ok(A) && grouped_partition_ok(A->At)) {
     g_args12 p1{{X}, {ldx}, {X, G}, {ldx, ldg}, nullptr, op};
     g_args21 p2{{X, G}, {ldx, ldg}, {X}, {ldx}, nullptr, op};
     isp_status st1;
@@ -329,9 +361,33 @@ isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx,
     st1 = run_grouped_d<g_bwd_row<ISP_OP_ONE>>(A, p1, d, dX, lddx, s);
     return st1 != ISP_OK ? st1 : run_grouped_d<g_bwd_col<ISP_OP_ONE>>(A->At, p2, d, dX, lddx, s);
   }
-  const int shape = pick_shape(d, ok4, ok2);
   const bool hv = A->v.values != nullptr;
   isp_status st = ISP_OK;
+  if (d > ISP_PARTIAL_TILE) {  // as in the forward: whole rows in the arithmetic, one column group stored per launch
+    if (!(ok4 && d % 4 == 0))
+      return isp_fail(ISP_EUNSUPPORTED, "FusedMM with d > %d needs d %% 4 == 0 and 16-byte aligned rows", ISP_PARTIAL_TILE);
+    const int n_groups = (d + ISP_PARTIAL_TILE - 1) / ISP_PARTIAL_TILE;
+    for (int w = 0; w < n_groups && st == ISP_OK; ++w) {
+#define ISP_WIDE(T, HV)                                                  \
+  {                                                                      \
+    using P1 = bwd_row_policy<4, T, HV>;                                 \
+    P1::args p1;                                                         \
+    p1.src[0] = X; p1.ld[0] = ldx; p1.G = G; p1.ldg = ldg; p1.op = op;   \
+    st = run_pass<P1>(A, p1, d, dX, lddx, s, w);                         \
+    if (st == ISP_OK) {                                                  \
+      using P2 = bwd_col_policy<4, T, HV>;                               \
+      P2::args p2;                                                       \
+      p2.src[0] = X; p2.ld[0] = ldx; p2.src[1] = G; p2.ld[1] = ldg; p2.op = op; \
+      st = run_pass<P2>(A->At, p2, d, dX, lddx, s, w);                   \
+    }                                                                    \
+  }
+      if (n_groups <= 2) { if (hv) ISP_WIDE(2, true) else ISP_WIDE(2, false) }
+      else { if (hv) ISP_WIDE(4, true) else ISP_WIDE(4, false) }
+#undef ISP_WIDE
+    }
+    return st;
+  }
+  const int shape = pick_shape(d, ok4, ok2);
 #define ISP_BWD(V, T, HV)                                  \
   {                                                        \
     using P1 = bwd_row_policy<V, T, HV>;                   \

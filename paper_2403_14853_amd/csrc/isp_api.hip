@@ -143,7 +143,7 @@ static isp_status check_fused(const isp_csr_t* A, int32_t d, int op) {
   if (op != ISP_OP_SIGMOID && op != ISP_OP_DOT && op != ISP_OP_ONE)
     return isp_fail(ISP_EUNSUPPORTED, "unknown edge op %d", op);
   if (A->v.n_rows != A->v.n_cols) return isp_fail(ISP_EINVAL, "FusedMM needs a square matrix");
-  if (d > ISP_PARTIAL_TILE) return isp_fail(ISP_EUNSUPPORTED, "FusedMM supports d <= %d", ISP_PARTIAL_TILE);
+  if (d > 4 * ISP_PARTIAL_TILE) return isp_fail(ISP_EUNSUPPORTED, "FusedMM supports d <= %d", 4 * ISP_PARTIAL_TILE);
   return check_device(A);
 }
 

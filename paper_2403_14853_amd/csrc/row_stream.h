@@ -109,7 +109,11 @@ struct policy_has_skip<P, std::void_t<decltype(P::HAS_SKIP)>> : std::bool_consta
 template <class P>
 __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                    const int32_t* __restrict__ indices, const float* __restrict__ values,
-                                   const typename P::args& pa, int d, int k0, float* __restrict__ Y, int64_t ldy) {
+                                   const typename P::args& pa, int d, int k0, float* __restrict__ Y, int64_t ldy,
+                                   int store_group = -1) {
+  // store_group >= 0: every column group takes part in the arithmetic but only that one is stored (its
+  // 64 * VEC columns are what a hub segment's partial row then holds): for operations that need whole rows
+  // per entry at widths beyond a partial row, run once per group
   constexpr int VEC = P::VEC, T = P::T, NG = P::NG, U = P::U;
   const int lane = threadIdx.x & (ISP_WAVE - 1);
   const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6)));
@@ -127,7 +131,8 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
   // where results go: Y rows for block items, partial rows for segments
   float* __restrict__ out = it.is_seg ? A.partials : Y;
   const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
-  const int out_k0 = it.is_seg ? k0 : 0;  // partial rows hold only the current column tile
+  // partial rows hold only the current column tile (of it, only the stored group)
+  const int out_k0 = it.is_seg ? k0 + (store_group > 0 ? store_group * ISP_WAVE * VEC : 0) : 0;
 
   int row = it.row;
   const int row_last = it.row_last;
@@ -157,7 +162,7 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
                 it.is_seg ? A.partials + (int64_t)row * ISP_PARTIAL_TILE : nullptr, col, on, k0);
 #pragma unroll
     for (int tt = 0; tt < T; ++tt) {
-      if (on[tt]) {
+      if (on[tt] && (store_group < 0 || tt == store_group)) {
         float* o = out + (int64_t)row * ldo + (col[tt] - out_k0);
         if (P::ACCUMULATE && !it.is_seg) {
           float old[VEC];

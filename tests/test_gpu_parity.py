@@ -92,7 +92,7 @@ def _run_all_ops(indptr, indices, values, n_rows, n_cols, d, seed, fused=True):
     out2 = torch.empty_like(out)
     isp.sddmm(A, Gd, Xd, out2, scale_by_a=True)
     assert torch.equal(out, out2)  # run-to-run bitwise determinism
-    if fused and n_rows == n_cols and d <= 256:
+    if fused and n_rows == n_cols and (d <= 256 or (d <= 1024 and d % 4 == 0)):
         Xs = (0.3 * X).astype(np.float32)
         Xsd = dev(Xs)
         for op in ("sigmoid", "dot", "one"):
@@ -123,6 +123,31 @@ def test_all_ops_small_graph_many_items(small_partition, d):
 def test_wide_features_tile_over_columns(small_partition, d):
     w = graphgen.make_config(1, shrink=256)
     _run_all_ops(w.indptr, w.indices, w.values, w.n, w.n, d, seed=d, fused=False)
+
+
+@pytest.mark.parametrize("d", [260, 512, 516, 1024])
+def test_fusedmm_wider_than_a_partial_row(small_partition, d):
+    """Beyond 256 columns the score still needs whole rows while a hub segment's partial row holds 256: the
+    kernels compute with whole rows and store one 256-column group per launch (2 groups at 260 and 512, the
+    last one ragged at 260; 3 of 4 at 516; 4 at 1024)."""
+    w = graphgen.make_config(1, shrink=256)
+    rng = np.random.default_rng(d)
+    X = (0.1 * rng.standard_normal((w.n, d))).astype(np.float32)
+    G = rng.standard_normal((w.n, d)).astype(np.float32)
+    for values in (w.values, None):
+        A = build(w.indptr, w.indices, values)
+        assert A.info()["n_hub_rows"] > 0
+        isp.csr_transpose_cached(A)
+        Xd, Gd = dev(X), dev(G)
+        for op in ("sigmoid", "dot", "one"):
+            Y = torch.full((w.n, d), float("nan"), device="cuda")
+            isp.fusedmm(A, Xd, Y, op=op)
+            assert_close(Y, *oracle.fusedmm(w.indptr, w.indices, values, X, op=op), "fusedmm %s d=%d" % (op, d))
+            dX = torch.full((w.n, d), float("nan"), device="cuda")
+            isp.fusedmm_backward(A, Xd, Gd, dX, op=op)
+            assert_close(dX, *oracle.fusedmm_backward(w.indptr, w.indices, values, X, G, op=op),
+                         "fusedmm backward %s d=%d" % (op, d))
+        A.destroy()
 
 
 def test_rectangular_unsorted_duplicates_no_values(small_partition):
@@ -247,9 +272,10 @@ def test_malformed_csr_is_rejected():
     with pytest.raises(isp.IspError) as e:  # backward before the transpose exists
         isp.fusedmm_backward(A, X, X, torch.empty_like(X))
     assert e.value.status_name == "ISP_EINVAL"
-    with pytest.raises(isp.IspError) as e:  # FusedMM width limit
-        isp.fusedmm(A, torch.ones(w.n, 260, device="cuda"), torch.empty(w.n, 260, device="cuda"))
-    assert e.value.status_name == "ISP_EUNSUPPORTED"
+    for wide in (1028, 258):  # FusedMM width limits: 1024 columns; beyond 256 only multiples of 4
+        with pytest.raises(isp.IspError) as e:
+            isp.fusedmm(A, torch.ones(w.n, wide, device="cuda"), torch.empty(w.n, wide, device="cuda"))
+        assert e.value.status_name == "ISP_EUNSUPPORTED"
     A.destroy()
 
 
