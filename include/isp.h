@@ -152,7 +152,7 @@ isp_status isp_sddmm(const isp_csr_t* A, const float* U, int64_t ldu, const floa
  * f chosen by op (ISP_OP_SIGMOID, ISP_OP_DOT, ISP_OP_ONE).  The per-edge scores are never written to
  * memory.  d <= 1024; beyond 256 columns d must be a multiple of 4 and the rows 16-byte aligned (base pointers
  * and leading dimensions), else ISP_EUNSUPPORTED.  Up to 256 columns run on the tuned kernels; wider rows on a
- * slower general path that stores 256 columns per pass.
+ * slower general path (one launch per 256 columns for the rows long enough to be split).
  */
 isp_status isp_fusedmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,
                        int64_t ldy, void* stream);

@@ -142,8 +142,9 @@ __global__ void __launch_bounds__(ISP_WG) k_fused_fixup_group(isp_view A, int d,
   hub_fixup<VEC, 1, ACC>(A, d, k0, Y, ldy);
 }
 
-// store_group < 0: one launch covers all d <= 256 columns.  Otherwise (wider rows) the launch computes with
-// whole rows but stores column group store_group only, and the fix-up adds that group's partial rows.
+// store_group < 0: one launch covers all d <= 256 columns.  Otherwise (wider rows) one launch per column
+// group: hub segments compute with whole rows but store that group only, and the fix-up adds the group's
+// partial rows; the row blocks do all their work in the launch of group 0.
 template <class P>
 isp_status run_pass(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s,
                     int store_group = -1) {
@@ -367,24 +368,32 @@ isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx,
     if (!(ok4 && d % 4 == 0))
       return isp_fail(ISP_EUNSUPPORTED, "FusedMM with d > %d needs d %% 4 == 0 and 16-byte aligned rows", ISP_PARTIAL_TILE);
     const int n_groups = (d + ISP_PARTIAL_TILE - 1) / ISP_PARTIAL_TILE;
-    for (int w = 0; w < n_groups && st == ISP_OK; ++w) {
-#define ISP_WIDE(T, HV)                                                  \
+    // every row pass before the first column pass: the column pass of group 0 already adds to all columns of
+    // the rows that are not hubs of A^T, which a later row pass's fix-up must not overwrite
+#define ISP_WIDE_ROW(T, HV)                                              \
   {                                                                      \
     using P1 = bwd_row_policy<4, T, HV>;                                 \
     P1::args p1;                                                         \
     p1.src[0] = X; p1.ld[0] = ldx; p1.G = G; p1.ldg = ldg; p1.op = op;   \
     st = run_pass<P1>(A, p1, d, dX, lddx, s, w);                         \
-    if (st == ISP_OK) {                                                  \
-      using P2 = bwd_col_policy<4, T, HV>;                               \
-      P2::args p2;                                                       \
-      p2.src[0] = X; p2.ld[0] = ldx; p2.src[1] = G; p2.ld[1] = ldg; p2.op = op; \
-      st = run_pass<P2>(A->At, p2, d, dX, lddx, s, w);                   \
-    }                                                                    \
   }
-      if (n_groups <= 2) { if (hv) ISP_WIDE(2, true) else ISP_WIDE(2, false) }
-      else { if (hv) ISP_WIDE(4, true) else ISP_WIDE(4, false) }
-#undef ISP_WIDE
+#define ISP_WIDE_COL(T, HV)                                              \
+  {                                                                      \
+    using P2 = bwd_col_policy<4, T, HV>;                                 \
+    P2::args p2;                                                         \
+    p2.src[0] = X; p2.ld[0] = ldx; p2.src[1] = G; p2.ld[1] = ldg; p2.op = op; \
+    st = run_pass<P2>(A->At, p2, d, dX, lddx, s, w);                     \
+  }
+    for (int w = 0; w < n_groups && st == ISP_OK; ++w) {
+      if (n_groups <= 2) { if (hv) ISP_WIDE_ROW(2, true) else ISP_WIDE_ROW(2, false) }
+      else { if (hv) ISP_WIDE_ROW(4, true) else ISP_WIDE_ROW(4, false) }
     }
+    for (int w = 0; w < n_groups && st == ISP_OK; ++w) {
+      if (n_groups <= 2) { if (hv) ISP_WIDE_COL(2, true) else ISP_WIDE_COL(2, false) }
+      else { if (hv) ISP_WIDE_COL(4, true) else ISP_WIDE_COL(4, false) }
+    }
+#undef ISP_WIDE_ROW
+#undef ISP_WIDE_COL
     return st;
   }
   const int shape = pick_shape(d, ok4, ok2);

@@ -111,15 +111,18 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
                                    const int32_t* __restrict__ indices, const float* __restrict__ values,
                                    const typename P::args& pa, int d, int k0, float* __restrict__ Y, int64_t ldy,
                                    int store_group = -1) {
-  // store_group >= 0: every column group takes part in the arithmetic but only that one is stored (its
-  // 64 * VEC columns are what a hub segment's partial row then holds): for operations that need whole rows
-  // per entry at widths beyond a partial row, run once per group
+  // store_group >= 0 (operations that need whole rows per entry, at widths beyond a partial row; one launch
+  // per column group): a hub segment computes with every group but stores only that one - its 64 * VEC
+  // columns are what the partial row then holds; row blocks write whole output rows, so they run in the
+  // launch of group 0 only
   constexpr int VEC = P::VEC, T = P::T, NG = P::NG, U = P::U;
   const int lane = threadIdx.x & (ISP_WAVE - 1);
   const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6)));
   if (item >= A.n_blocks + A.n_seg) return;
   item_range it = locate_item(A, indptr, item);
   if (it.skip) return;
+  if (store_group > 0 && !it.is_seg) return;
+  if (!it.is_seg) store_group = -1;
 
   int col[T];      // first feature column of this lane in each group, relative to the matrix
   bool on[T];
