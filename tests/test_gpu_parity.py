@@ -150,6 +150,22 @@ def test_fusedmm_wider_than_a_partial_row(small_partition, d):
         A.destroy()
 
 
+def test_one_row_owning_most_entries():
+    """A single row with 150,000 entries among short ones (default partition: about two thousand segments for
+    that row): the fix-ups of every kernel family combine a long chain of partial rows - SpMM and its
+    backward, SDDMM, FusedMM and the reductions."""
+    n, d, long_row, long_len = 3000, 64, 1500, 150_000
+    rng = np.random.default_rng(77)
+    lens = rng.integers(0, 9, size=n)
+    lens[long_row] = long_len
+    indptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    indices = np.concatenate([np.sort(rng.integers(0, n, size=k)) for k in lens]).astype(np.int32)
+    values = rng.uniform(-1, 1, size=len(indices)).astype(np.float32)
+    _run_all_ops(indptr, indices, values, n, n, d, seed=78)
+    import test_gpu_reduce
+    test_gpu_reduce._check(indptr, indices, values, n, n, d, seed=79)
+
+
 def test_rectangular_unsorted_duplicates_no_values(small_partition):
     indptr, indices, values = graphgen.random_csr(700, 333, 9000, 5, sorted_cols=False, allow_dup=True)
     _run_all_ops(indptr, indices, values, 700, 333, 48, seed=1)
