@@ -88,6 +88,22 @@ def test_random_shape(seed):
             assert_close(dXf[:, :d].contiguous(), *oracle.fusedmm_backward(indptr, indices, values, Xs[:, :d], G, op=op),
                          "fusedmm backward " + op)
             assert torch.all(Yf[:, d:] == 3.0) and torch.all(dXf[:, d:] == 3.0)
+        # one of the other reductions, forward (min / max bit for bit) and backward, on padded rows too
+        reduce = ("mean", "min", "max")[(seed // 3) % 3]
+        Yr = torch.full((n_rows, ld), 3.0, device="cuda")
+        arg = torch.full((n_rows, d), -7, dtype=torch.int32, device="cuda") if reduce != "mean" else None
+        isp.spmm_reduce(A, Xd, Yr[:, :d], reduce, arg)
+        ref, ref_arg, mag = oracle.spmm_reduce(indptr, indices, values, X, reduce)
+        if reduce == "mean":
+            assert_close(Yr[:, :d].contiguous(), ref, mag, "mean")
+        else:
+            assert np.array_equal(Yr[:, :d].cpu().numpy().astype(np.float64), ref), reduce + ": values differ"
+            assert np.array_equal(arg.cpu().numpy(), ref_arg), reduce + ": positions differ"
+        dXr = torch.full((n_cols, ld), 3.0, device="cuda")
+        isp.spmm_reduce_backward(A, Gd, dXr[:, :d], reduce, None if reduce == "mean" else dev(ref_arg))
+        assert_close(dXr[:, :d].contiguous(), *oracle.spmm_reduce_backward(n_cols, indptr, indices, values, G, reduce, ref_arg),
+                     reduce + " backward")
+        assert torch.all(Yr[:, d:] == 3.0) and torch.all(dXr[:, d:] == 3.0)
         A.destroy()
     finally:
         for k in c["env"]:
