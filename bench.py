@@ -242,7 +242,7 @@ def main():
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); keyed by (config, shrink).  None = not measured for that workload.
 TRAFFIC_BYTES = {
-    (3, 1): 37.39e9,  # profiles/spmm_c3-rmat2.4m-d128.txt: 2 x FETCH_SIZE (calibrated) + WRITE_SIZE of k_spmm_grouped
+    (3, 1): 35.42e9,  # profiles/spmm_c3-rmat2.4m-d128.txt: 2 x FETCH_SIZE (calibrated) + WRITE_SIZE of k_spmm_grouped
 }
 
 

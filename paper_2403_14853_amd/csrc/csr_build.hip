@@ -42,7 +42,7 @@ int env_int(const char* name, int dflt, int lo, int hi) {
   return (int)v;
 }
 
-partition_params get_params(int64_t n_rows, int64_t nnz) {
+partition_params get_params(int64_t n_rows, int64_t n_cols, int64_t nnz) {
   partition_params p;
   // Upper limits = what the grouped kernels' per-wave LDS tables hold (block_cost + hub_t <= 768
   // entries, block_cost <= 256 rows, seg_len <= 768 entries).  The environment overrides exist for
@@ -57,8 +57,13 @@ partition_params get_params(int64_t n_rows, int64_t nnz) {
   // launch hands out last: a quarter of the per-slot share, between 80 and 512 entries, rows of more than two
   // segments' worth being hubs (2.4 M entries: segments of 157 instead of 512, 0.512 -> 0.468 ms for four
   // SpMMs; 0.6 M entries: 0.167 -> 0.155 ms; from 8 M entries up the sizes are 512 / 512 as before).
+  // With many columns a column band of the dense operand is far larger than an L2, and finer pieces of the
+  // hub rows (segments of at most 384, pieces from 192 entries) keep more of each segment's gathers inside its
+  // band (2.4 M columns: 5.30 -> 5.19 ms per SpMM, the other kernels 1-3 %); with few columns a band's popular
+  // rows fit an L2 anyway and the longer segments win (233 k columns: SDDMM 3.21 vs 3.32 ms).
+  const int seg_cap = n_cols >= (1 << 19) ? 384 : 512;
   int64_t auto_seg = (nnz + n_rows + 4095) / 4096 / 4;
-  auto_seg = auto_seg < 80 ? 80 : (auto_seg > 512 ? 512 : auto_seg);
+  auto_seg = auto_seg < 80 ? 80 : (auto_seg > seg_cap ? seg_cap : auto_seg);
   const int auto_hub = 2 * auto_seg > 512 ? 512 : (int)(2 * auto_seg);
   p.hub_t = env_int("ISP_HUB_THRESHOLD", auto_hub, 8, 512);
   p.seg_len = env_int("ISP_SEGMENT_LEN", (int)auto_seg, 8, 768);
@@ -360,14 +365,14 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
 
 }  // namespace
 
-size_t isp_partition_workspace(int64_t n_rows, int64_t nnz) {
-  return make_layout(n_rows, nnz, get_params(n_rows, nnz)).total;
+size_t isp_partition_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz) {
+  return make_layout(n_rows, nnz, get_params(n_rows, n_cols, nnz)).total;
 }
 
 isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
                             const int32_t* indices, const float* values, void* ws, size_t ws_bytes, bool validate,
                             hipStream_t s, isp_csr** out) {
-  const partition_params pp = get_params(n_rows, nnz);
+  const partition_params pp = get_params(n_rows, n_cols, nnz);
   const ws_layout L = make_layout(n_rows, nnz, pp);
   if (ws_bytes < L.total) return isp_fail(ISP_EINVAL, "workspace too small: %zu < %zu bytes", ws_bytes, L.total);
   if (((uintptr_t)ws & 255) != 0) return isp_fail(ISP_EINVAL, "workspace must be 256-byte aligned");

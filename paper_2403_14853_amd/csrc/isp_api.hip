@@ -32,7 +32,7 @@ isp_status isp_csr_build_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz, 
   if (!bytes) return isp_fail(ISP_EINVAL, "bytes is NULL");
   isp_status st = check_shape(n_rows, n_cols, nnz);
   if (st != ISP_OK) return st;
-  *bytes = isp_partition_workspace(n_rows, nnz);
+  *bytes = isp_partition_workspace(n_rows, n_cols, nnz);
   return ISP_OK;
 }
 

@@ -70,7 +70,7 @@ isp_status isp_scan_i32_to_i64(const int32_t* in, int64_t* out, int64_t n, void*
 isp_status isp_scan_i32_to_i32(const int32_t* in, int32_t* out, int64_t n, void* tmp, hipStream_t s);
 
 // ---- partition (csr_build.hip) ---------------------------------------------------------------
-size_t isp_partition_workspace(int64_t n_rows, int64_t nnz);
+size_t isp_partition_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz);
 isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
                             const int32_t* indices, const float* values, void* ws, size_t ws_bytes,
                             bool validate, hipStream_t s, isp_csr** out);

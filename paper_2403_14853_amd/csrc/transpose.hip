@@ -249,7 +249,6 @@ struct t_layout {
 };
 
 t_layout make_layout(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_values) {
-  (void)n_rows;
   t_layout L;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += isp_align(bytes); return o; };
@@ -267,7 +266,7 @@ t_layout make_layout(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_value
   L.table = take((size_t)(tbl + 1) * 4);
   L.table_scanned = take((size_t)(tbl + 1) * 4);
   L.scan_tmp = take(isp_scan_tmp_bytes(tbl + 1));
-  L.part = take(isp_partition_workspace(n_cols, nnz));
+  L.part = take(isp_partition_workspace(n_cols, n_rows, nnz));  // (A^T: n_cols rows, n_rows columns)
   L.total = off;
   return L;
 }
