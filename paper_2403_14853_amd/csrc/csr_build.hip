@@ -314,10 +314,36 @@ __global__ void __launch_bounds__(SO_TILE) k_seg_scatter(const int32_t* __restri
   val_out[dst] = val_in ? val_in[s] : s;
 }
 
+// What work item `item` covers, written once per handle (see isp_view::item_desc).
+__global__ void __launch_bounds__(256) k_item_desc(const int64_t* __restrict__ indptr, const int32_t* __restrict__ blk_row,
+                                                   int n_blocks, const int32_t* __restrict__ hub_rows,
+                                                   const int32_t* __restrict__ hub_seg_ptr,
+                                                   const int32_t* __restrict__ seg_hub,
+                                                   const int32_t* __restrict__ seg_begin,
+                                                   const int32_t* __restrict__ seg_order, int n_seg, int hub_t,
+                                                   int4* __restrict__ desc) {
+  const int item = blockIdx.x * blockDim.x + threadIdx.x;
+  if (item >= n_blocks + n_seg) return;
+  int4 q;
+  if (item < n_blocks) {
+    const int row = blk_row[item], row_last = blk_row[item + 1];
+    const int64_t p = indptr[row], p_end = indptr[row_last];
+    const bool skip = (row_last == row + 1) && (p_end - p > hub_t);
+    q = make_int4((int)p, (int)p_end, row, skip ? -1 : row_last);
+  } else {
+    const int s = seg_order[item - n_blocks];
+    const int h = seg_hub[s];
+    const int hr = hub_rows[h];
+    const int64_t p_end = (s + 1 < hub_seg_ptr[h + 1]) ? (int64_t)seg_begin[s + 1] : indptr[hr + 1];
+    q = make_int4(seg_begin[s], (int)p_end, s, hr);
+  }
+  desc[item] = q;
+}
+
 struct ws_layout {
   size_t counters, cost, hubflag, nseg, cum_cost, mark, mpos, hpos, segbase, scan_tmp;
   size_t blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin, seg_key[2], seg_order[2], so_table, so_scanned, so_tmp;
-  size_t inv_len, partials, total;
+  size_t inv_len, item_desc, partials, total;
   int64_t max_blocks, max_hub, max_seg;
 };
 
@@ -358,6 +384,7 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
   L.so_scanned = take((size_t)(so_tbl + 1) * 4);
   L.so_tmp = take(isp_scan_tmp_bytes(so_tbl + 1));
   L.inv_len = take((size_t)(n_rows + 1) * 4);
+  L.item_desc = take((size_t)(max_blocks + max_seg + 2) * 16);
   L.partials = take((size_t)(max_seg + 1) * ISP_PARTIAL_TILE * sizeof(float));
   L.total = off;
   return L;
@@ -453,6 +480,14 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
     seg_order = seg_ord[n_pass & 1];
   }
 
+  int4* item_desc = (int4*)(base + L.item_desc);
+  if (h.n_blocks + h.n_seg > 0) {
+    k_item_desc<<<(unsigned)((h.n_blocks + h.n_seg + 255) / 256), 256, 0, s>>>(indptr, blk_row, h.n_blocks, hub_rows,
+                                                                             hub_seg_ptr, seg_hub, seg_begin, seg_order,
+                                                                             h.n_seg, pp.hub_t, item_desc);
+    ISP_LAUNCH_CHECK();
+  }
+
   int device = 0;
   ISP_HIP(hipGetDevice(&device));
   isp_csr* A = new (std::nothrow) isp_csr();
@@ -462,7 +497,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->v.indptr = indptr; A->v.indices = indices; A->v.values = values;
   A->v.blk_row = blk_row; A->v.n_blocks = h.n_blocks;
   A->v.hub_rows = hub_rows; A->v.hub_seg_ptr = hub_seg_ptr; A->v.seg_hub = seg_hub;
-  A->v.seg_begin = seg_begin; A->v.seg_order = seg_order;
+  A->v.seg_begin = seg_begin; A->v.seg_order = seg_order; A->v.item_desc = item_desc;
   A->v.n_hub = h.n_hub; A->v.n_seg = h.n_seg;
   A->v.hub_t = pp.hub_t; A->v.seg_len = pp.seg_len;
   A->v.partials = (float*)(base + L.partials);

@@ -27,6 +27,9 @@ struct isp_view {
   const int32_t* seg_begin;  // n_seg: position of each segment's first nonzero; a segment ends where the
                              // row's next one begins, the row's last one at the end of the row
   const int32_t* seg_order;  // n_seg: work item n_blocks + k processes segment seg_order[k] (in order of first column)
+  const int4* item_desc;     // n_blocks + n_seg: what each work item covers, resolved at build time so that a
+                             // wavefront starts with one 16-byte load instead of a chain through the tables
+                             // above: (first entry, end, first row | segment, end row or -1 = skip | hub row)
   int32_t n_hub, n_seg;
   int32_t hub_t, seg_len;
   float* partials;         // n_seg * ISP_PARTIAL_TILE floats

@@ -67,26 +67,22 @@ struct item_range {
 };
 
 __device__ inline item_range locate_item(const isp_view& A, const int64_t* __restrict__ indptr, int item) {
+  (void)indptr;
   item_range r;
+  const int4 q = A.item_desc[item];  // item is wave-uniform: one scalar load
   r.is_seg = item >= A.n_blocks;
-  r.skip = false;
+  r.p = q.x;
+  r.p_end = q.y;
+  r.row = q.z;
   if (!r.is_seg) {
-    r.row = A.blk_row[item];
-    r.row_last = A.blk_row[item + 1];
-    r.src_row = r.row;
-    r.p = indptr[r.row];
-    r.p_end = indptr[r.row_last];
-    // a block made of one hub row is empty here: its nonzeros are covered by segment items
-    r.skip = (r.row_last == r.row + 1) && (r.p_end - r.p > A.hub_t);
+    // a block made of one hub row is empty here (its nonzeros are covered by segment items): end row -1
+    r.skip = q.w < 0;
+    r.row_last = q.w;
+    r.src_row = q.z;
   } else {
-    const int s = A.seg_order[item - A.n_blocks];
-    const int h = A.seg_hub[s];
-    const int hr = A.hub_rows[h];
-    r.p = A.seg_begin[s];
-    r.p_end = (s + 1 < A.hub_seg_ptr[h + 1]) ? (int64_t)A.seg_begin[s + 1] : indptr[hr + 1];
-    r.row = s;
-    r.row_last = s + 1;
-    r.src_row = hr;
+    r.skip = false;
+    r.row_last = q.z + 1;  // (row = the segment's number, which names its partial row)
+    r.src_row = q.w;       // the hub row
   }
   return r;
 }
