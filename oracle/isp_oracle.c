@@ -24,7 +24,8 @@
  *     pinned by finite differences in the tests.
  *
  * Parity pins (tests/test_oracle_*.py): dense brute force, scipy, closed forms, adjoint
- * identities, finite differences.  No function here is unpinned.
+ * identities, finite differences; the error-scale outputs (mag) are each recomputed in dense
+ * fp64 from their formulas.  No function or output here is unpinned.
  *
  * Conventions: indptr int64[n_rows+1], indices int32[nnz], values float[nnz] or NULL (= all
  * ones); dense matrices fp32 row-major with leading dimension ld (elements).  Rows may hold
@@ -249,8 +250,12 @@ void isp_oracle_fusedmm_backward(int64_t n, const int64_t* indptr, const int32_t
  *   mean: Y[i,k] = (sum_p a_p x_jk) / len_i, len_i = stored entries of row i; empty row -> 0.
  *   min / max: Y[i,k] = min / max over the stored entries p of row i of a_p * x_jk; arg[i,k] = the
  *     position p (index into the CSR arrays) of the first entry attaining it; empty row -> 0, arg -1.
- * For min / max the product is formed and compared in fp32 (one rounded multiply), the precision
- * the GPU kernel decides in, so values and arg positions can be compared bit for bit.
+ * For min / max the product is formed and compared in fp32 (one rounded multiply), the precision of
+ * the method's arithmetic, so that the position (an integer decided by floating point) is decided in
+ * the same precision on both sides and can be compared bit for bit.  Against the plain fp64 definition
+ * this changes nothing in the value (rounding is monotone: the fp32 extremum is the fp64 extremum
+ * rounded once) and moves the position only between entries whose products round to the same fp32
+ * number; tests/test_oracle_scale_pins.py asserts exactly that against an fp64 brute force.
  * reduce: 1 mean, 2 min, 3 max.  arg may be NULL for mean.  mag (mean only, may be NULL) is the sum
  * of |a_p x_jk| / len_i. */
 void isp_oracle_spmm_reduce(int64_t n_rows, const int64_t* indptr, const int32_t* indices, const float* values,

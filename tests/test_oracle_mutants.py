@@ -9,6 +9,7 @@ import pytest
 import oracle
 import test_oracle_pins as pins
 import test_oracle_reduce_pins as rpins
+import test_oracle_scale_pins as spins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "isp_oracle.c")
 
@@ -66,6 +67,72 @@ MUTANTS = [
     ("mean backward: weight without the division by the row length",
      "        const double w = (values ? (double)values[p] : 1.0) / (double)(e - s);", "        const double w = (values ? (double)values[p] : 1.0);",
      [rpins.test_reduce_backward_is_the_adjoint_of_the_selected_linear_map]),
+    # ---- the error scales (mag) the FusedMM / reduction parity tests divide by
+    ("fusedmm scale: doubled",
+     "        if (m) m[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)xj[k]);",
+     "        if (m) m[k] += 2.0 * fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)xj[k]);",
+     [spins.test_fusedmm_forward_scale]),
+    ("fusedmm scale: edge value without the absolute value",
+     "        if (m) m[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)xj[k]);",
+     "        if (m) m[k] += a * (fabs(s) + edge_l1(op) * za) * fabs((double)xj[k]);",
+     [spins.test_fusedmm_forward_scale]),
+    ("fusedmm scale: the dot product's share (L1 term) dropped",
+     "        if (m) m[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)xj[k]);",
+     "        if (m) m[k] += fabs(a) * fabs(s) * fabs((double)xj[k]);",
+     [spins.test_fusedmm_forward_scale]),
+    ("fusedmm scale: derivative bound of the sigmoid inflated",
+     "static double edge_l1(int op) { return op == 0 ? 0.25 :", "static double edge_l1(int op) { return op == 0 ? 250.0 :",
+     [spins.test_fusedmm_forward_scale]),
+    ("fusedmm scale: za accumulated without the absolute value",
+     "        z += t;\n        za += fabs(t);", "        z += t;\n        za += t;",
+     [spins.test_fusedmm_forward_scale]),
+    ("fusedmm backward scale: dz bound doubled",
+     "      const double dzm = fabs(a) * gda * (fabs(edge_df(op, z)) + edge_l2(op) * za);",
+     "      const double dzm = 2.0 * fabs(a) * gda * (fabs(edge_df(op, z)) + edge_l2(op) * za);",
+     [spins.test_fusedmm_backward_scale]),
+    ("fusedmm backward scale: second-derivative (L2) term dropped",
+     "      const double dzm = fabs(a) * gda * (fabs(edge_df(op, z)) + edge_l2(op) * za);",
+     "      const double dzm = fabs(a) * gda * fabs(edge_df(op, z));",
+     [spins.test_fusedmm_backward_scale]),
+    ("fusedmm backward scale: second-derivative bound inflated",
+     "static double edge_l2(int op) { return op == 0 ? 0.1 : 0.0; }", "static double edge_l2(int op) { return op == 0 ? 100.0 : 0.0; }",
+     [spins.test_fusedmm_backward_scale]),
+    ("fusedmm backward scale: row term multiplied by 1000",
+     "          mi[k] += dzm * fabs((double)xj[k]);", "          mi[k] += 1000.0 * dzm * fabs((double)xj[k]);",
+     [spins.test_fusedmm_backward_scale]),
+    ("fusedmm backward scale: direct term of the column part doubled",
+     "          mj[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)gi[k]) + dzm * fabs((double)xi[k]);",
+     "          mj[k] += 2.0 * fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)gi[k]) + dzm * fabs((double)xi[k]);",
+     [spins.test_fusedmm_backward_scale]),
+    ("fusedmm backward scale: L1 term of the column part dropped",
+     "          mj[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)gi[k]) + dzm * fabs((double)xi[k]);",
+     "          mj[k] += fabs(a) * fabs(s) * fabs((double)gi[k]) + dzm * fabs((double)xi[k]);",
+     [spins.test_fusedmm_backward_scale]),
+    ("fusedmm backward scale: the z path of the column part dropped",
+     "          mj[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)gi[k]) + dzm * fabs((double)xi[k]);",
+     "          mj[k] += fabs(a) * (fabs(s) + edge_l1(op) * za) * fabs((double)gi[k]);",
+     [spins.test_fusedmm_backward_scale]),
+    ("fusedmm backward scale: |g x| accumulated without the absolute value",
+     "        gda += fabs(t);", "        gda += t;",
+     [spins.test_fusedmm_backward_scale]),
+    ("mean scale: not divided by the row length",
+     "        if (m) m[k] = e > s ? am / (double)(e - s) : 0.0;", "        if (m) m[k] = e > s ? am : 0.0;",
+     [spins.test_mean_scale]),
+    ("mean scale: doubled",
+     "          am += fabs(t);", "          am += 2.0 * fabs(t);",
+     [spins.test_mean_scale]),
+    ("mean backward scale: doubled",
+     "          if (m) m[k] += fabs(w * (double)g[k]);", "          if (m) m[k] += 2.0 * fabs(w * (double)g[k]);",
+     [spins.test_reduce_backward_scale]),
+    ("min / max backward scale: doubled",
+     "        if (mag) mag[(int64_t)indices[p] * d + k] += fabs(t);", "        if (mag) mag[(int64_t)indices[p] * d + k] += 2.0 * fabs(t);",
+     [spins.test_reduce_backward_scale]),
+    ("min / max backward scale: without the absolute value",
+     "        if (mag) mag[(int64_t)indices[p] * d + k] += fabs(t);", "        if (mag) mag[(int64_t)indices[p] * d + k] += t;",
+     [spins.test_reduce_backward_scale]),
+    ("min / max: products compared in fp64 but reported position of the last near-tie",
+     "(reduce == 2 ? tv < best : tv > best)", "(reduce == 2 ? tv <= best : tv >= best)",
+     [spins.test_minmax_against_the_fp64_definition]),
 ]
 
 
