@@ -32,12 +32,25 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def use_library(path):
+    """Point this module at another build of gen.cpp (the sanitizer test loads an instrumented one);
+    ``None`` goes back to the real one."""
+    global _lib
+    _lib = None
+    if path is not None:
+        _lib = _bind(ctypes.CDLL(path))
+
+
 def _load():
     global _lib
     if _lib is not None:
         return _lib
     build()
-    lib = ctypes.CDLL(_LIB)
+    _lib = _bind(ctypes.CDLL(_LIB))
+    return _lib
+
+
+def _bind(lib):
     i32p = ctypes.POINTER(ctypes.c_int32)
     i64p = ctypes.POINTER(ctypes.c_int64)
     f32p = ctypes.POINTER(ctypes.c_float)
@@ -58,7 +71,6 @@ def _load():
     lib.gg_fill_normal.argtypes = [f32p, ctypes.c_int64, ctypes.c_uint64, ctypes.c_double, ctypes.c_double]
     lib.gg_fill_normal.restype = None
     lib.gg_max_threads.restype = ctypes.c_int
-    _lib = lib
     return lib
 
 

@@ -31,6 +31,14 @@
  *   - Calls that use the same handle (or a handle and its cached transpose) on different streams
  *     at the same time race on the handle's scratch (hub-row partial sums); serialise them.
  *   - Results are run-to-run bitwise deterministic: no floating-point atomics are used.
+ *   - Environment variables (tuning and tests only; none is needed).  All are read when isp_csr_build runs and
+ *     are kept in the handle (a cached transpose inherits its source's); no compute call reads the environment.
+ *       ISP_BLOCK_COST, ISP_HUB_THRESHOLD, ISP_SEGMENT_LEN, ISP_BANDS, ISP_MIN_PIECE, ISP_MID_THRESHOLD:
+ *                              sizes of the work partition (clamped to what the kernels' tables hold)
+ *       ISP_NO_GROUPED         run every operation on the general kernels
+ *       ISP_SPMM_LPG, ISP_SPMM_TILE   lanes per group / feature columns per launch of the tuned SpMM
+ *       ISP_SDDMM_ONE_PASS     SDDMM keeps 128-column rows in one pass
+ *     isp_csr_build_workspace reads the partition sizes too, so set them before both calls or not at all.
  */
 #ifndef ISP_H
 #define ISP_H
@@ -117,8 +125,14 @@ isp_status isp_csr_transpose_cached(isp_csr_t* A, void* workspace, size_t worksp
  * Tell the handle that the caller has overwritten A's values array in place (same pointer, same structure),
  * as happens every epoch when the edge values are trained from the SDDMM gradients.  What Section 3.3 caches
  * stays cached - A^T's structure, its permutation and both work partitions - and only the transposed values
- * are gathered again: t_values[q] = values[perm[q]], one asynchronous pass on `stream`.  A no-op for a handle
- * without values or without a cached transpose.  A must be the source handle, not its transpose.
+ * are gathered again: t_values[q] = values[perm[q]], one asynchronous pass on `stream`; if a mean-reduction
+ * backward has run on the handle, the per-entry values it keeps (value / row length) are recomputed right
+ * behind it on the same stream.  Everything happens in stream order, so the call may be captured into a HIP
+ * graph (every replay refreshes), and graphs captured earlier read the refreshed arrays.  What a graph cannot
+ * see is a change of the cache's bookkeeping on the host: a graph captured BEFORE the first mean backward of a
+ * handle contains that first call's fill pass and keeps running it on every replay - correct, only redundant.
+ * A no-op for a handle without values or without a cached transpose.  A must be the source handle, not its
+ * transpose.
  */
 isp_status isp_csr_values_changed(isp_csr_t* A, void* stream);
 

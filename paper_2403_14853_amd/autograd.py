@@ -124,5 +124,7 @@ class _FusedMM(torch.autograd.Function):
 
 
 def fusedmm(graph: SparseGraph, X):
-    """Differentiable sigmoid FusedMM: y_i = sum_j a_ij sigmoid(<x_i, x_j>) x_j."""
+    """Differentiable sigmoid FusedMM: y_i = sum_j a_ij sigmoid(<x_i, x_j>) x_j (with respect to X only)."""
+    if graph.values is not None and graph.values.requires_grad:
+        raise NotImplementedError("FusedMM has no gradient with respect to the edge values")
     return _FusedMM.apply(graph, X)

@@ -30,7 +30,7 @@ def _run(cmd, verbose):
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every source to an object (in parallel), link libisp.so, build the bandwidth probe."""
+    """Compile every source to an object (in parallel), link libisp.so, build the C-ABI example."""
     from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")
@@ -44,14 +44,6 @@ def build(verbose: bool = False) -> str:
     tmp = LIB + ".tmp%d" % os.getpid()
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp], verbose)
     os.replace(tmp, LIB)
-    # stand-alone bandwidth probe (measurement companion, not linked into the library)
-    probe = os.path.join(HERE, "bw_probe")
-    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
-                          "-packed-fp32-ops", os.path.join(CSRC, "bw_probe.hip"), "-o", probe + ".tmp"],
-                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed on bw_probe.hip:\n" + res.stdout)
-    os.replace(probe + ".tmp", probe)
     # a consumer of the C ABI without Python or PyTorch (run by the GPU tests)
     example = os.path.join(HERE, "abi_example")
     res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", *inc, os.path.join(CSRC, "abi_example.cpp"),

@@ -44,13 +44,14 @@ int env_int(const char* name, int dflt, int lo, int hi) {
 
 partition_params get_params(int64_t n_rows, int64_t n_cols, int64_t nnz) {
   partition_params p;
+  const int64_t slots = isp_wave_slots();  // 4,096 on an MI355X (256 compute units)
   // Upper limits = what the grouped kernels' per-wave LDS tables hold (block_cost + hub_t <= 768
   // entries, block_cost <= 256 rows, seg_len <= 768 entries).  The environment overrides exist for
   // tuning and for tests that want many small work items.
-  // Small matrices get smaller row blocks, about as many as the chip has wavefront slots (256 CUs x 16):
+  // Small matrices get smaller row blocks, about as many as the chip has wavefront slots (compute units x 16):
   // a wavefront's work is a chain of dependent memory round trips, and a short chain on every slot
   // finishes sooner than a long one on a few (4,096 rows x 9 entries: 16 -> 7 us per SpMM).
-  int64_t auto_cost = (nnz + n_rows + 4095) / 4096;
+  int64_t auto_cost = (nnz + n_rows + slots - 1) / slots;
   auto_cost = auto_cost < 16 ? 16 : (auto_cost > 256 ? 256 : auto_cost);
   p.block_cost = env_int("ISP_BLOCK_COST", (int)auto_cost, 16, 256);
   // ... and shorter hub segments, for the same reason and because the segments are the heavy items that the
@@ -62,7 +63,7 @@ partition_params get_params(int64_t n_rows, int64_t n_cols, int64_t nnz) {
   // band (2.4 M columns: 5.30 -> 5.19 ms per SpMM, the other kernels 1-3 %); with few columns a band's popular
   // rows fit an L2 anyway and the longer segments win (233 k columns: SDDMM 3.21 vs 3.32 ms).
   const int seg_cap = n_cols >= (1 << 19) ? 384 : 512;
-  int64_t auto_seg = (nnz + n_rows + 4095) / 4096 / 4;
+  int64_t auto_seg = (nnz + n_rows + slots - 1) / slots / 4;
   auto_seg = auto_seg < 80 ? 80 : (auto_seg > seg_cap ? seg_cap : auto_seg);
   const int auto_hub = 2 * auto_seg > 512 ? 512 : (int)(2 * auto_seg);
   p.hub_t = env_int("ISP_HUB_THRESHOLD", auto_hub, 8, 512);
@@ -75,6 +76,38 @@ partition_params get_params(int64_t n_rows, int64_t n_cols, int64_t nnz) {
   p.min_piece = env_int("ISP_MIN_PIECE", p.seg_len / 2 > mp_lo ? p.seg_len / 2 : mp_lo, mp_lo, 1 << 20);
   return p;
 }
+
+}  // namespace
+
+isp_tuning isp_read_tuning() {
+  isp_tuning t;
+  t.no_grouped = getenv("ISP_NO_GROUPED") != nullptr;
+  t.sddmm_one_pass = getenv("ISP_SDDMM_ONE_PASS") != nullptr;
+  const int lpg = env_int("ISP_SPMM_LPG", 0, 0, 64);
+  t.spmm_lpg = (lpg == 4 || lpg == 8 || lpg == 16 || lpg == 32 || lpg == 64) ? lpg : 0;
+  const int tile = env_int("ISP_SPMM_TILE", 0, 0, 256);
+  t.spmm_tile = (tile == 64 || tile == 128 || tile == 256) ? tile : 0;
+  return t;
+}
+
+int isp_wave_slots() {
+  constexpr int MAX_DEV = 64;
+  static int cached[MAX_DEV] = {};  // 0 = not asked yet (racing first calls store the same number)
+  constexpr int fallback = 256 * 16;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return fallback; }
+  if (dev >= 0 && dev < MAX_DEV && cached[dev]) return cached[dev];
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+    (void)hipGetLastError();
+    return fallback;
+  }
+  const int slots = cus * 16;  // 4 SIMDs per compute unit x the 4 waves per SIMD the kernels are built for
+  if (dev >= 0 && dev < MAX_DEV) cached[dev] = slots;
+  return slots;
+}
+
+namespace {
 
 __global__ void k_zero_counters(build_counters* c) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *c = build_counters{};
@@ -493,6 +526,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   isp_csr* A = new (std::nothrow) isp_csr();
   if (!A) return isp_fail(ISP_ENOMEM, "host allocation of the handle failed");
   A->device = device;
+  A->tune = isp_read_tuning();
   A->v.n_rows = n_rows; A->v.n_cols = n_cols; A->v.nnz = nnz;
   A->v.indptr = indptr; A->v.indices = indices; A->v.values = values;
   A->v.blk_row = blk_row; A->v.n_blocks = h.n_blocks;
@@ -503,6 +537,8 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->v.partials = (float*)(base + L.partials);
   A->v.inv_len = (const float*)(base + L.inv_len);
   A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false;
+  A->mean_values = nullptr; A->mean_values_valid = false; A->mean_values_used = false;
+  A->sel_flags = nullptr; A->inv_perm = nullptr; A->inv_perm_valid = false;
   isp_csr_info_t& I = A->info;
   I.n_rows = n_rows; I.n_cols = n_cols; I.nnz = nnz; I.max_degree = (int64_t)h.max_degree;
   for (int b = 0; b < 5; ++b) { I.bin_rows[b] = (int64_t)h.bin_rows[b]; I.bin_nnz[b] = (int64_t)h.bin_nnz[b]; }

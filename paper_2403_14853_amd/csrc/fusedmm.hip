@@ -5,7 +5,6 @@
 // The per-edge scores exist only in registers: each gathered row x_j is used for the dot product
 // and for the accumulation in the same pass, and the backward recomputes the scores instead of
 // reading them back.  The column sum of the backward runs over the rows of the cached transpose.
-#include <stdlib.h>
 #include "grouped_ops.h"
 
 namespace {
@@ -269,7 +268,7 @@ isp_status run_grouped_d(const isp_csr* A, const typename P::args& pa, int d, fl
 
 bool grouped_partition_ok(const isp_csr* A) {
   return A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + A->v.hub_t <= GS_MAX_ENT &&
-         A->v.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
+         A->v.seg_len <= GS_MAX_ENT && !A->tune.no_grouped;
 }
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }

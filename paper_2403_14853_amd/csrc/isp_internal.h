@@ -36,13 +36,29 @@ struct isp_view {
   const float* inv_len;    // n_rows: 1 / (stored entries of the row), 0 for an empty row
 };
 
+// Tuning and debugging overrides.  They come from the environment and are resolved ONCE, when a handle is
+// built (the cached transpose inherits its source's): the compute entry points read the handle, never the
+// environment.  include/isp.h lists the variables.
+struct isp_tuning {
+  bool no_grouped;      // ISP_NO_GROUPED: every op runs on the generic kernels
+  bool sddmm_one_pass;  // ISP_SDDMM_ONE_PASS: SDDMM never splits 128-column rows into two 64-column passes
+  int spmm_lpg;         // ISP_SPMM_LPG: lanes per group of the grouped SpMM (0 = chosen by shape)
+  int spmm_tile;        // ISP_SPMM_TILE: feature columns per launch of the grouped SpMM (0 = chosen by shape)
+};
+isp_tuning isp_read_tuning();
+// Wavefront slots of the current device at the occupancy the row-streaming kernels run at (compute units x 4
+// SIMDs x 4 waves); the device is asked once per process and device.
+int isp_wave_slots();
+
 struct isp_csr {
   isp_view v;
+  isp_tuning tune;
   const int32_t* perm;     // transposes only
   float* t_values_rw;      // transposes only: the values array (in the workspace), writable
   float* mean_values;      // transposes only: nnz floats of workspace the transposition no longer needs, for
                            // value / (length of the entry's source row), filled on first use
-  bool mean_values_valid;  // false until filled and after isp_csr_values_changed
+  bool mean_values_valid;  // false until filled
+  bool mean_values_used;   // a mean backward has run on this handle: isp_csr_values_changed refills the array
   uint8_t* sel_flags;      // transposes only: nnz bytes of the same spare workspace; the min / max backward
                            // marks there which entries its arg array names
   int32_t* inv_perm;       // transposes only, same spare workspace: inv_perm[perm[q]] = q, filled on first use

@@ -5,7 +5,6 @@
 // Same work items as SpMM.  The wave keeps U's row in registers, gathers V's rows with the 64
 // lanes spread over the feature dimension, and reduces each product across the wave.  Results
 // of up to 64 consecutive entries are collected one per lane and stored coalesced.
-#include <stdlib.h>
 #include "grouped_ops.h"
 
 namespace {
@@ -164,7 +163,7 @@ isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const
   const bool grouped_ok = d % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 && aligned(U, 16) &&
                           aligned(V, 16) && A->info.block_cost <= GS_MAX_ROWS &&
                           A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT &&
-                          !getenv("ISP_NO_GROUPED");
+                          !A->tune.no_grouped;
   if (grouped_ok) {
     // One pass covers a window of the feature columns; later passes add their partial dot products.
     //  - big graphs with many columns, rows of whole 64-float halves: 64-column passes, so that every L2 holds
@@ -174,7 +173,7 @@ isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const
     const bool big = av.nnz >= ((int64_t)8 << 20);
     int wp = d;
     if (big && av.n_cols >= (1 << 19) && d > ISP_WAVE && d % ISP_WAVE == 0 && ldu % 32 == 0 && ldv % 32 == 0 &&
-        !getenv("ISP_SDDMM_ONE_PASS"))
+        !A->tune.sddmm_one_pass)
       wp = ISP_WAVE;
     else if (big && d > 2 * ISP_WAVE) wp = 2 * ISP_WAVE;
     else if (d > ISP_PARTIAL_TILE) wp = ISP_PARTIAL_TILE;

@@ -2,7 +2,6 @@
 // 3.4, 3.5).  The backward dX = A^T dY is this same code run on the cached transpose's handle
 // (Section 3.3).  Gather-bound: per nonzero one 4*d-byte row of X is fetched and d FMAs are done,
 // so the kernels are built around coalesced row gathers, not around matrix cores.
-#include <stdlib.h>
 #include "group_stream.h"
 
 namespace {
@@ -258,7 +257,7 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
   // (a matrix without entries never reads X, which may then be absent: the generic path handles it)
   const bool grouped_ok = av.nnz > 0 && (vec == 4 || (a32 && mean_mode == 0)) && A->info.block_cost <= GS_MAX_ROWS &&
                           A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT &&
-                          !getenv("ISP_NO_GROUPED");
+                          !A->tune.no_grouped;
   *done = grouped_ok;
   if (!grouped_ok) return ISP_OK;
   if (vec < 4) {
@@ -286,7 +285,7 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
   // row win (dealt to alternating XCDs, each L2 then keeps half-rows of twice as many hot columns,
   // which outweighs staging the CSR arrays twice) provided both halves are whole 128-byte lines.  With
   // few columns (233 k measured) a column band's hot rows fit an L2 whole and one slice is faster.
-  // ISP_SPMM_LPG / ISP_SPMM_TILE override the choices for tuning.
+  // ISP_SPMM_LPG / ISP_SPMM_TILE (read when the handle was built) override the choices for tuning.
   const bool big = av.nnz >= (int64_t)8 << 20;
   const bool large = big && av.n_cols >= (1 << 19);
   int lpg = d <= 32 ? 8 : (d <= 64 ? 16 : 32);
@@ -295,12 +294,9 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
   const int tile_dflt = big ? 128 : ISP_PARTIAL_TILE;
   int tile = tile_dflt;
   if (large && d > 64 && d % 64 == 0 && ldx % 32 == 0) lpg = 16;  // (rows start on 128-byte lines)
-  if (const char* e = getenv("ISP_SPMM_LPG")) {
-    const int v = atoi(e);
-    if (v == 4 || v == 8 || v == 16 || v == 32 || v == 64) lpg = v;
-  }
+  if (A->tune.spmm_lpg) lpg = A->tune.spmm_lpg;
   isp_status st = ISP_OK;
-  if (const char* e = getenv("ISP_SPMM_TILE")) { const int v = atoi(e); if (v == 64 || v == 128 || v == 256) tile = v; }
+  if (A->tune.spmm_tile) tile = A->tune.spmm_tile;
   for (int k_base = 0; k_base < d && st == ISP_OK; k_base += tile) {
     const int w = (d - k_base < tile) ? d - k_base : tile;
     const int ns = (w + 4 * lpg - 1) / (4 * lpg);

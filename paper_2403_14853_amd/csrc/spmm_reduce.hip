@@ -10,7 +10,6 @@
 //   backward min/max : dX[j,k] = sum_{p in column j, arg[row(p),k] == p} a_p dY[row(p),k]
 // Both backward forms are row passes over the cached transpose (whose perm gives p), so no
 // floating-point atomics are needed and results are deterministic.
-#include <stdlib.h>
 #include "row_stream.h"
 #include "group_stream.h"
 
@@ -405,7 +404,7 @@ isp_status fwd_all(const isp_csr* A, const float* X, int64_t ldx, int d, float* 
                      ((uint64_t)av.n_cols * (uint64_t)ldx + (uint64_t)d) * 4u < ((uint64_t)1 << 32);
     const bool ok = av.nnz > 0 && a32 && d % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(X, 16) &&
                     aligned(Y, 16) && aligned(arg, 16) && A->info.block_cost <= GS_MAX_ROWS &&
-                    A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT && !getenv("ISP_NO_GROUPED");
+                    A->info.block_cost + av.hub_t <= GS_MAX_ENT && av.seg_len <= GS_MAX_ENT && !A->tune.no_grouped;
     if (ok) {
       // 128 columns per launch (a hub partial row holds 128 values and 128 positions), one slice: the two
       // 64-column slices that pay for the sum on large graphs cost more here than they save, the loop doing

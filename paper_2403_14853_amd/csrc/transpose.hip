@@ -337,11 +337,13 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   isp_status st = isp_build_handle(n_cols, n_rows, nnz, t_indptr, t_indices, t_values, base + L.part,
                                    ws_bytes - L.part, false, s, &At);
   if (st != ISP_OK) return st;
+  At->tune = A->tune;  // (resolved when A was built)
   At->perm = perm;
   At->t_values_rw = t_values;
   // the record arrays of the sort are free from here on; one of them later holds the mean reduction's values
   At->mean_values = (float*)(base + L.set[0][1]);
   At->mean_values_valid = false;
+  At->mean_values_used = false;
   At->sel_flags = (uint8_t*)(base + L.set[1][1]);
   At->inv_perm = (int32_t*)(base + L.set[0][2]);
   At->inv_perm_valid = false;
@@ -375,6 +377,7 @@ isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** ou
     ISP_LAUNCH_CHECK();
     At->mean_values_valid = !stream_is_capturing(s);
   }
+  At->mean_values_used = true;
   *out = At->mean_values;
   return ISP_OK;
 }
@@ -391,11 +394,19 @@ isp_status isp_transpose_inverse_perm(isp_csr* A, hipStream_t s, const int32_t**
   return ISP_OK;
 }
 
+// Everything derived from A's values is brought up to date on s itself, in stream order: a call recorded into a
+// HIP graph refreshes on every replay, and a graph that was captured while the mean reduction's values were
+// valid (and therefore holds no pass that computes them) reads refreshed ones after an eager call.
 isp_status isp_transpose_refresh_values(isp_csr* A, hipStream_t s) {
   isp_csr* At = A->At;
-  if (At) At->mean_values_valid = false;
   if (!At || !A->v.values || !At->t_values_rw || A->v.nnz == 0) return ISP_OK;
-  k_gather_values<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(At->perm, A->v.values, A->v.nnz, At->t_values_rw);
+  const unsigned grid = (unsigned)((A->v.nnz + 255) / 256);
+  k_gather_values<<<grid, 256, 0, s>>>(At->perm, A->v.values, A->v.nnz, At->t_values_rw);
   ISP_LAUNCH_CHECK();
+  if (At->mean_values_used) {  // a mean backward has run (or was captured): its values follow at once
+    k_mean_values<<<grid, 256, 0, s>>>(At->v.indices, At->v.values, A->v.inv_len, A->v.nnz, At->mean_values);
+    ISP_LAUNCH_CHECK();
+    // (valid stays as it is: during a capture the refill runs with the replays, like the fill itself)
+  }
   return ISP_OK;
 }
