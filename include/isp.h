@@ -153,6 +153,22 @@ isp_status isp_spmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, 
                     void* stream);
 
 /*
+ * isp_spmm for callers that cannot allocate device memory or hand over scratch: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results; the difference is where the partial sums of the hub-row segments live.  isp_spmm keeps them in the
+ * workspace given to isp_csr_build; this call keeps them in a fixed 32 MiB array inside the library's device
+ * image (one per GPU, present from the library's first use on that GPU until the process ends) and makes no
+ * allocation of any kind.  Limits and rules:
+ *   - a handle with more than 32,768 hub-row segments (isp_csr_info: n_segments) is rejected with
+ *     ISP_EUNSUPPORTED and nothing is launched;
+ *   - the array is shared by every handle and every call on that GPU: calls of this function that overlap
+ *     on one GPU (different streams or threads) race, whichever handles they use; calls on one stream are safe;
+ *   - nothing in the array needs clearing between calls (each launch writes every partial row it later reads).
+ */
+isp_status isp_spmm_static_scratch(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, float* Y,
+                                   int64_t ldy, void* stream);
+
+/*
  * SDDMM (Section 1): out[p] = <U[i, 0:d], V[indices[p], 0:d]> for every stored entry p of every
  * row i, in A's CSR order; with ISP_SCALE_BY_A multiplied by values[p].  U has n_rows rows, V has
  * n_cols rows, out has nnz elements.  With U = dY and V = X this is dA of Y = A X.

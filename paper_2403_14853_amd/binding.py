@@ -14,7 +14,7 @@ _lib = None
 
 EXPORTED_SYMBOLS = [
     "isp_csr_build_workspace", "isp_csr_build", "isp_csr_transpose_workspace", "isp_csr_transpose_cached",
-    "isp_csr_values_changed", "isp_csr_export", "isp_csr_info", "isp_spmm", "isp_sddmm", "isp_fusedmm", "isp_fusedmm_backward",
+    "isp_csr_values_changed", "isp_csr_export", "isp_csr_info", "isp_spmm", "isp_spmm_static_scratch", "isp_sddmm", "isp_fusedmm", "isp_fusedmm_backward",
     "isp_spmm_reduce", "isp_spmm_reduce_backward", "isp_csr_destroy", "isp_last_error", "isp_version",
 ]
 
@@ -63,6 +63,7 @@ def load_library():
     lib.isp_csr_values_changed.argtypes = [vp, vp]
     lib.isp_csr_info.argtypes = [vp, P(CsrInfo)]
     lib.isp_spmm.argtypes = [vp, vp, i64, i32, vp, i64, vp]
+    lib.isp_spmm_static_scratch.argtypes = [vp, vp, i64, i32, vp, i64, vp]
     lib.isp_sddmm.argtypes = [vp, vp, i64, vp, i64, i32, u32, vp, vp]
     lib.isp_fusedmm.argtypes = [vp, vp, i64, i32, ctypes.c_int, vp, i64, vp]
     lib.isp_fusedmm_backward.argtypes = [vp, vp, i64, vp, i64, i32, ctypes.c_int, vp, i64, vp]
@@ -254,6 +255,14 @@ def spmm(A: CSR, X, Y, *, stream=None):
     d = X.shape[1]
     assert X.shape[0] == A.n_cols and Y.shape == (A.n_rows, d)
     _check(load_library().isp_spmm(A._h, _dptr(X), _ld(X), d, _dptr(Y), _ld(Y), _stream(stream)))
+    return Y
+
+
+def spmm_static_scratch(A: CSR, X, Y, *, stream=None):
+    """isp_spmm_static_scratch: isp_spmm with the hub-row partial sums in the library's static device array."""
+    d = X.shape[1]
+    assert X.shape[0] == A.n_cols and Y.shape == (A.n_rows, d)
+    _check(load_library().isp_spmm_static_scratch(A._h, _dptr(X), _ld(X), d, _dptr(Y), _ld(Y), _stream(stream)))
     return Y
 
 

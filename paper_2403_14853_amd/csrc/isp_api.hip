@@ -52,14 +52,25 @@ isp_status isp_csr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int6
                           !(flags & ISP_TRUSTED), (hipStream_t)stream, out);
 }
 
+}  // extern "C"
+
 // The handle's arrays live on the device that was current when it was built.
-static isp_status check_device(const isp_csr_t* A) {
+isp_status isp_check_device(const isp_csr* A) {
   int dev = -1;
   ISP_HIP(hipGetDevice(&dev));
   if (dev != A->device)
     return isp_fail(ISP_EINVAL, "the handle was built on device %d, the current device is %d", A->device, dev);
   return ISP_OK;
 }
+
+isp_status isp_check_dense(const void* p, int64_t ld, int32_t d, int64_t rows, const char* name) {
+  if (d <= 0) return isp_fail(ISP_EINVAL, "d must be positive");
+  if (rows > 0 && !p) return isp_fail(ISP_EINVAL, "%s is NULL", name);
+  if (ld < d) return isp_fail(ISP_EINVAL, "leading dimension of %s (%lld) is smaller than d (%d)", name, (long long)ld, d);
+  return ISP_OK;
+}
+
+extern "C" {
 
 isp_status isp_csr_transpose_workspace(const isp_csr_t* A, size_t* bytes) {
   if (!A || !bytes) return isp_fail(ISP_EINVAL, "NULL argument");
@@ -77,7 +88,7 @@ isp_status isp_csr_transpose_cached(isp_csr_t* A, void* workspace, size_t worksp
     return ISP_OK;
   }
   if (was_cached) *was_cached = 0;
-  isp_status st = check_device(A);
+  isp_status st = isp_check_device(A);
   if (st != ISP_OK) return st;
   st = isp_transpose_build(A, workspace, workspace_bytes, (hipStream_t)stream);
   if (st != ISP_OK) return st;
@@ -88,7 +99,7 @@ isp_status isp_csr_transpose_cached(isp_csr_t* A, void* workspace, size_t worksp
 isp_status isp_csr_values_changed(isp_csr_t* A, void* stream) {
   if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");
   if (A->is_transpose) return isp_fail(ISP_EINVAL, "pass the source handle, not its transpose");
-  isp_status st = check_device(A);
+  isp_status st = isp_check_device(A);
   if (st != ISP_OK) return st;
   return isp_transpose_refresh_values(A, (hipStream_t)stream);
 }
@@ -109,19 +120,12 @@ isp_status isp_csr_info(const isp_csr_t* A, isp_csr_info_t* info) {
   return ISP_OK;
 }
 
-static isp_status check_dense(const void* p, int64_t ld, int32_t d, int64_t rows, const char* name) {
-  if (d <= 0) return isp_fail(ISP_EINVAL, "d must be positive");
-  if (rows > 0 && !p) return isp_fail(ISP_EINVAL, "%s is NULL", name);
-  if (ld < d) return isp_fail(ISP_EINVAL, "leading dimension of %s (%lld) is smaller than d (%d)", name, (long long)ld, d);
-  return ISP_OK;
-}
-
 isp_status isp_spmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy, void* stream) {
   if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");
   isp_status st;
-  if ((st = check_device(A)) != ISP_OK) return st;
-  if ((st = check_dense(X, ldx, d, A->v.nnz > 0 ? A->v.n_cols : 0, "X")) != ISP_OK) return st;
-  if ((st = check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
+  if ((st = isp_check_device(A)) != ISP_OK) return st;
+  if ((st = isp_check_dense(X, ldx, d, A->v.nnz > 0 ? A->v.n_cols : 0, "X")) != ISP_OK) return st;
+  if ((st = isp_check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
   return isp_spmm_launch(A, X, ldx, d, Y, ldy, (hipStream_t)stream);
 }
 
@@ -130,10 +134,10 @@ isp_status isp_sddmm(const isp_csr_t* A, const float* U, int64_t ldu, const floa
   if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");
   if (flags & ~ISP_SCALE_BY_A) return isp_fail(ISP_EUNSUPPORTED, "unknown flag bits 0x%x", flags & ~ISP_SCALE_BY_A);
   isp_status st;
-  if ((st = check_device(A)) != ISP_OK) return st;
+  if ((st = isp_check_device(A)) != ISP_OK) return st;
   const int64_t live = A->v.nnz > 0 ? 1 : 0;
-  if ((st = check_dense(U, ldu, d, live * A->v.n_rows, "U")) != ISP_OK) return st;
-  if ((st = check_dense(V, ldv, d, live * A->v.n_cols, "V")) != ISP_OK) return st;
+  if ((st = isp_check_dense(U, ldu, d, live * A->v.n_rows, "U")) != ISP_OK) return st;
+  if ((st = isp_check_dense(V, ldv, d, live * A->v.n_cols, "V")) != ISP_OK) return st;
   if (A->v.nnz > 0 && !out) return isp_fail(ISP_EINVAL, "out is NULL");
   return isp_sddmm_launch(A, U, ldu, V, ldv, d, (flags & ISP_SCALE_BY_A) != 0, out, (hipStream_t)stream);
 }
@@ -144,15 +148,15 @@ static isp_status check_fused(const isp_csr_t* A, int32_t d, int op) {
     return isp_fail(ISP_EUNSUPPORTED, "unknown edge op %d", op);
   if (A->v.n_rows != A->v.n_cols) return isp_fail(ISP_EINVAL, "FusedMM needs a square matrix");
   if (d > 4 * ISP_PARTIAL_TILE) return isp_fail(ISP_EUNSUPPORTED, "FusedMM supports d <= %d", 4 * ISP_PARTIAL_TILE);
-  return check_device(A);
+  return isp_check_device(A);
 }
 
 isp_status isp_fusedmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int op, float* Y, int64_t ldy,
                        void* stream) {
   isp_status st;
   if ((st = check_fused(A, d, op)) != ISP_OK) return st;
-  if ((st = check_dense(X, ldx, d, A->v.n_rows, "X")) != ISP_OK) return st;
-  if ((st = check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
+  if ((st = isp_check_dense(X, ldx, d, A->v.n_rows, "X")) != ISP_OK) return st;
+  if ((st = isp_check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
   return isp_fusedmm_launch(A, X, ldx, d, op, Y, ldy, (hipStream_t)stream);
 }
 
@@ -161,9 +165,9 @@ isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const
   isp_status st;
   if ((st = check_fused(A, d, op)) != ISP_OK) return st;
   if (!A->At) return isp_fail(ISP_EINVAL, "call isp_csr_transpose_cached on the handle first");
-  if ((st = check_dense(X, ldx, d, A->v.n_rows, "X")) != ISP_OK) return st;
-  if ((st = check_dense(dY, lddy, d, A->v.n_rows, "dY")) != ISP_OK) return st;
-  if ((st = check_dense(dX, lddx, d, A->v.n_rows, "dX")) != ISP_OK) return st;
+  if ((st = isp_check_dense(X, ldx, d, A->v.n_rows, "X")) != ISP_OK) return st;
+  if ((st = isp_check_dense(dY, lddy, d, A->v.n_rows, "dY")) != ISP_OK) return st;
+  if ((st = isp_check_dense(dX, lddx, d, A->v.n_rows, "dX")) != ISP_OK) return st;
   return isp_fusedmm_bwd_launch(A, X, ldx, dY, lddy, d, op, dX, lddx, (hipStream_t)stream);
 }
 
@@ -174,9 +178,9 @@ isp_status isp_spmm_reduce(const isp_csr_t* A, const float* X, int64_t ldx, int3
   if (reduce != ISP_REDUCE_MEAN && reduce != ISP_REDUCE_MIN && reduce != ISP_REDUCE_MAX)
     return isp_fail(ISP_EUNSUPPORTED, "unknown reduction %d", reduce);
   isp_status st;
-  if ((st = check_device(A)) != ISP_OK) return st;
-  if ((st = check_dense(X, ldx, d, A->v.nnz > 0 ? A->v.n_cols : 0, "X")) != ISP_OK) return st;
-  if ((st = check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
+  if ((st = isp_check_device(A)) != ISP_OK) return st;
+  if ((st = isp_check_dense(X, ldx, d, A->v.nnz > 0 ? A->v.n_cols : 0, "X")) != ISP_OK) return st;
+  if ((st = isp_check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
   if (reduce != ISP_REDUCE_MEAN && A->v.n_rows > 0 && !arg) return isp_fail(ISP_EINVAL, "arg is NULL");
   return isp_spmm_reduce_launch(A, X, ldx, d, reduce, Y, ldy, arg, (hipStream_t)stream);
 }
@@ -190,9 +194,9 @@ isp_status isp_spmm_reduce_backward(isp_csr_t* A, const float* dY, int64_t lddy,
   if (reduce != ISP_REDUCE_MEAN && reduce != ISP_REDUCE_MIN && reduce != ISP_REDUCE_MAX)
     return isp_fail(ISP_EUNSUPPORTED, "unknown reduction %d", reduce);
   isp_status st;
-  if ((st = check_device(A)) != ISP_OK) return st;
-  if ((st = check_dense(dY, lddy, d, A->v.nnz > 0 ? A->v.n_rows : 0, "dY")) != ISP_OK) return st;
-  if ((st = check_dense(dX, lddx, d, A->v.n_cols, "dX")) != ISP_OK) return st;
+  if ((st = isp_check_device(A)) != ISP_OK) return st;
+  if ((st = isp_check_dense(dY, lddy, d, A->v.nnz > 0 ? A->v.n_rows : 0, "dY")) != ISP_OK) return st;
+  if ((st = isp_check_dense(dX, lddx, d, A->v.n_cols, "dX")) != ISP_OK) return st;
   if (reduce != ISP_REDUCE_MEAN && A->v.nnz > 0 && !arg) return isp_fail(ISP_EINVAL, "arg is NULL");
   return isp_spmm_reduce_bwd_launch(A, dY, lddy, d, reduce, arg, dX, lddx, (hipStream_t)stream);
 }

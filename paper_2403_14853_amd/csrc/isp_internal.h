@@ -81,6 +81,10 @@ isp_status isp_fail(isp_status st, const char* fmt, ...);
 
 static inline size_t isp_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// ---- argument checks shared by the entry points (isp_api.hip) -----------------------------------
+isp_status isp_check_device(const isp_csr* A);  // the handle's device must be the current one
+isp_status isp_check_dense(const void* p, int64_t ld, int32_t d, int64_t rows, const char* name);
+
 // ---- device scans (scan.hip) -----------------------------------------------------------------
 // Exclusive prefix sums; out has n + 1 entries (out[n] = total).  tmp must hold
 // isp_scan_tmp_bytes(n) bytes.  in and out may not alias.
