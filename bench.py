@@ -54,8 +54,8 @@ def main():
                     help="instead of the benchmark line: per-op time when a 1 GiB copy has swept L2 and the "
                          "Infinity Cache before every op (the small workloads otherwise run cache-warm)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run three plain device copies of X (known size) before the timed region, "
-                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+                    help="(kept for older command lines: plain device copies of X, the known-size kernel that "
+                         "scales rocprofv3 FETCH_SIZE / WRITE_SIZE readings, now always run before the timed region)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -172,9 +172,12 @@ def main():
                           "warm_ms": {("%d:%s" % (i, o)): round(float(np.median(warm[i])), 4) for i, o in enumerate(ops)},
                           "flushed_ms": {("%d:%s" % (i, o)): round(float(np.median(cold[i])), 4) for i, o in enumerate(ops)}}))
         return
-    if args.copy_calibration:
-        for _ in range(3):
-            Y.copy_(X)  # plain copy kernel: reads 4*n*d bytes, writes 4*n*d bytes
+    # plain device copy of X (reads 4 n d bytes, writes 4 n d bytes): the streaming ceiling of this machine, and the
+    # known-size kernel the rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by
+    for _ in range(2):
+        Y.copy_(X)
+    copy_ms = _time_ms(lambda: Y.copy_(X), 5 if args.copy_calibration or n * d > 1 << 20 else 50)
+    copy_gbps = 2.0 * 4.0 * n * d / (copy_ms * 1e-3) / 1e9
     torch.cuda.synchronize()
     # per-op HIP events on the launch stream, recorded inside the timed region
     evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
@@ -203,17 +206,29 @@ def main():
     alg_bytes = csr_bytes + 2.0 * 4.0 * n * d
     gather_bytes = csr_bytes + 4.0 * d * nnz + 4.0 * n * d  # every entry fetches its own X row
     achieved = alg_bytes / (dom_ms * 1e-3) / 1e9
+    dom_kernel = {"fusedmm": "k_fused_grouped<g_fwd>", "spmm": "k_spmm_grouped"}.get(dom, dom)
     roofline = {
-        "bound": "hbm", "kernel": {"fusedmm": "k_fused_grouped<g_fwd>", "spmm": "k_spmm_grouped"}.get(dom, dom),
+        "bound": "hbm", "kernel": dom_kernel,
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None if args.no_relabel else TRAFFIC_BYTES.get((args.config, args.shrink)),
+        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
         "algorithmic_bytes": alg_bytes, "launch_ms": round(dom_ms, 4),
         "gather_model_bytes": gather_bytes,
         "gather_model_GBps": round(gather_bytes / (dom_ms * 1e-3) / 1e9, 1),
+        # what a plain device copy of X reaches on this machine in this run (read + written bytes over time)
+        "copy_ceiling_GBps": round(copy_gbps, 1),
+        "achieved_frac_of_copy_ceiling": round(achieved / copy_gbps, 4),
     }
-    if roofline["traffic"]:  # counter bytes of the stored profile over this run's launch time
-        roofline["traffic_GBps"] = round(roofline["traffic"] / (dom_ms * 1e-3) / 1e9, 1)
+    rec = None if (args.no_relabel or args.shrink != 1 or args.ops) else counter_record(w.name, dom_kernel)
+    if rec:  # counter bytes of the stored profile record over this run's launch time
+        roofline["traffic"] = rec["bytes"]
+        roofline["traffic_commit"] = rec["commit"]
+        roofline["traffic_source"] = "profiles/counter_records.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated)"
+        roofline["traffic_over_algorithmic"] = round(rec["bytes"] / alg_bytes, 2)
+        roofline["traffic_GBps"] = round(rec["bytes"] / (dom_ms * 1e-3) / 1e9, 1)
         roofline["traffic_frac_of_peak"] = round(roofline["traffic_GBps"] / HBM_PEAK_GBPS, 4)
+        roofline["traffic_frac_of_copy_ceiling"] = round(roofline["traffic_GBps"] / copy_gbps, 4)
+        if rec["tcc_hit"] + rec["tcc_miss"] > 0:
+            roofline["l2_hit_rate"] = round(rec["tcc_hit"] / (rec["tcc_hit"] + rec["tcc_miss"]), 4)
 
     cpu = None
     if not args.no_cpu_baseline and not args.ops:  # the oracle leg checks the workload's own dominant output
@@ -239,11 +254,27 @@ def main():
     print(json.dumps(out))
 
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); keyed by (config, shrink).  None = not measured for that workload.
-TRAFFIC_BYTES = {
-    (3, 1): 35.42e9,  # profiles/spmm_c3-rmat2.4m-d128.txt: 2 x FETCH_SIZE (calibrated) + WRITE_SIZE of k_spmm_grouped
-}
+def counter_record(workload, kernel):
+    """The rocprofv3 counter readings kept for this workload's dominant kernel in profiles/counter_records.txt
+    (per launch: FETCH_SIZE and WRITE_SIZE in KiB, TCC_HIT_sum, TCC_MISS_sum, the average duration of the run
+    that was counted, and the commit whose kernels were measured), or None.  The calibration factors that
+    turn counter KiB into bytes are lines of the same file."""
+    path = os.path.join(ROOT, "profiles", "counter_records.txt")
+    if not os.path.exists(path):
+        return None
+    factor = {"fetch_factor": 1.0, "write_factor": 1.0}
+    rec = None
+    for line in open(path):
+        f = line.split("#")[0].split()
+        if len(f) == 2 and f[0] in factor:
+            factor[f[0]] = float(f[1])
+        elif len(f) == 8 and f[0] == workload and f[1] == kernel:
+            rec = dict(fetch_kib=float(f[2]), write_kib=float(f[3]), tcc_hit=float(f[4]), tcc_miss=float(f[5]),
+                       avg_us=float(f[6]), commit=f[7])
+    if rec is None:
+        return None
+    rec["bytes"] = (factor["fetch_factor"] * rec["fetch_kib"] + factor["write_factor"] * rec["write_kib"]) * 1024.0
+    return rec
 
 
 def _time_ms(fn, reps):
@@ -259,48 +290,77 @@ def _time_ms(fn, reps):
 
 
 def epoch_ablation(isp, w, indptr, indices, values, X, dY, epochs):
-    """The paper's caching claim at kernel level (Section 3.3): per-epoch time of forward + backward
-    SpMM when the transpose is built once and cached vs rebuilt in every epoch."""
+    """The paper's caching claim at kernel level (Section 3.3): per-epoch time of forward + backward SpMM when
+    the transpose is built once and cached vs built again in every epoch.  Both legs run on handles that were
+    built beforehand with workspaces that were allocated (and touched) beforehand, so the only work that
+    differs between them is the transposition itself: the rebuilt leg uses one fresh handle per epoch, whose
+    first isp_csr_transpose_cached call is a cache miss."""
     import torch
     Y, dX = torch.empty_like(X), torch.empty_like(X)
-    A = isp.csr_build(indptr, indices, values)
+    n, nnz = w.n, w.nnz
+
+    def fresh():
+        ws_a = torch.zeros(isp.csr_build_workspace(n, n, nnz), dtype=torch.uint8, device="cuda")
+        H = isp.csr_build(indptr, indices, values, workspace=ws_a)
+        ws_t = torch.zeros(isp.csr_transpose_workspace(H), dtype=torch.uint8, device="cuda")
+        return H, ws_t
+
+    A, ws_t = fresh()
 
     def epoch_cached():
         isp.spmm(A, X, Y)
-        At, _ = isp.csr_transpose_cached(A)  # built in the first epoch only
+        At, _ = isp.csr_transpose_cached(A, workspace=ws_t)  # built in the first epoch only
         isp.spmm(At, dY, dX)
 
     first = _time_ms(epoch_cached, 1)
+    epoch_cached()
     cached = _time_ms(epoch_cached, epochs)
 
-    def epoch_uncached():
-        B = isp.csr_build(indptr, indices, values)  # fresh handle: nothing cached
+    handles = [fresh() for _ in range(epochs + 1)]
+    torch.cuda.synchronize()
+    it = iter(handles)
+
+    def epoch_rebuilt():
+        B, ws = next(it)
         isp.spmm(B, X, Y)
-        Bt, _ = isp.csr_transpose_cached(B)
+        Bt, was = isp.csr_transpose_cached(B, workspace=ws)  # a cache miss: the transpose is built here
+        assert not was
         isp.spmm(Bt, dY, dX)
-        torch.cuda.synchronize()
+
+    epoch_rebuilt()  # (warm-up on the first spare handle)
+    rebuilt = _time_ms(epoch_rebuilt, epochs)
+    transpose_ms = rebuilt - cached
+    bwd_ms = _time_ms(lambda: isp.spmm(isp.csr_transpose_cached(A)[0], dY, dX), max(3, epochs))
+    for B, _ in handles:
         B.destroy()
-
-    epoch_uncached()
-    uncached = _time_ms(epoch_uncached, epochs)
-    return {"what": "epoch ablation: SpMM forward + backward per epoch", "workload": w.name, "epochs": epochs,
+    return {"what": "epoch ablation: SpMM forward + backward per epoch; handles and workspaces prepared beforehand, "
+                    "only the transposition differs", "workload": w.name, "epochs": epochs, "d": w.d,
             "first_epoch_ms_with_cache": round(first, 3), "epoch_ms_cached_transpose": round(cached, 3),
-            "epoch_ms_transpose_rebuilt": round(uncached, 3), "speedup_from_cache": round(uncached / cached, 3)}
+            "epoch_ms_transpose_rebuilt": round(rebuilt, 3), "speedup_from_cache": round(rebuilt / cached, 3),
+            "transpose_ms": round(transpose_ms, 3), "backward_spmm_ms": round(bwd_ms, 3),
+            # the cache has paid for itself once the epochs' savings exceed nothing at all: the first epoch costs
+            # the same either way, every later epoch saves one transposition
+            "transpose_cost_in_backward_spmms": round(transpose_ms / bwd_ms, 2), "break_even_epoch": 2}
 
 
-def sweep_d(isp, w, A):
-    """SpMM forward over feature widths (the GPU counterpart of the paper's tuning graph, Section 3.2)."""
+SWEEP_WIDTHS = (8, 16, 30, 32, 64, 100, 128, 256, 512, 1024)
+
+
+def sweep_d(isp, w, A, widths=SWEEP_WIDTHS):
+    """SpMM forward over feature widths (the GPU counterpart of the paper's tuning graph, Section 3.2),
+    including widths that are not multiples of 4 (the narrow-lane kernels) and d = 8."""
     import torch
     out = []
-    for d in (8, 16, 32, 64, 100, 128, 256, 512, 1024):
+    for d in widths:
         X = torch.randn(w.n, d, device="cuda")
         Y = torch.empty_like(X)
         isp.spmm(A, X, Y)
-        ms = _time_ms(lambda: isp.spmm(A, X, Y), 5)
+        ms = _time_ms(lambda: isp.spmm(A, X, Y), 5 if w.nnz > 1 << 22 else 50)
         out.append({"d": d, "ms": round(ms, 4), "gflops": round(2.0 * w.nnz * d / ms / 1e6, 1),
-                    "gather_GBps": round(w.nnz * (8.0 + 4.0 * d) / ms / 1e6, 1)})
+                    "requested_GBps": round(w.nnz * (8.0 + 4.0 * d) / ms / 1e6, 1)})
         del X, Y
-    return {"what": "SpMM forward vs feature width", "workload": w.name, "nnz": w.nnz, "sweep": out}
+    return {"what": "SpMM forward vs feature width; requested_GBps = nnz * (8 + 4 d) bytes over time (every entry "
+                    "fetching its own row)", "workload": w.name, "nnz": w.nnz, "sweep": out}
 
 
 def gcn_step(w, indptr, indices, values, X):

@@ -36,3 +36,41 @@ def test_bench_refuses_more_than_one_gpu(repo_root):
     res = subprocess.run([sys.executable, os.path.join(repo_root, "bench.py"), "--gpus", "2"],
                          stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120, cwd=repo_root)
     assert res.returncode != 0 and "ONE GPU" in res.stderr
+
+
+def _bench_json(repo_root, *args):
+    res = subprocess.run([sys.executable, os.path.join(repo_root, "bench.py"), *args],
+                         stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=300, cwd=repo_root)
+    assert res.returncode == 0, res.stderr[-2000:]
+    lines = [l for l in res.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1, res.stdout
+    return json.loads(lines[0])
+
+
+def test_epoch_ablation_mode_on_a_shrunk_graph(repo_root):
+    """Section 3.3's claim at kernel level: the mode runs, only the transposition differs between its legs, and
+    rebuilding the transpose every epoch costs more than looking it up."""
+    j = _bench_json(repo_root, "--config", "1", "--shrink", "4", "--epoch-ablation", "4")
+    for key in ("epoch_ms_cached_transpose", "epoch_ms_transpose_rebuilt", "transpose_ms", "backward_spmm_ms",
+                "transpose_cost_in_backward_spmms", "speedup_from_cache", "first_epoch_ms_with_cache"):
+        assert key in j and j[key] > 0, key
+    assert j["epochs"] == 4 and j["epoch_ms_transpose_rebuilt"] > j["epoch_ms_cached_transpose"]
+
+
+def test_width_sweep_mode_on_a_shrunk_graph(repo_root):
+    """The GPU counterpart of the tuning graph (Section 3.2): every width of the sweep runs, including d = 8
+    and widths that are not multiples of 4."""
+    j = _bench_json(repo_root, "--config", "1", "--shrink", "4", "--sweep-d")
+    widths = [p["d"] for p in j["sweep"]]
+    assert widths == [8, 16, 30, 32, 64, 100, 128, 256, 512, 1024]
+    assert all(p["ms"] > 0 and p["gflops"] > 0 and p["requested_GBps"] > 0 for p in j["sweep"])
+
+
+def test_traffic_comes_from_the_tracked_counter_records(repo_root):
+    """roofline.traffic is read from profiles/counter_records.txt (no byte constant in bench.py) and says which
+    commit it was measured on."""
+    sys.path.insert(0, repo_root)
+    import bench
+    rec = bench.counter_record("c3-rmat2.4m-d128", "k_spmm_grouped")
+    assert rec and rec["bytes"] > 0 and rec["commit"]
+    assert "35.42e9" not in open(os.path.join(repo_root, "bench.py")).read()

@@ -119,10 +119,28 @@ def test_all_ops_small_graph_many_items(small_partition, d):
     _run_all_ops(w.indptr, w.indices, w.values, w.n, w.n, d, seed=d)
 
 
-@pytest.mark.parametrize("d", [300, 513])
+@pytest.mark.parametrize("d", [300, 513, 1024])
 def test_wide_features_tile_over_columns(small_partition, d):
     w = graphgen.make_config(1, shrink=256)
     _run_all_ops(w.indptr, w.indices, w.values, w.n, w.n, d, seed=d, fused=False)
+
+
+@pytest.mark.parametrize("d", [8, 16, 30, 100, 512, 1024])
+def test_sweep_widths_default_partition(d):
+    """The widths of the feature-width sweep (bench.py --sweep-d) that the cases above do not cover, on the
+    partition the library chooses by itself: SpMM forward and backward against the oracle, every element."""
+    w = graphgen.make_config(1, shrink=8)
+    rng = np.random.default_rng(d)
+    X = rng.standard_normal((w.n, d)).astype(np.float32)
+    A = build(w.indptr, w.indices, w.values)
+    Y = torch.full((w.n, d), float("nan"), device="cuda")
+    isp.spmm(A, dev(X), Y)
+    assert_close(Y, *oracle.spmm(w.indptr, w.indices, w.values, X), "spmm d=%d" % d)
+    At, _ = isp.csr_transpose_cached(A)
+    ti, tj, _, tv = oracle.transpose(w.n, w.n, w.indptr, w.indices, w.values)
+    isp.spmm(At, dev(X), Y)
+    assert_close(Y, *oracle.spmm(ti, tj, tv, X), "spmm backward d=%d" % d)
+    A.destroy()
 
 
 @pytest.mark.parametrize("d", [260, 512, 516, 1024])
