@@ -84,6 +84,12 @@ typedef struct {
   int32_t n_segments;     /* wavefront work items made of hub-row segments          */
   int32_t is_transpose;   /* 1 for a handle returned by isp_csr_transpose_cached    */
   int32_t has_cached_transpose;
+  /* the packed layout the tuned SpMM runs on (large matrices with many columns; all 0 without it): rows
+     longer than spmm_mid_threshold are cut into column-band pieces that share work items                 */
+  int32_t spmm_mid_threshold;
+  int32_t spmm_cut_rows;
+  int32_t spmm_pieces;
+  int32_t spmm_row_blocks; /* work items of that layout (whole short rows, or several pieces)              */
 } isp_csr_info_t;
 
 /* Bytes of device workspace isp_csr_build needs for a matrix of this shape (upper bound). */
@@ -94,7 +100,11 @@ isp_status isp_csr_build_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz, 
  * degree; short rows are grouped into contiguous row blocks of about equal (nnz + rows); hub rows
  * (degree > hub threshold) are cut into segments of bounded length, at column-band boundaries first,
  * which are scheduled in column order (Section 1(b): balanced scheduling; Section 3.5: CSR operand).
- * Integer work only.  Rows with ascending columns schedule best; any order is accepted.
+ * For large matrices with many columns (>= 8 Mi entries, >= 512 Ki columns) the tuned SpMM also gets a packed
+ * layout of its own: rows longer than 256 entries are cut into column-band pieces of 64 entries or more, and
+ * the pieces, scheduled in column order, share work items with each other; that layout keeps a reordered copy
+ * of the index and value arrays in the workspace (isp_csr_values_changed refreshes the values).
+ * Integer work and copies only.  Rows with ascending columns schedule best; any order is accepted.
  *   indptr/indices/values: borrowed device arrays (values may be NULL).
  *   workspace: device memory, 256-byte aligned, >= isp_csr_build_workspace() bytes; borrowed
  *              until isp_csr_destroy.
@@ -159,7 +169,8 @@ isp_status isp_spmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, 
  * workspace given to isp_csr_build; this call keeps them in a fixed 32 MiB array inside the library's device
  * image (one per GPU, present from the library's first use on that GPU until the process ends) and makes no
  * allocation of any kind.  Limits and rules:
- *   - a handle with more than 32,768 hub-row segments (isp_csr_info: n_segments) is rejected with
+ *   - a handle that needs more than 32,768 partial rows - one per hub-row segment, or one per row piece where
+ *     the handle has the packed SpMM layout (isp_csr_info: n_segments, spmm_pieces) - is rejected with
  *     ISP_EUNSUPPORTED and nothing is launched;
  *   - the array is shared by every handle and every call on that GPU: calls of this function that overlap
  *     on one GPU (different streams or threads) race, whichever handles they use; calls on one stream are safe;

@@ -37,7 +37,9 @@ class CsrInfo(ctypes.Structure):
                 ("max_degree", ctypes.c_int64), ("bin_rows", ctypes.c_int64 * 5), ("bin_nnz", ctypes.c_int64 * 5),
                 ("hub_threshold", ctypes.c_int32), ("segment_len", ctypes.c_int32), ("block_cost", ctypes.c_int32),
                 ("n_row_blocks", ctypes.c_int32), ("n_hub_rows", ctypes.c_int32), ("n_segments", ctypes.c_int32),
-                ("is_transpose", ctypes.c_int32), ("has_cached_transpose", ctypes.c_int32)]
+                ("is_transpose", ctypes.c_int32), ("has_cached_transpose", ctypes.c_int32),
+                ("spmm_mid_threshold", ctypes.c_int32), ("spmm_cut_rows", ctypes.c_int32),
+                ("spmm_pieces", ctypes.c_int32), ("spmm_row_blocks", ctypes.c_int32)]
 
 
 def lib_path() -> str:

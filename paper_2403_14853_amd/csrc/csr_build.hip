@@ -238,11 +238,13 @@ __global__ void __launch_bounds__(256) k_check_indices(const int32_t* __restrict
 }
 
 // Block boundaries forced by hub rows: a hub row starts a block and so does the row after it.
+// force_row (if inside the matrix) also starts a block: the derived matrix of the packed SpMM layout keeps
+// blocks of whole rows and blocks of row pieces apart that way.
 __global__ void __launch_bounds__(256) k_mark_rows(const int32_t* __restrict__ hubflag, int64_t n_rows,
-                                                   int32_t* __restrict__ mark) {
+                                                   int64_t force_row, int32_t* __restrict__ mark) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_rows) return;
-  mark[i] = (i == 0 || hubflag[i] || hubflag[i - 1]) ? 1 : 0;
+  mark[i] = (i == 0 || i == force_row || hubflag[i] || hubflag[i - 1]) ? 1 : 0;
 }
 
 // Balanced boundaries: block b starts at the first row whose cumulative short-row cost reaches b * block_cost.
@@ -373,6 +375,107 @@ __global__ void __launch_bounds__(256) k_item_desc(const int64_t* __restrict__ i
   desc[item] = q;
 }
 
+// ---- the derived matrix of the packed SpMM layout ------------------------------------------------------
+// Rows longer than mid_t ("cut rows") are cut into column-band pieces exactly like hub rows, but with a lower
+// threshold and smaller pieces, and the pieces - far too short to be work items of their own - become the rows
+// of a derived CSR that is appended, in schedule order (by first column), to a copy of the short rows:
+//   rows [0, n)        : the matrix's own rows, the cut ones left empty
+//   rows [n, n + n_pc) : the pieces, piece k being segment seg_order[k] of the cut partition
+// The derived matrix has short rows only, so the ordinary row blocks pack several pieces into every
+// full-sized work item; a piece's sum goes to the partial row of its segment and the fixed-order fix-up adds a
+// cut row's pieces as it does a hub row's segments.
+
+// lengths of the short part's rows (0 for a cut row)
+__global__ void __launch_bounds__(256) k_short_len(const int64_t* __restrict__ indptr, const int32_t* __restrict__ hubflag,
+                                                   int64_t n_rows, int32_t* __restrict__ len) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_rows) len[i] = hubflag[i] ? 0 : (int32_t)(indptr[i + 1] - indptr[i]);
+}
+
+// lengths of the pieces in schedule order
+__global__ void __launch_bounds__(256) k_piece_len(const int64_t* __restrict__ indptr, const int32_t* __restrict__ hub_rows,
+                                                   const int32_t* __restrict__ hub_seg_ptr,
+                                                   const int32_t* __restrict__ seg_hub,
+                                                   const int32_t* __restrict__ seg_begin,
+                                                   const int32_t* __restrict__ seg_order, int n_seg,
+                                                   int32_t* __restrict__ len) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= n_seg) return;
+  const int s = seg_order[k];
+  const int h = seg_hub[s];
+  const int64_t end = (s + 1 < hub_seg_ptr[h + 1]) ? (int64_t)seg_begin[s + 1] : indptr[hub_rows[h] + 1];
+  len[k] = (int32_t)(end - seg_begin[s]);
+}
+
+// row offsets of the derived matrix: the short part's scan, then the pieces' scan behind it
+__global__ void __launch_bounds__(256) k_join_offsets(const int64_t* __restrict__ short_scan, int64_t n_rows,
+                                                      const int64_t* __restrict__ piece_scan, int64_t n_seg,
+                                                      int64_t* __restrict__ indptr2) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_rows) indptr2[i] = short_scan[i];
+  else if (i <= n_rows + n_seg) indptr2[i] = short_scan[n_rows] + piece_scan[i - n_rows];
+}
+
+// Copy of the short rows' entries.  One thread per stored entry of the source matrix; the workgroup's tile of
+// consecutive entries spans a narrow range of rows, found once per tile, in which each thread then searches.
+constexpr int CP_TILE = 1024;
+__global__ void __launch_bounds__(256) k_copy_short(const int64_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+                                                    const float* __restrict__ values,
+                                                    const int32_t* __restrict__ hubflag, int64_t n_rows, int64_t nnz,
+                                                    const int64_t* __restrict__ indptr2, int32_t* __restrict__ indices2,
+                                                    float* __restrict__ values2, int32_t* __restrict__ src_pos) {
+  __shared__ int64_t s_lo, s_hi;
+  const int64_t p0 = (int64_t)blockIdx.x * CP_TILE;
+  if (threadIdx.x < 2) {  // last row starting at or before the tile's first / last entry
+    const int64_t target = threadIdx.x == 0 ? p0 : (p0 + CP_TILE - 1 < nnz ? p0 + CP_TILE - 1 : nnz - 1);
+    int64_t lo = 0, hi = n_rows;  // invariant: indptr[lo] <= target < indptr[hi]
+    while (hi - lo > 1) {
+      const int64_t mid = (lo + hi) >> 1;
+      if (indptr[mid] <= target) lo = mid; else hi = mid;
+    }
+    if (threadIdx.x == 0) s_lo = lo; else s_hi = lo;
+  }
+  __syncthreads();
+  for (int64_t p = p0 + threadIdx.x; p < p0 + CP_TILE && p < nnz; p += blockDim.x) {
+    int64_t lo = s_lo, hi = s_hi + 1;  // the entry's row: last one with indptr[row] <= p
+    while (hi - lo > 1) {
+      const int64_t mid = (lo + hi) >> 1;
+      if (indptr[mid] <= p) lo = mid; else hi = mid;
+    }
+    if (hubflag[lo]) continue;  // a cut row: its entries are copied piece by piece
+    const int64_t q = indptr2[lo] + (p - indptr[lo]);
+    indices2[q] = indices[p];
+    if (values2) values2[q] = values[p];
+    src_pos[q] = (int32_t)p;
+  }
+}
+
+// Copy of the pieces' entries: one wavefront per piece, both sides contiguous.
+__global__ void __launch_bounds__(256) k_copy_pieces(const int32_t* __restrict__ indices, const float* __restrict__ values,
+                                                     const int32_t* __restrict__ seg_begin,
+                                                     const int32_t* __restrict__ seg_order, int n_seg, int64_t n_rows,
+                                                     const int64_t* __restrict__ indptr2, int32_t* __restrict__ indices2,
+                                                     float* __restrict__ values2, int32_t* __restrict__ src_pos) {
+  const int lane = threadIdx.x & (ISP_WAVE - 1);
+  const int k = blockIdx.x * (blockDim.x / ISP_WAVE) + (threadIdx.x >> 6);
+  if (k >= n_seg) return;
+  const int64_t src = seg_begin[seg_order[k]];
+  const int64_t q0 = indptr2[n_rows + k], q1 = indptr2[n_rows + k + 1];
+  for (int64_t q = q0 + lane; q < q1; q += ISP_WAVE) {
+    const int64_t p = src + (q - q0);
+    indices2[q] = indices[p];
+    if (values2) values2[q] = values[p];
+    src_pos[q] = (int32_t)p;
+  }
+}
+
+__global__ void __launch_bounds__(256) k_regather_values(const int32_t* __restrict__ src_pos, const float* __restrict__ values,
+                                                         int64_t nnz, float* __restrict__ values2) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q < nnz) values2[q] = values[src_pos[q]];
+}
+
+// ---- workspace layout ------------------------------------------------------------------------------------
 struct ws_layout {
   size_t counters, cost, hubflag, nseg, cum_cost, mark, mpos, hpos, segbase, scan_tmp;
   size_t blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin, seg_key[2], seg_order[2], so_table, so_scanned, so_tmp;
@@ -380,14 +483,16 @@ struct ws_layout {
   int64_t max_blocks, max_hub, max_seg;
 };
 
-ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
+// The tables of one partition of a matrix with n_rows rows and nnz entries, laid out from offset `start`.
+ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp, size_t start = 0,
+                      bool with_partials = true) {
   ws_layout L;
-  size_t off = 0;
+  size_t off = start;
   auto take = [&](size_t bytes) { size_t o = off; off += isp_align(bytes); return o; };
   const int64_t n_bal = (nnz + n_rows) / pp.block_cost + 2;
   int64_t max_hub = nnz / ((int64_t)pp.hub_t + 1);
   if (max_hub > n_rows) max_hub = n_rows;
-  int64_t max_blocks = n_bal + 2 * max_hub + 2;
+  int64_t max_blocks = n_bal + 2 * max_hub + 3;
   if (max_blocks > n_rows + 1) max_blocks = n_rows + 1;
   // a row of degree deg has at most deg / min_piece pieces, and a piece of len entries at most
   // len / seg_len + 1 segments
@@ -418,25 +523,85 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp) {
   L.so_tmp = take(isp_scan_tmp_bytes(so_tbl + 1));
   L.inv_len = take((size_t)(n_rows + 1) * 4);
   L.item_desc = take((size_t)(max_blocks + max_seg + 2) * 16);
-  L.partials = take((size_t)(max_seg + 1) * ISP_PARTIAL_TILE * sizeof(float));
+  // (a derived matrix has no hub rows of its own, hence no partial rows)
+  L.partials = take(with_partials ? (size_t)(max_seg + 1) * ISP_PARTIAL_TILE * sizeof(float) : 256);
   L.total = off;
   return L;
 }
 
-}  // namespace
+// The packed SpMM layout's share of the workspace, behind the matrix's ordinary partition.
+struct packed_layout {
+  ws_layout cut;      // the cut partition of the matrix itself (its partial rows are the pieces' partial rows)
+  size_t indptr2, indices2, values2, src_pos, len_tmp, scan64, scan_tmp;
+  size_t part2_start; // the derived matrix's partition starts here (laid out once its row count is known)
+  size_t total;
+};
 
-size_t isp_partition_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz) {
-  return make_layout(n_rows, nnz, get_params(n_rows, n_cols, nnz)).total;
+partition_params cut_params(const partition_params& p1, int mid_t) {
+  partition_params c = p1;
+  c.hub_t = mid_t;
+  // pieces of 64 entries or more, on up to 32 bands (measured on 2.4 M columns: smaller pieces fetch less but
+  // pay it back in partial rows)
+  c.min_piece = env_int("ISP_MIN_PIECE", 64, c.seg_len / 8 > 4 ? c.seg_len / 8 : 4, 1 << 20);
+  return c;
 }
 
-isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
-                            const int32_t* indices, const float* values, void* ws, size_t ws_bytes, bool validate,
-                            hipStream_t s, isp_csr** out) {
-  const partition_params pp = get_params(n_rows, n_cols, nnz);
-  const ws_layout L = make_layout(n_rows, nnz, pp);
-  if (ws_bytes < L.total) return isp_fail(ISP_EINVAL, "workspace too small: %zu < %zu bytes", ws_bytes, L.total);
-  if (((uintptr_t)ws & 255) != 0) return isp_fail(ISP_EINVAL, "workspace must be 256-byte aligned");
-  char* base = (char*)ws;
+partition_params derived_params(const partition_params& p1, const partition_params& cut) {
+  partition_params d = p1;
+  d.hub_t = cut.hub_t > cut.seg_len ? cut.hub_t : cut.seg_len;  // no row of the derived matrix is longer
+  d.seg_len = d.hub_t;
+  d.bands = 1;
+  return d;
+}
+
+packed_layout make_packed_layout(int64_t n_rows, int64_t nnz, bool has_values, const partition_params& p1, int mid_t,
+                                 size_t start) {
+  packed_layout P;
+  const partition_params pc = cut_params(p1, mid_t);
+  P.cut = make_layout(n_rows, nnz, pc, start);
+  size_t off = P.cut.total;
+  auto take = [&](size_t bytes) { size_t o = off; off += isp_align(bytes); return o; };
+  const int64_t n2 = n_rows + P.cut.max_seg;
+  P.indptr2 = take((size_t)(n2 + 2) * 8);
+  P.indices2 = take((size_t)(nnz + 1) * 4);
+  P.values2 = has_values ? take((size_t)(nnz + 1) * 4) : 0;
+  P.src_pos = take((size_t)(nnz + 1) * 4);
+  const int64_t longest = n_rows > P.cut.max_seg ? n_rows : P.cut.max_seg;
+  P.len_tmp = take((size_t)(longest + 2) * 4);
+  P.scan64 = take((size_t)(n_rows + P.cut.max_seg + 4) * 8);  // the two scans, one behind the other
+  P.scan_tmp = take(isp_scan_tmp_bytes(longest + 1));
+  P.part2_start = off;
+  // upper bound of the derived matrix's partition
+  P.total = make_layout(n2, nnz, derived_params(p1, pc), off, false).total;
+  return P;
+}
+
+// Rows above this length are cut for the packed SpMM layout; 0 = no packed layout.  Chosen for large
+// matrices with many columns, where a column band of the dense operand is far larger than an L2: there the
+// pieces of mid-sized rows (too short to be work items, hence packed) gather from one band at a time like the
+// hub segments do.  ISP_MID_THRESHOLD overrides (0 disables).
+int mid_threshold(int64_t n_cols, int64_t nnz, const partition_params& p1) {
+  const int dflt = (nnz >= ((int64_t)8 << 20) && n_cols >= (1 << 19)) ? 256 : 0;
+  int t = env_int("ISP_MID_THRESHOLD", dflt, 0, 512);
+  if (t > 0 && t < 8) t = 8;
+  // the derived matrix's rows (short rows, pieces) must fit the grouped kernels' tables next to a block
+  if (t > 0 && (p1.block_cost + (t > p1.seg_len ? t : p1.seg_len) > 768)) t = 0;
+  return t;
+}
+
+// One partition of a CSR matrix: every table the kernels read, in the workspace region laid out by L.
+struct partition_out {
+  int32_t *blk_row, *hub_rows, *hub_seg_ptr, *seg_hub, *seg_begin, *hubflag;
+  const int32_t* seg_order;
+  int4* item_desc;
+  float* partials;
+  float* inv_len;
+  build_counters h;
+};
+
+isp_status build_partition(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr, const int32_t* indices,
+                           const partition_params& pp, char* base, const ws_layout& L, bool validate,
+                           int64_t force_row, hipStream_t s, partition_out* out) {
   build_counters* ctr = (build_counters*)(base + L.counters);
   int32_t* cost = (int32_t*)(base + L.cost);
   int32_t* hubflag = (int32_t*)(base + L.hubflag);
@@ -471,7 +636,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   isp_status st;
   if ((st = isp_scan_i32_to_i64(cost, cum_cost, n_rows, scan_tmp, s)) != ISP_OK) return st;
   if (n_rows > 0) {
-    k_mark_rows<<<row_grid, 256, 0, s>>>(hubflag, n_rows, mark);
+    k_mark_rows<<<row_grid, 256, 0, s>>>(hubflag, n_rows, force_row, mark);
     ISP_LAUNCH_CHECK();
     // total short-row cost <= nnz + n_rows, so this many targets cover it
     const int64_t n_bal = (nnz + n_rows) / pp.block_cost + 1;
@@ -485,7 +650,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
                                                        n_rows, blk_row, hub_rows, hub_seg_ptr, seg_hub, seg_begin,
                                                        seg_key[0], ctr, L.max_blocks, L.max_hub, L.max_seg);
   ISP_LAUNCH_CHECK();
-  build_counters h;
+  build_counters& h = out->h;
   ISP_HIP(hipMemcpyAsync(&h, ctr, sizeof(h), hipMemcpyDeviceToHost, s));
   ISP_HIP(hipStreamSynchronize(s));
   if (h.err & 1) return isp_fail(ISP_EBADCSR, "indptr is not a monotone offset array from 0 to nnz");
@@ -520,6 +685,125 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
                                                                              h.n_seg, pp.hub_t, item_desc);
     ISP_LAUNCH_CHECK();
   }
+  out->blk_row = blk_row; out->hub_rows = hub_rows; out->hub_seg_ptr = hub_seg_ptr; out->seg_hub = seg_hub;
+  out->seg_begin = seg_begin; out->hubflag = hubflag; out->seg_order = seg_order; out->item_desc = item_desc;
+  out->partials = (float*)(base + L.partials);
+  out->inv_len = (float*)(base + L.inv_len);
+  return ISP_OK;
+}
+
+void fill_view(isp_view& v, int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr, const int32_t* indices,
+               const float* values, const partition_out& po, const partition_params& pp) {
+  v.n_rows = n_rows; v.n_cols = n_cols; v.nnz = nnz;
+  v.indptr = indptr; v.indices = indices; v.values = values;
+  v.blk_row = po.blk_row; v.n_blocks = po.h.n_blocks;
+  v.hub_rows = po.hub_rows; v.hub_seg_ptr = po.hub_seg_ptr; v.seg_hub = po.seg_hub;
+  v.seg_begin = po.seg_begin; v.seg_order = po.seg_order; v.item_desc = po.item_desc;
+  v.n_hub = po.h.n_hub; v.n_seg = po.h.n_seg;
+  v.hub_t = pp.hub_t; v.seg_len = pp.seg_len;
+  v.partials = po.partials;
+  v.inv_len = po.inv_len;
+  v.n_real_rows = n_rows;
+  v.piece_slot = nullptr;
+}
+
+// The packed SpMM layout of the handle's matrix (see above), into A->vp.  A->v must be filled.
+isp_status build_packed(isp_csr* A, const partition_params& p1, int mid_t, char* base, const packed_layout& P,
+                        size_t ws_bytes, hipStream_t s) {
+  const isp_view& v = A->v;
+  const int64_t n = v.n_rows, nnz = v.nnz;
+  const partition_params pc = cut_params(p1, mid_t);
+  partition_out cut;
+  isp_status st = build_partition(n, v.n_cols, nnz, v.indptr, v.indices, pc, base, P.cut, false, -1, s, &cut);
+  if (st != ISP_OK) return st;
+  const int n_pc = cut.h.n_seg;
+  if (cut.h.n_hub == 0) return ISP_OK;  // nothing to cut: the ordinary partition serves
+  int64_t* indptr2 = (int64_t*)(base + P.indptr2);
+  int32_t* indices2 = (int32_t*)(base + P.indices2);
+  float* values2 = v.values ? (float*)(base + P.values2) : nullptr;
+  int32_t* src_pos = (int32_t*)(base + P.src_pos);
+  int32_t* len_tmp = (int32_t*)(base + P.len_tmp);
+  int64_t* short_scan = (int64_t*)(base + P.scan64);
+  int64_t* piece_scan = short_scan + (n + 2);
+  void* scan_tmp = base + P.scan_tmp;
+  k_short_len<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(v.indptr, cut.hubflag, n, len_tmp);
+  ISP_LAUNCH_CHECK();
+  if ((st = isp_scan_i32_to_i64(len_tmp, short_scan, n, scan_tmp, s)) != ISP_OK) return st;
+  k_piece_len<<<(unsigned)((n_pc + 255) / 256), 256, 0, s>>>(v.indptr, cut.hub_rows, cut.hub_seg_ptr, cut.seg_hub,
+                                                           cut.seg_begin, cut.seg_order, n_pc, len_tmp);
+  ISP_LAUNCH_CHECK();
+  if ((st = isp_scan_i32_to_i64(len_tmp, piece_scan, n_pc, scan_tmp, s)) != ISP_OK) return st;
+  const int64_t n2 = n + n_pc;
+  k_join_offsets<<<(unsigned)((n2 + 1 + 255) / 256), 256, 0, s>>>(short_scan, n, piece_scan, n_pc, indptr2);
+  ISP_LAUNCH_CHECK();
+  k_copy_short<<<(unsigned)((nnz + CP_TILE - 1) / CP_TILE), 256, 0, s>>>(v.indptr, v.indices, v.values, cut.hubflag, n, nnz,
+                                                                       indptr2, indices2, values2, src_pos);
+  ISP_LAUNCH_CHECK();
+  k_copy_pieces<<<(unsigned)((n_pc + 3) / 4), 256, 0, s>>>(v.indices, v.values, cut.seg_begin, cut.seg_order, n_pc, n,
+                                                         indptr2, indices2, values2, src_pos);
+  ISP_LAUNCH_CHECK();
+  // the derived matrix's own partition: row blocks only, none straddling the first piece row
+  const partition_params pd = derived_params(p1, pc);
+  const ws_layout L2 = make_layout(n2, nnz, pd, P.part2_start, false);
+  if (L2.total > ws_bytes) return isp_fail(ISP_EINVAL, "internal: packed layout exceeds the workspace (%zu > %zu)", L2.total, ws_bytes);
+  partition_out d2;
+  if ((st = build_partition(n2, v.n_cols, nnz, indptr2, indices2, pd, base, L2, false, n, s, &d2)) != ISP_OK) return st;
+  if (d2.h.n_hub != 0 || d2.h.n_seg != 0)
+    return isp_fail(ISP_EINVAL, "internal: the derived matrix has %d rows above its hub threshold", d2.h.n_hub);
+  isp_view& vp = A->vp;
+  fill_view(vp, n2, v.n_cols, nnz, indptr2, indices2, values2, d2, pd);
+  // the pieces' sums go to the cut partition's partial rows and are added by its hub tables
+  vp.hub_rows = cut.hub_rows; vp.hub_seg_ptr = cut.hub_seg_ptr; vp.n_hub = cut.h.n_hub;
+  vp.partials = cut.partials;
+  vp.inv_len = v.inv_len;
+  vp.n_real_rows = n;
+  vp.piece_slot = cut.seg_order;
+  A->has_packed = true;
+  A->packed_values_rw = values2;
+  A->packed_src_pos = src_pos;
+  A->info.spmm_mid_threshold = mid_t;
+  A->info.spmm_cut_rows = cut.h.n_hub;
+  A->info.spmm_pieces = n_pc;
+  A->info.spmm_row_blocks = d2.h.n_blocks;
+  return ISP_OK;
+}
+
+}  // namespace
+
+size_t isp_partition_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz) {
+  const partition_params p1 = get_params(n_rows, n_cols, nnz);
+  const ws_layout L = make_layout(n_rows, nnz, p1);
+  const int mid_t = mid_threshold(n_cols, nnz, p1);
+  if (mid_t == 0) return L.total;
+  return make_packed_layout(n_rows, nnz, true, p1, mid_t, L.total).total;
+}
+
+isp_status isp_refresh_packed_values(isp_csr* A, hipStream_t s) {
+  if (!A->has_packed || !A->packed_values_rw || !A->v.values || A->v.nnz == 0) return ISP_OK;
+  k_regather_values<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(A->packed_src_pos, A->v.values, A->v.nnz,
+                                                                      A->packed_values_rw);
+  ISP_LAUNCH_CHECK();
+  return ISP_OK;
+}
+
+isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
+                            const int32_t* indices, const float* values, void* ws, size_t ws_bytes, bool validate,
+                            hipStream_t s, isp_csr** out) {
+  const partition_params pp = get_params(n_rows, n_cols, nnz);
+  const ws_layout L = make_layout(n_rows, nnz, pp);
+  const int mid_t = mid_threshold(n_cols, nnz, pp);
+  packed_layout P{};
+  size_t need = L.total;
+  if (mid_t > 0) {
+    P = make_packed_layout(n_rows, nnz, values != nullptr, pp, mid_t, L.total);
+    need = P.total;
+  }
+  if (ws_bytes < need) return isp_fail(ISP_EINVAL, "workspace too small: %zu < %zu bytes", ws_bytes, need);
+  if (((uintptr_t)ws & 255) != 0) return isp_fail(ISP_EINVAL, "workspace must be 256-byte aligned");
+  char* base = (char*)ws;
+  partition_out po;
+  isp_status st = build_partition(n_rows, n_cols, nnz, indptr, indices, pp, base, L, validate, -1, s, &po);
+  if (st != ISP_OK) return st;
 
   int device = 0;
   ISP_HIP(hipGetDevice(&device));
@@ -527,24 +811,24 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   if (!A) return isp_fail(ISP_ENOMEM, "host allocation of the handle failed");
   A->device = device;
   A->tune = isp_read_tuning();
-  A->v.n_rows = n_rows; A->v.n_cols = n_cols; A->v.nnz = nnz;
-  A->v.indptr = indptr; A->v.indices = indices; A->v.values = values;
-  A->v.blk_row = blk_row; A->v.n_blocks = h.n_blocks;
-  A->v.hub_rows = hub_rows; A->v.hub_seg_ptr = hub_seg_ptr; A->v.seg_hub = seg_hub;
-  A->v.seg_begin = seg_begin; A->v.seg_order = seg_order; A->v.item_desc = item_desc;
-  A->v.n_hub = h.n_hub; A->v.n_seg = h.n_seg;
-  A->v.hub_t = pp.hub_t; A->v.seg_len = pp.seg_len;
-  A->v.partials = (float*)(base + L.partials);
-  A->v.inv_len = (const float*)(base + L.inv_len);
+  fill_view(A->v, n_rows, n_cols, nnz, indptr, indices, values, po, pp);
+  A->vp = A->v;
+  A->has_packed = false; A->packed_values_rw = nullptr; A->packed_src_pos = nullptr;
   A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false;
   A->mean_values = nullptr; A->mean_values_valid = false; A->mean_values_used = false;
   A->sel_flags = nullptr; A->inv_perm = nullptr; A->inv_perm_valid = false;
   isp_csr_info_t& I = A->info;
+  const build_counters& h = po.h;
   I.n_rows = n_rows; I.n_cols = n_cols; I.nnz = nnz; I.max_degree = (int64_t)h.max_degree;
   for (int b = 0; b < 5; ++b) { I.bin_rows[b] = (int64_t)h.bin_rows[b]; I.bin_nnz[b] = (int64_t)h.bin_nnz[b]; }
   I.hub_threshold = pp.hub_t; I.segment_len = pp.seg_len; I.block_cost = pp.block_cost;
   I.n_row_blocks = h.n_blocks; I.n_hub_rows = h.n_hub; I.n_segments = h.n_seg;
   I.is_transpose = 0; I.has_cached_transpose = 0;
+  I.spmm_mid_threshold = 0; I.spmm_cut_rows = 0; I.spmm_pieces = 0; I.spmm_row_blocks = 0;
+  if (mid_t > 0 && nnz > 0) {
+    st = build_packed(A, pp, mid_t, base, P, ws_bytes, s);
+    if (st != ISP_OK) { delete A; return st; }
+  }
   *out = A;
   return ISP_OK;
 }

@@ -101,7 +101,11 @@ isp_status isp_csr_values_changed(isp_csr_t* A, void* stream) {
   if (A->is_transpose) return isp_fail(ISP_EINVAL, "pass the source handle, not its transpose");
   isp_status st = isp_check_device(A);
   if (st != ISP_OK) return st;
-  return isp_transpose_refresh_values(A, (hipStream_t)stream);
+  // everything derived from the values, in stream order: the packed SpMM layout's copy, the transposed values
+  // (and what the mean backward keeps of them), the transpose's own packed copy
+  if ((st = isp_refresh_packed_values(A, (hipStream_t)stream)) != ISP_OK) return st;
+  if ((st = isp_transpose_refresh_values(A, (hipStream_t)stream)) != ISP_OK) return st;
+  return A->At ? isp_refresh_packed_values(A->At, (hipStream_t)stream) : ISP_OK;
 }
 
 isp_status isp_csr_export(const isp_csr_t* A, const int64_t** indptr, const int32_t** indices, const float** values,

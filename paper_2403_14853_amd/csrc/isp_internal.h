@@ -33,7 +33,13 @@ struct isp_view {
   int32_t n_hub, n_seg;
   int32_t hub_t, seg_len;
   float* partials;         // n_seg * ISP_PARTIAL_TILE floats
-  const float* inv_len;    // n_rows: 1 / (stored entries of the row), 0 for an empty row
+  const float* inv_len;    // 1 / (stored entries of the row), 0 for an empty row; indexed by the rows of the
+                           // handle's matrix (also in the view of a derived matrix)
+  // Views of a derived matrix (packed SpMM layout) only: rows [n_real_rows, n_rows) are pieces of the handle's
+  // long rows; piece k = row n_real_rows + k adds into partial row piece_slot[k], and hub_rows / hub_seg_ptr /
+  // n_hub list the cut rows with their partial rows for the fix-up.  Ordinary views: n_real_rows = n_rows.
+  int64_t n_real_rows;
+  const int32_t* piece_slot;
 };
 
 // Tuning and debugging overrides.  They come from the environment and are resolved ONCE, when a handle is
@@ -52,6 +58,13 @@ int isp_wave_slots();
 
 struct isp_csr {
   isp_view v;
+  // Packed SpMM layout (csr_build.hip): a derived matrix whose rows are the short rows of v's matrix followed by
+  // column-band pieces of its long rows, in its own copy of the index / value arrays (in the build workspace).
+  // Only the tuned SpMM reads it.  Without it vp == v.
+  isp_view vp;
+  bool has_packed;
+  float* packed_values_rw;        // vp.values, writable, NULL without values
+  const int32_t* packed_src_pos;  // position in v's arrays of every entry of the derived matrix
   isp_tuning tune;
   const int32_t* perm;     // transposes only
   float* t_values_rw;      // transposes only: the values array (in the workspace), writable
@@ -97,6 +110,8 @@ size_t isp_partition_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz);
 isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* indptr,
                             const int32_t* indices, const float* values, void* ws, size_t ws_bytes,
                             bool validate, hipStream_t s, isp_csr** out);
+// Copy A's (rewritten) values into the packed SpMM layout's own value array again.
+isp_status isp_refresh_packed_values(isp_csr* A, hipStream_t s);
 
 // ---- transpose (transpose.hip) ---------------------------------------------------------------
 size_t isp_transpose_workspace_bytes(int64_t n_rows, int64_t n_cols, int64_t nnz, bool has_values);

@@ -392,7 +392,7 @@ __device__ inline void hub_fixup_wg(const isp_view& A, int d, int k0, float* __r
       }
   }
   const int row = A.hub_rows[h];
-  const float inv = MEAN ? 1.f / (float)(A.indptr[row + 1] - A.indptr[row]) : 1.f;
+  const float inv = MEAN ? A.inv_len[row] : 1.f;  // (= 1.f / (float)length, as the row blocks compute it)
 #pragma unroll
   for (int tt = 0; tt < T; ++tt) {
     const int rel = (tt * ISP_WAVE + lane) * VEC;

@@ -105,13 +105,18 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const float* __restrict__ xcol = lane_on ? X + col : X;
   const unsigned lane_byte = lane_on ? (unsigned)col * 4u : 0u;
   const unsigned pitch_byte = (unsigned)ldx * 4u;
-  float* __restrict__ out = it.is_seg ? A.partials + (col - k_base) : Y + col;
-  const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
+  // Rows of a derived matrix (packed layout) beyond the real ones are pieces of long rows: like a hub segment
+  // each adds into a partial row, named by piece_slot.  A block never mixes real rows and pieces.
+  const bool pieces = !it.is_seg && (int64_t)it.row >= A.n_real_rows;
+  const bool to_partial = it.is_seg || pieces;
+  const int32_t* __restrict__ slot_of = A.piece_slot - (pieces ? A.n_real_rows : 0);  // indexed by the piece's row
+  float* __restrict__ out = to_partial ? A.partials + (col - k_base) : Y + col;
+  const int64_t ldo = to_partial ? (int64_t)ISP_PARTIAL_TILE : ldy;
   float acc[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
   const bool listed = SPARSE_ROWS && !it.is_seg;  // else every row owns a step and the k-th row end is row k's
-  if (listed && lane_on) {  // the empty rows' outputs (also their mean)
+  if (listed && lane_on && !pieces) {  // the empty rows' outputs (also their mean); a piece is never empty
     const int n_rows = it.row_last - it.row;
     for (int r = g; r < n_rows; r += G)
       if (L.rp[r + 1] == L.rp[r]) store_vec<VEC>(out + (int64_t)(it.row + r) * ldo, acc);
@@ -123,12 +128,13 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 
   auto finish_row = [&]() {
     const int r_local = __builtin_amdgcn_readfirstlane(r_next);  // (wave-uniform: scalar address math)
-    const int row = it.row + r_local;
+    int row = it.row + r_local;
+    if (pieces) row = __builtin_amdgcn_readfirstlane(slot_of[row]);  // (wave-uniform address: one scalar load)
     ++k_done;
     r_next = listed ? (int)L.ss[k_done] : k_done;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = group_sum<LPG>(acc[v]);
-    if (mean_mode == 1 && !it.is_seg) {  // hub segments keep plain partial sums; their fix-up divides
+    if (mean_mode == 1 && !to_partial) {  // segments and pieces keep plain partial sums; their fix-up divides
       const int len = (int)L.rp[r_local + 1] - (int)L.rp[r_local];
       const float inv = len > 0 ? 1.f / (float)len : 0.f;
 #pragma unroll
@@ -200,8 +206,11 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 template <int LPG, int VEC = 4>
 isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, int k_base, int n_slices, float* Y,
                           int64_t ldy, int mean_mode, const float* values_override, hipStream_t s) {
-  const isp_view& v = A->v;
-  const float* vals = values_override ? values_override : v.values;  // (one value per stored entry, A's order)
+  // The packed layout (a derived matrix in which the pieces of long rows share work items) when the handle has
+  // one; an override of the values is in the order of A's own entries and therefore runs on A's own partition.
+  const bool packed = A->has_packed && !values_override && A->info.block_cost + A->vp.hub_t <= GS_MAX_ENT;
+  const isp_view& v = packed ? A->vp : A->v;
+  const float* vals = values_override ? values_override : v.values;  // (one value per stored entry, the view's order)
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * (unsigned)n_slices;

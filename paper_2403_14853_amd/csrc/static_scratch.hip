@@ -45,9 +45,13 @@ extern "C" isp_status isp_spmm_static_scratch(const isp_csr_t* A, const float* X
   if ((st = isp_check_device(A)) != ISP_OK) return st;  // (the handle's device is the current one from here on)
   if ((st = isp_check_dense(X, ldx, d, A->v.nnz > 0 ? A->v.n_cols : 0, "X")) != ISP_OK) return st;
   if ((st = isp_check_dense(Y, ldy, d, A->v.n_rows, "Y")) != ISP_OK) return st;
-  if (A->v.n_seg > ISP_STATIC_SCRATCH_ROWS)
-    return isp_fail(ISP_EUNSUPPORTED, "the handle has %d hub-row segments; the static scratch holds %d partial rows "
-                    "(use isp_spmm, whose scratch is the build workspace)", A->v.n_seg, ISP_STATIC_SCRATCH_ROWS);
+  // partial rows a launch may touch: one per hub-row segment, or one per piece where the handle has the
+  // packed SpMM layout (large matrices with many columns)
+  const int n_partial = A->has_packed && A->info.spmm_pieces > A->v.n_seg ? A->info.spmm_pieces : A->v.n_seg;
+  if (n_partial > ISP_STATIC_SCRATCH_ROWS)
+    return isp_fail(ISP_EUNSUPPORTED, "the handle needs %d partial rows (hub-row segments / row pieces); the static "
+                    "scratch holds %d (use isp_spmm, whose scratch is the build workspace)", n_partial,
+                    ISP_STATIC_SCRATCH_ROWS);
   float* ptr = nullptr;
   if ((st = scratch_address(A->device, &ptr)) != ISP_OK) return st;
   // The same handle with its partial rows redirected.  Every partial row a launch reads was written by that
@@ -55,5 +59,6 @@ extern "C" isp_status isp_spmm_static_scratch(const isp_csr_t* A, const float* X
   // and whatever an earlier call left in the array is never read.
   isp_csr view = *A;
   view.v.partials = ptr;
+  view.vp.partials = ptr;
   return isp_spmm_launch(&view, X, ldx, d, Y, ldy, (hipStream_t)stream);
 }

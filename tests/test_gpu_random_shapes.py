@@ -33,6 +33,8 @@ def _case(seed):
     # column bands of the hub rows (drawn last, so the fields above keep their values per seed)
     env["ISP_BANDS"] = str(int(rng.choice([1, 2, 8, 32])))
     env["ISP_MIN_PIECE"] = str(int(rng.choice([4, 16, 64, 256])))
+    # the packed SpMM layout: off, or rows above a small threshold cut into pieces that share work items
+    env["ISP_MID_THRESHOLD"] = str(int(rng.choice([0, 8, 20, 64])))
     return c
 
 
