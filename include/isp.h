@@ -38,6 +38,7 @@
  *       ISP_NO_GROUPED         run every operation on the general kernels
  *       ISP_SPMM_LPG, ISP_SPMM_TILE   lanes per group / feature columns per launch of the tuned SpMM
  *       ISP_SDDMM_ONE_PASS     SDDMM keeps 128-column rows in one pass
+ *       ISP_WIDE_GROUPS        most 256-column groups a split row stores per launch of a FusedMM pass wider than 256
  *     isp_csr_build_workspace reads the partition sizes too, so set them before both calls or not at all.
  */
 #ifndef ISP_H
@@ -193,7 +194,8 @@ isp_status isp_sddmm(const isp_csr_t* A, const float* U, int64_t ldu, const floa
  * f chosen by op (ISP_OP_SIGMOID, ISP_OP_DOT, ISP_OP_ONE).  The per-edge scores are never written to
  * memory.  d <= 1024; beyond 256 columns d must be a multiple of 4 and the rows 16-byte aligned (base pointers
  * and leading dimensions), else ISP_EUNSUPPORTED.  Up to 256 columns run on the tuned kernels; wider rows on a
- * slower general path (one launch per 256 columns for the rows long enough to be split).
+ * slower general path (whole rows per lane group; the rows long enough to be split keep one partial row per 256
+ * columns, normally all in one launch, in several when the scratch is too small for that).
  */
 isp_status isp_fusedmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,
                        int64_t ldy, void* stream);

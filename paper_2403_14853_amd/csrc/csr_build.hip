@@ -87,6 +87,7 @@ isp_tuning isp_read_tuning() {
   t.spmm_lpg = (lpg == 4 || lpg == 8 || lpg == 16 || lpg == 32 || lpg == 64) ? lpg : 0;
   const int tile = env_int("ISP_SPMM_TILE", 0, 0, 256);
   t.spmm_tile = (tile == 64 || tile == 128 || tile == 256) ? tile : 0;
+  t.wide_groups = env_int("ISP_WIDE_GROUPS", 0, 0, 4);
   return t;
 }
 
@@ -815,6 +816,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->tune = isp_read_tuning();
   fill_view(A->v, n_rows, n_cols, nnz, indptr, indices, values, po, pp);
   A->vp = A->v;
+  A->partial_rows = L.max_seg + 1;
   A->has_packed = false; A->packed_values_rw = nullptr; A->packed_src_pos = nullptr;
   A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false;
   A->mean_values = nullptr; A->mean_values_valid = false; A->mean_values_used = false;

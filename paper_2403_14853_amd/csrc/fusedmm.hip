@@ -126,8 +126,8 @@ template <class P>
 __global__ void __launch_bounds__(ISP_WG) k_fused(isp_view A, const int64_t* __restrict__ indptr,
                                                   const int32_t* __restrict__ indices,
                                                   const float* __restrict__ values, typename P::args pa, int d,
-                                                  float* __restrict__ Y, int64_t ldy, int store_group) {
-  stream_item<P>(A, indptr, indices, values, pa, d, 0, Y, ldy, store_group);
+                                                  float* __restrict__ Y, int64_t ldy, int store_group, int group_cnt) {
+  stream_item<P>(A, indptr, indices, values, pa, d, 0, Y, ldy, store_group, group_cnt);
 }
 
 template <int VEC, int T, bool ACC>
@@ -137,28 +137,35 @@ __global__ void __launch_bounds__(ISP_WG) k_fused_fixup(isp_view A, int d, float
 
 template <int VEC, bool ACC>
 __global__ void __launch_bounds__(ISP_WG) k_fused_fixup_group(isp_view A, int d, int k0, float* __restrict__ Y,
-                                                              int64_t ldy) {
-  hub_fixup<VEC, 1, ACC>(A, d, k0, Y, ldy);
+                                                              int64_t ldy, int stride, int slot) {
+  hub_fixup<VEC, 1, ACC>(A, d, k0, Y, ldy, stride, slot);
 }
 
-// store_group < 0: one launch covers all d <= 256 columns.  Otherwise (wider rows) one launch per column
-// group: hub segments compute with whole rows but store that group only, and the fix-up adds the group's
-// partial rows; the row blocks do all their work in the launch of group 0.
+// store_group < 0: one launch covers all d <= 256 columns.  Otherwise (wider rows) hub segments compute with
+// whole rows and store column groups [store_group, store_group + group_cnt), one partial row per group, and
+// one fix-up per group adds them; the row blocks do all their work in the launch that starts at group 0.
 template <class P>
 isp_status run_pass(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s,
-                    int store_group = -1) {
+                    int store_group = -1, int group_cnt = 1) {
   const isp_view& v = A->v;
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    k_fused<P><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy, store_group);
+    k_fused<P><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy, store_group, group_cnt);
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
     const unsigned grid = (unsigned)((v.n_hub + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
-    if (store_group < 0) k_fused_fixup<P::VEC, P::T, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, Y, ldy);
-    else k_fused_fixup_group<P::VEC, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, store_group * ISP_WAVE * P::VEC, Y, ldy);
-    ISP_LAUNCH_CHECK();
+    if (store_group < 0) {
+      k_fused_fixup<P::VEC, P::T, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, Y, ldy);
+      ISP_LAUNCH_CHECK();
+    } else {
+      for (int g = 0; g < group_cnt; ++g) {
+        k_fused_fixup_group<P::VEC, P::ACCUMULATE><<<grid, ISP_WG, 0, s>>>(v, d, (store_group + g) * ISP_WAVE * P::VEC, Y,
+                                                                          ldy, group_cnt, g);
+        ISP_LAUNCH_CHECK();
+      }
+    }
   }
   return ISP_OK;
 }
@@ -266,6 +273,15 @@ isp_status run_grouped_d(const isp_csr* A, const typename P::args& pa, int d, fl
   return run_grouped<P, 64>(A, pa, d, Y, ldy, s);
 }
 
+// Column groups (of 256) a hub segment may store per launch of a wide pass: as many as the partial-row scratch
+// holds for all segments at once (the scratch is sized for the worst-case segment count, usually several times
+// the actual one), at least one.  ISP_WIDE_GROUPS (read at build) caps it, for tests.
+int groups_per_launch(const isp_csr* A, int n_groups) {
+  int64_t gc = A->v.n_seg > 0 ? A->partial_rows / A->v.n_seg : n_groups;
+  if (A->tune.wide_groups > 0 && gc > A->tune.wide_groups) gc = A->tune.wide_groups;
+  return gc < 1 ? 1 : (gc > n_groups ? n_groups : (int)gc);
+}
+
 bool grouped_partition_ok(const isp_csr* A) {
   return A->info.block_cost <= GS_MAX_ROWS && A->info.block_cost + A->v.hub_t <= GS_MAX_ENT &&
          A->v.seg_len <= GS_MAX_ENT && !A->tune.no_grouped;
@@ -311,7 +327,9 @@ isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int
     if (!(ok4 && d % 4 == 0))
       return isp_fail(ISP_EUNSUPPORTED, "FusedMM with d > %d needs d %% 4 == 0 and 16-byte aligned rows", ISP_PARTIAL_TILE);
     const int n_groups = (d + ISP_PARTIAL_TILE - 1) / ISP_PARTIAL_TILE;
-    for (int w = 0; w < n_groups && st == ISP_OK; ++w) {
+    const int gc = groups_per_launch(A, n_groups);
+    for (int w = 0; w < n_groups && st == ISP_OK; w += gc) {
+      const int cnt = n_groups - w < gc ? n_groups - w : gc;
 #define ISP_WIDE(T, HV)                             \
   {                                                 \
     using P = fwd_policy<4, T, HV>;                 \
@@ -319,7 +337,7 @@ isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int
     pa.src[0] = X;                                  \
     pa.ld[0] = ldx;                                 \
     pa.op = op;                                     \
-    st = run_pass<P>(A, pa, d, Y, ldy, s, w);       \
+    st = run_pass<P>(A, pa, d, Y, ldy, s, w, cnt);  \
   }
       if (n_groups <= 2) { if (hv) ISP_WIDE(2, true) else ISP_WIDE(2, false) }
       else { if (hv) ISP_WIDE(4, true) else ISP_WIDE(4, false) }
@@ -374,20 +392,23 @@ isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx,
     using P1 = bwd_row_policy<4, T, HV>;                                 \
     P1::args p1;                                                         \
     p1.src[0] = X; p1.ld[0] = ldx; p1.G = G; p1.ldg = ldg; p1.op = op;   \
-    st = run_pass<P1>(A, p1, d, dX, lddx, s, w);                         \
+    st = run_pass<P1>(A, p1, d, dX, lddx, s, w, cnt);                    \
   }
 #define ISP_WIDE_COL(T, HV)                                              \
   {                                                                      \
     using P2 = bwd_col_policy<4, T, HV>;                                 \
     P2::args p2;                                                         \
     p2.src[0] = X; p2.ld[0] = ldx; p2.src[1] = G; p2.ld[1] = ldg; p2.op = op; \
-    st = run_pass<P2>(A->At, p2, d, dX, lddx, s, w);                     \
+    st = run_pass<P2>(A->At, p2, d, dX, lddx, s, w, cnt);                \
   }
-    for (int w = 0; w < n_groups && st == ISP_OK; ++w) {
+    const int gc1 = groups_per_launch(A, n_groups), gc2 = groups_per_launch(A->At, n_groups);
+    for (int w = 0; w < n_groups && st == ISP_OK; w += gc1) {
+      const int cnt = n_groups - w < gc1 ? n_groups - w : gc1;
       if (n_groups <= 2) { if (hv) ISP_WIDE_ROW(2, true) else ISP_WIDE_ROW(2, false) }
       else { if (hv) ISP_WIDE_ROW(4, true) else ISP_WIDE_ROW(4, false) }
     }
-    for (int w = 0; w < n_groups && st == ISP_OK; ++w) {
+    for (int w = 0; w < n_groups && st == ISP_OK; w += gc2) {
+      const int cnt = n_groups - w < gc2 ? n_groups - w : gc2;
       if (n_groups <= 2) { if (hv) ISP_WIDE_COL(2, true) else ISP_WIDE_COL(2, false) }
       else { if (hv) ISP_WIDE_COL(4, true) else ISP_WIDE_COL(4, false) }
     }

@@ -50,6 +50,7 @@ struct isp_tuning {
   bool sddmm_one_pass;  // ISP_SDDMM_ONE_PASS: SDDMM never splits 128-column rows into two 64-column passes
   int spmm_lpg;         // ISP_SPMM_LPG: lanes per group of the grouped SpMM (0 = chosen by shape)
   int spmm_tile;        // ISP_SPMM_TILE: feature columns per launch of the grouped SpMM (0 = chosen by shape)
+  int wide_groups;      // ISP_WIDE_GROUPS: most column groups a hub segment stores per launch of a wide FusedMM pass (0 = as many as fit)
 };
 isp_tuning isp_read_tuning();
 // Wavefront slots of the current device at the occupancy the row-streaming kernels run at (compute units x 4
@@ -62,6 +63,7 @@ struct isp_csr {
   // column-band pieces of its long rows, in its own copy of the index / value arrays (in the build workspace).
   // Only the tuned SpMM reads it.  Without it vp == v.
   isp_view vp;
+  int64_t partial_rows;           // partial rows (ISP_PARTIAL_TILE floats each) v.partials has room for
   bool has_packed;
   float* packed_values_rw;        // vp.values, writable, NULL without values
   const int32_t* packed_src_pos;  // position in v's arrays of every entry of the derived matrix

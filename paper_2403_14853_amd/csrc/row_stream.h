@@ -106,11 +106,12 @@ template <class P>
 __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                    const int32_t* __restrict__ indices, const float* __restrict__ values,
                                    const typename P::args& pa, int d, int k0, float* __restrict__ Y, int64_t ldy,
-                                   int store_group = -1) {
-  // store_group >= 0 (operations that need whole rows per entry, at widths beyond a partial row; one launch
-  // per column group): a hub segment computes with every group but stores only that one - its 64 * VEC
-  // columns are what the partial row then holds; row blocks write whole output rows, so they run in the
-  // launch of group 0 only
+                                   int store_group = -1, int group_cnt = 1) {
+  // store_group >= 0 (operations that need whole rows per entry, at widths beyond a partial row): a hub
+  // segment computes with every column group of 64 * VEC columns but stores only groups [store_group,
+  // store_group + group_cnt), into group_cnt consecutive partial rows (segment s owns rows s * group_cnt ...);
+  // the host picks group_cnt so that all segments' rows fit the scratch and launches once per run of groups.
+  // Row blocks write whole output rows, so they run in the launch that starts at group 0 only
   constexpr int VEC = P::VEC, T = P::T, NG = P::NG, U = P::U;
   const int lane = threadIdx.x & (ISP_WAVE - 1);
   const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6)));
@@ -129,8 +130,8 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
   }
   // where results go: Y rows for block items, partial rows for segments
   float* __restrict__ out = it.is_seg ? A.partials : Y;
-  const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE : ldy;
-  // partial rows hold only the current column tile (of it, only the stored group)
+  const int64_t ldo = it.is_seg ? (int64_t)ISP_PARTIAL_TILE * (store_group >= 0 ? group_cnt : 1) : ldy;
+  // partial rows hold only the current column tile (of it, only the stored groups, one row each)
   const int out_k0 = it.is_seg ? k0 + (store_group > 0 ? store_group * ISP_WAVE * VEC : 0) : 0;
 
   int row = it.row;
@@ -161,7 +162,7 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
                 it.is_seg ? A.partials + (int64_t)row * ISP_PARTIAL_TILE : nullptr, col, on, k0);
 #pragma unroll
     for (int tt = 0; tt < T; ++tt) {
-      if (on[tt] && (store_group < 0 || tt == store_group)) {
+      if (on[tt] && (store_group < 0 || (tt >= store_group && tt < store_group + group_cnt))) {
         float* o = out + (int64_t)row * ldo + (col[tt] - out_k0);
         if (P::ACCUMULATE && !it.is_seg) {
           float old[VEC];
@@ -294,8 +295,11 @@ __device__ inline void stream_item(const isp_view& A, const int64_t* __restrict_
 
 // Fixed-order combination of hub-segment partial sums: one wave per hub row adds its segments'
 // partial rows in segment order and writes (or, with ACCUMULATE, adds to) the output row.
+// stride / slot: segment s's partial row is row s * stride + slot of the scratch (1 / 0 unless the segments
+// stored several column groups each).
 template <int VEC, int T, bool ACCUMULATE>
-__device__ inline void hub_fixup(const isp_view& A, int d, int k0, float* __restrict__ Y, int64_t ldy) {
+__device__ inline void hub_fixup(const isp_view& A, int d, int k0, float* __restrict__ Y, int64_t ldy, int stride = 1,
+                                 int slot = 0) {
   const int lane = threadIdx.x & (ISP_WAVE - 1);
   const int h = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * ISP_WAVES_PER_WG + (threadIdx.x >> 6)));
   if (h >= A.n_hub) return;
@@ -312,7 +316,7 @@ __device__ inline void hub_fixup(const isp_view& A, int d, int k0, float* __rest
     for (; s + 8 <= s1; s += 8) {  // eight partial rows in flight, added in segment order
       float t[8][VEC];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) load_vec<VEC>(A.partials + (int64_t)(s + u) * ISP_PARTIAL_TILE + rel, t[u]);
+      for (int u = 0; u < 8; ++u) load_vec<VEC>(A.partials + ((int64_t)(s + u) * stride + slot) * ISP_PARTIAL_TILE + rel, t[u]);
 #pragma unroll
       for (int u = 0; u < 8; ++u)
 #pragma unroll
@@ -320,7 +324,7 @@ __device__ inline void hub_fixup(const isp_view& A, int d, int k0, float* __rest
     }
     for (; s < s1; ++s) {
       float t[VEC];
-      load_vec<VEC>(A.partials + (int64_t)s * ISP_PARTIAL_TILE + rel, t);
+      load_vec<VEC>(A.partials + ((int64_t)s * stride + slot) * ISP_PARTIAL_TILE + rel, t);
 #pragma unroll
       for (int v = 0; v < VEC; ++v) acc[v] += t[v];
     }

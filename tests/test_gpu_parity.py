@@ -143,11 +143,23 @@ def test_sweep_widths_default_partition(d):
     A.destroy()
 
 
+@pytest.mark.parametrize("groups_per_launch", [None, 1, 2, 3])
 @pytest.mark.parametrize("d", [260, 512, 516, 1024])
-def test_fusedmm_wider_than_a_partial_row(small_partition, d):
+def test_fusedmm_wider_than_a_partial_row(small_partition, d, groups_per_launch):
     """Beyond 256 columns the score still needs whole rows while a hub segment's partial row holds 256: the
-    kernels compute with whole rows and store one 256-column group per launch (2 groups at 260 and 512, the
-    last one ragged at 260; 3 of 4 at 516; 4 at 1024)."""
+    kernels compute with whole rows and a segment stores its 256-column groups (2 at 260 and 512, the last one
+    ragged at 260; 3 at 516; 4 at 1024) into as many partial rows as the scratch has room for - all of them in
+    one launch by default, one, two or three per launch when capped."""
+    os.environ.pop("ISP_WIDE_GROUPS", None)
+    if groups_per_launch:
+        os.environ["ISP_WIDE_GROUPS"] = str(groups_per_launch)
+    try:
+        _fusedmm_wide_case(d)
+    finally:
+        os.environ.pop("ISP_WIDE_GROUPS", None)
+
+
+def _fusedmm_wide_case(d):
     w = graphgen.make_config(1, shrink=256)
     rng = np.random.default_rng(d)
     X = (0.1 * rng.standard_normal((w.n, d))).astype(np.float32)
