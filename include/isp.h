@@ -38,6 +38,7 @@
  *       ISP_NO_GROUPED         run every operation on the general kernels
  *       ISP_SPMM_LPG, ISP_SPMM_TILE   lanes per group / feature columns per launch of the tuned SpMM
  *       ISP_SDDMM_ONE_PASS     SDDMM keeps 128-column rows in one pass
+ *       ISP_NO_MIRROR          the FusedMM backward always runs its two passes, also on symmetric patterns
  *       ISP_WIDE_GROUPS        most 256-column groups a split row stores per launch of a FusedMM pass wider than 256
  *     isp_csr_build_workspace reads the partition sizes too, so set them before both calls or not at all.
  */
@@ -91,6 +92,9 @@ typedef struct {
   int32_t spmm_cut_rows;
   int32_t spmm_pieces;
   int32_t spmm_row_blocks; /* work items of that layout (whole short rows, or several pieces)              */
+  /* 1 once the cached transpose exists and its offsets and indices equal the handle's own element for element
+     (a symmetric pattern with ascending rows): the FusedMM backward then runs as one pass over the matrix     */
+  int32_t symmetric_pattern;
 } isp_csr_info_t;
 
 /* Bytes of device workspace isp_csr_build needs for a matrix of this shape (upper bound). */
@@ -205,7 +209,10 @@ isp_status isp_fusedmm(const isp_csr_t* A, const float* X, int64_t ldx, int32_t 
  * dz_p = values[p] <g_i, x_j> f'(z_p)   (s_p (1 - s_p) for the sigmoid):
  *   dX[i] = sum_{p in row i} dz_p x_j  +  sum_{p: indices[p] = i} (values[p] s_p g_r + dz_p x_r),
  * r = row of p.  The second sum runs over row i of the cached transpose, so
- * isp_csr_transpose_cached(A) must have succeeded before; otherwise ISP_EINVAL.
+ * isp_csr_transpose_cached(A) must have succeeded before; otherwise ISP_EINVAL.  When the transpose's offsets
+ * and indices turn out equal to A's own (a symmetric pattern with ascending rows; the values may differ) both
+ * sums run over the same neighbours and the tuned kernels take them in one pass over A, gathering x_j and g_j
+ * once for both (two gathered rows per entry instead of three).
  */
 isp_status isp_fusedmm_backward(isp_csr_t* A, const float* X, int64_t ldx, const float* dY, int64_t lddy,
                                 int32_t d, int op, float* dX, int64_t lddx, void* stream);

@@ -39,7 +39,7 @@ class CsrInfo(ctypes.Structure):
                 ("n_row_blocks", ctypes.c_int32), ("n_hub_rows", ctypes.c_int32), ("n_segments", ctypes.c_int32),
                 ("is_transpose", ctypes.c_int32), ("has_cached_transpose", ctypes.c_int32),
                 ("spmm_mid_threshold", ctypes.c_int32), ("spmm_cut_rows", ctypes.c_int32),
-                ("spmm_pieces", ctypes.c_int32), ("spmm_row_blocks", ctypes.c_int32)]
+                ("spmm_pieces", ctypes.c_int32), ("spmm_row_blocks", ctypes.c_int32), ("symmetric_pattern", ctypes.c_int32)]
 
 
 def lib_path() -> str:

@@ -88,6 +88,7 @@ isp_tuning isp_read_tuning() {
   const int tile = env_int("ISP_SPMM_TILE", 0, 0, 256);
   t.spmm_tile = (tile == 64 || tile == 128 || tile == 256) ? tile : 0;
   t.wide_groups = env_int("ISP_WIDE_GROUPS", 0, 0, 4);
+  t.no_mirror = getenv("ISP_NO_MIRROR") != nullptr;
   return t;
 }
 
@@ -818,7 +819,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->vp = A->v;
   A->partial_rows = L.max_seg + 1;
   A->has_packed = false; A->packed_values_rw = nullptr; A->packed_src_pos = nullptr;
-  A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false;
+  A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false; A->mirror_aligned = false;
   A->mean_values = nullptr; A->mean_values_valid = false; A->mean_values_used = false;
   A->sel_flags = nullptr; A->inv_perm = nullptr; A->inv_perm_valid = false;
   isp_csr_info_t& I = A->info;
@@ -828,7 +829,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   I.hub_threshold = pp.hub_t; I.segment_len = pp.seg_len; I.block_cost = pp.block_cost;
   I.n_row_blocks = h.n_blocks; I.n_hub_rows = h.n_hub; I.n_segments = h.n_seg;
   I.is_transpose = 0; I.has_cached_transpose = 0;
-  I.spmm_mid_threshold = 0; I.spmm_cut_rows = 0; I.spmm_pieces = 0; I.spmm_row_blocks = 0;
+  I.spmm_mid_threshold = 0; I.spmm_cut_rows = 0; I.spmm_pieces = 0; I.spmm_row_blocks = 0; I.symmetric_pattern = 0;
   if (mid_t > 0 && nnz > 0) {
     st = build_packed(A, pp, mid_t, base, P, ws_bytes, s);
     if (st != ISP_OK) { delete A; return st; }

@@ -236,6 +236,37 @@ struct g_bwd_col {  // over A^T: gathered x_i and g_i, row operand x_j:  dX_j +=
   }
 };
 
+// Backward in ONE pass over A when A^T's structure equals A's (symmetric pattern, ascending rows): entry p of
+// row i names neighbour j, and position p of A^T holds the mirrored entry (j, i) with value a_ji.  Both sums of
+// the backward then run over the same neighbours, and x_j and g_j are gathered once for both:
+//   dX_i = sum_j (dz_ij + dz_ji) x_j + a_ji s g_j,   dz_ij = a_ij <g_i, x_j> f'(z),  dz_ji = a_ji <g_j, x_i> f'(z),
+// z = <x_i, x_j> being the same for (i, j) and (j, i).  Two gathered rows per entry instead of three, one sweep
+// over the index arrays instead of two.
+struct g_args22 { const float* src[2]; int64_t lds_[2]; const float* rowop[2]; int64_t ldr[2]; float* out_entry; int op; const float* val2; };
+
+template <int OP>
+struct g_bwd_mirror {  // gathered x_j and g_j, row operands x_i and g_i
+  static constexpr int NSRC = 2, NROW = 2, STEPS = 2;
+  static constexpr bool PER_ENTRY = false, ACCUMULATE = false, HAS_VAL2 = true;
+  using args = g_args22;
+  template <int LPG>
+  __device__ static inline void edge(const args&, float a, float at, const float (&x)[2][4], const float (&r)[2][4],
+                                     float (&acc)[4], bool lane_on, bool live) {
+    float sg = 1.f, dsg = 0.f, gd_ij = 0.f, gd_ji = 0.f;
+    if (OP != ISP_OP_ONE) {
+      edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0], lane_on)), sg, dsg);
+      gd_ij = group_allreduce<LPG>(dot4(r[1], x[0], lane_on));  // <g_i, x_j>
+      gd_ji = group_allreduce<LPG>(dot4(x[1], r[0], lane_on));  // <g_j, x_i>
+    }
+    const float w = at * sg;
+    const float dz = (a * gd_ij + at * gd_ji) * dsg;
+    if (live) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
+    }
+  }
+};
+
 template <class P, int LPG, bool ADDR32>
 __global__ void __launch_bounds__(ISP_WG) k_fused_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                           const int32_t* __restrict__ indices,
@@ -364,6 +395,13 @@ isp_status isp_fusedmm_bwd_launch(const isp_csr* A, const float* X, int64_t ldx,
                                   int32_t d, int op, float* dX, int64_t lddx, hipStream_t s) {
   const bool ok4 = ldx % 4 == 0 && ldg % 4 == 0 && lddx % 4 == 0 && aligned(X, 16) && aligned(G, 16) && aligned(dX, 16);
   const bool ok2 = ldx % 2 == 0 && ldg % 2 == 0 && lddx % 2 == 0 && aligned(X, 8) && aligned(G, 8) && aligned(dX, 8);
+  if (ok4 && d % 4 == 0 && d <= ISP_PARTIAL_TILE && grouped_partition_ok(A) && A->mirror_aligned && !A->tune.no_mirror) {
+    // symmetric pattern: one pass over A serves both sums (the mirrored entries' values are A^T's)
+    g_args22 pm{{X, G}, {ldx, ldg}, {X, G}, {ldx, ldg}, nullptr, op, A->At->v.values};
+    if (op == ISP_OP_SIGMOID) return run_grouped_d<g_bwd_mirror<ISP_OP_SIGMOID>>(A, pm, d, dX, lddx, s);
+    if (op == ISP_OP_DOT) return run_grouped_d<g_bwd_mirror<ISP_OP_DOT>>(A, pm, d, dX, lddx, s);
+    return run_grouped_d<g_bwd_mirror<ISP_OP_ONE>>(A, pm, d, dX, lddx, s);
+  }
   if (ok4 && d % 4 == 0 && d <= ISP_PARTIAL_TILE && grouped_partition_ok(A) && grouped_partition_ok(A->At)) {
     g_args12 p1{{X}, {ldx}, {X, G}, {ldx, ldg}, nullptr, op};
     g_args21 p2{{X, G}, {ldx, ldg}, {X}, {ldx}, nullptr, op};

@@ -16,10 +16,17 @@ namespace isp_dev {
 // args { src[NSRC], lds_[NSRC], rowop[NROW], ldr[NROW], out_entry };
 // either edge<LPG>(args, a, src, rowop, acc, lane_on, live) accumulating into the row's result in live
 // lanes, or (PER_ENTRY) entry<LPG>(a, src, rowop, lane_on) returning the value stored for the entry.
+// A policy with HAS_VAL2 = true also gets a second value per stored entry, args::val2[p] (a parallel array in
+// the order of the matrix's entries; null = all ones), as an extra argument of edge().
 // ADDR32: every byte offset into the gathered operands fits 32 bits and both factors of column * row pitch
 // fit 24 bits (fused_offsets_fit_32 below), so a gather address is one full-rate 24-bit multiply-add on a
 // scalar base pointer instead of a 64-bit multiply (three quarter-rate instructions).
 // values may be null (every stored value is 1).
+template <class P, class = void>
+struct policy_has_val2 : std::false_type {};
+template <class P>
+struct policy_has_val2<P, std::void_t<decltype(P::HAS_VAL2)>> : std::bool_constant<P::HAS_VAL2> {};
+
 template <class P, int LPG, bool ADDR32>
 __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                           const int32_t* __restrict__ indices, const float* __restrict__ values,
@@ -96,7 +103,8 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
 #pragma unroll
       for (int k = 0; k < NROW; ++k) load_vec<4>(pa.rowop[k] + (int64_t)it.src_row * pa.ldr[k] + coff, rS[k]);
     }
-    auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][NSRC][4], float (&r)[U][NR + 1][4], float (&a)[U]) {
+    auto issue = [&](int s0, unsigned (&dsc)[U], float (&x)[U][NSRC][4], float (&r)[U][NR + 1][4], float (&a)[U],
+                     float (&a2)[U]) {
       int2 e[U];
       int srow[U];
 #pragma unroll
@@ -113,6 +121,11 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
         const bool act = g < gs_cnt(dsc[u]) && lane_on;
         a[u] = __int_as_float(e[u].y);
         const int cj = act ? e[u].x : 0;  // dead lanes gather row 0; what they fetch is never used
+        if constexpr (policy_has_val2<P>::value) {
+          // (a dead lane reads the step's first entry, or the item's first one in a null step: valid positions)
+          a2[u] = 1.f;
+          if (pa.val2) a2[u] = pa.val2[it.p + gs_off(dsc[u]) + (g < gs_cnt(dsc[u]) ? g : 0)];
+        }
 #pragma unroll
         for (int k = 0; k < NSRC; ++k) {
           if constexpr (ADDR32) {
@@ -130,7 +143,7 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
       }
     };
     auto consume = [&](const unsigned (&dsc)[U], const float (&x)[U][NSRC][4], const float (&r)[U][NR + 1][4],
-                       const float (&a)[U]) {
+                       const float (&a)[U], const float (&a2)[U]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         // The policies mask the per-lane partial dot products with lane_on (columns past d) and
@@ -147,7 +160,8 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
           const float val = P::template entry<LPG>(a[u], x[u], rr, lane_on);
           if (live && q == 0) L.ent[gs_off(dsc[u]) + g].y = __float_as_int(val);
         } else {
-          P::template edge<LPG>(pa, a[u], x[u], rr, acc, lane_on, live && lane_on);
+          if constexpr (policy_has_val2<P>::value) P::template edge<LPG>(pa, a[u], a2[u], x[u], rr, acc, lane_on, live && lane_on);
+          else P::template edge<LPG>(pa, a[u], x[u], rr, acc, lane_on, live && lane_on);
           if (dsc[u] & GS_LAST) finish_row();
         }
       }
@@ -156,21 +170,22 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
     const int n_groups = n_steps / U;
     unsigned dA[U], dB[U];
     float xA[U][NSRC][4], xB[U][NSRC][4], rA[U][NR + 1][4], rB[U][NR + 1][4], aA[U], aB[U];
-    issue(0, dA, xA, rA, aA);
+    float a2A[U], a2B[U];  // (unused, and optimised away, unless the policy takes a second value)
+    issue(0, dA, xA, rA, aA, a2A);
     int gi = 0;
     while (gi + 2 < n_groups) {
-      issue((gi + 1) * U, dB, xB, rB, aB);
-      consume(dA, xA, rA, aA);
-      issue((gi + 2) * U, dA, xA, rA, aA);
-      consume(dB, xB, rB, aB);
+      issue((gi + 1) * U, dB, xB, rB, aB, a2B);
+      consume(dA, xA, rA, aA, a2A);
+      issue((gi + 2) * U, dA, xA, rA, aA, a2A);
+      consume(dB, xB, rB, aB, a2B);
       gi += 2;
     }
     if (gi + 1 < n_groups) {
-      issue((gi + 1) * U, dB, xB, rB, aB);
-      consume(dA, xA, rA, aA);
-      consume(dB, xB, rB, aB);
+      issue((gi + 1) * U, dB, xB, rB, aB, a2B);
+      consume(dA, xA, rA, aA, a2A);
+      consume(dB, xB, rB, aB, a2B);
     } else {
-      consume(dA, xA, rA, aA);
+      consume(dA, xA, rA, aA, a2A);
     }
   };
   if (n_steps == 0) return;

@@ -50,6 +50,7 @@ struct isp_tuning {
   bool sddmm_one_pass;  // ISP_SDDMM_ONE_PASS: SDDMM never splits 128-column rows into two 64-column passes
   int spmm_lpg;         // ISP_SPMM_LPG: lanes per group of the grouped SpMM (0 = chosen by shape)
   int spmm_tile;        // ISP_SPMM_TILE: feature columns per launch of the grouped SpMM (0 = chosen by shape)
+  bool no_mirror;       // ISP_NO_MIRROR: the FusedMM backward never takes the one-pass form of symmetric patterns
   int wide_groups;      // ISP_WIDE_GROUPS: most column groups a hub segment stores per launch of a wide FusedMM pass (0 = as many as fit)
 };
 isp_tuning isp_read_tuning();
@@ -82,6 +83,9 @@ struct isp_csr {
   int device;
   isp_csr* At;             // cached transpose (owned), or NULL
   bool is_transpose;
+  bool mirror_aligned;     // set with the cached transpose: A^T's offsets and indices equal A's own element for
+                           // element (a symmetric pattern, rows ascending), so entry p of A^T is the mirror of
+                           // entry p of A and one pass over A can serve both
 };
 
 // ---- error plumbing --------------------------------------------------------------------------

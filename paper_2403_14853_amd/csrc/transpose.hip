@@ -238,6 +238,25 @@ __global__ void __launch_bounds__(256) k_inverse_perm(const int32_t* __restrict_
   if (q < nnz) inv_perm[perm[q]] = (int32_t)q;
 }
 
+// *differs becomes 1 when A^T's offsets and indices are not, element for element, A's own: otherwise the pattern
+// is symmetric with every row's columns ascending, and entry p of A^T is the mirror (j, i) of entry p = (i, j)
+// of A.  (*differs is zeroed before.)
+__global__ void __launch_bounds__(256) k_compare_pattern(const int64_t* __restrict__ indptr, const int64_t* __restrict__ t_indptr,
+                                                         int64_t n, const int32_t* __restrict__ indices,
+                                                         const int32_t* __restrict__ t_indices, int64_t nnz,
+                                                         int* __restrict__ differs) {
+  bool bad = false;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz + n + 1; i += (int64_t)gridDim.x * blockDim.x) {
+    if (i < nnz) bad |= indices[i] != t_indices[i];
+    else bad |= indptr[i - nnz] != t_indptr[i - nnz];
+  }
+  if (__any(bad) && (threadIdx.x & (ISP_WAVE - 1)) == 0) *differs = 1;  // (plain store of the same value from any wave)
+}
+
+__global__ void k_zero_int(int* p) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0;
+}
+
 __global__ void __launch_bounds__(256) k_fill_i64(int64_t* __restrict__ a, int64_t n, int64_t v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) a[i] = v;
@@ -333,10 +352,27 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
     k_col_offsets<<<(unsigned)((nnz + 255) / 256), 256, 0, s>>>(in[0], nnz, n_cols, t_indptr);
     ISP_LAUNCH_CHECK();
   }
+  // Is the pattern symmetric (A^T's structure identical to A's)?  The flag lives in the sort's histogram table,
+  // which is free by now, and is read back with the counters of the partition build below.
+  int* differs = (int*)table;
+  const bool square = n_rows == n_cols && nnz > 0;
+  if (square) {
+    k_zero_int<<<1, 64, 0, s>>>(differs);
+    ISP_LAUNCH_CHECK();
+    k_compare_pattern<<<2048, 256, 0, s>>>(v.indptr, t_indptr, n_rows, v.indices, t_indices, nnz, differs);
+    ISP_LAUNCH_CHECK();
+  }
   isp_csr* At = nullptr;
   isp_status st = isp_build_handle(n_cols, n_rows, nnz, t_indptr, t_indices, t_values, base + L.part,
                                    ws_bytes - L.part, false, s, &At);
   if (st != ISP_OK) return st;
+  int h_differs = 1;
+  if (square) {
+    ISP_HIP(hipMemcpyAsync(&h_differs, differs, sizeof(int), hipMemcpyDeviceToHost, s));
+    ISP_HIP(hipStreamSynchronize(s));
+  }
+  A->mirror_aligned = At->mirror_aligned = (h_differs == 0);
+  A->info.symmetric_pattern = At->info.symmetric_pattern = A->mirror_aligned ? 1 : 0;
   At->tune = A->tune;  // (resolved when A was built)
   At->perm = perm;
   At->t_values_rw = t_values;

@@ -570,3 +570,54 @@ def test_c_abi_consumer_without_python():
     res = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=100)
     print(res.stdout)
     assert res.returncode == 0 and res.stdout.startswith("OK"), res.stdout
+
+
+@pytest.mark.parametrize("d", [4, 32, 64, 100, 128, 256])
+def test_fusedmm_backward_one_pass_on_a_symmetric_pattern(small_partition, d):
+    """A symmetric pattern with ascending rows makes A^T's structure equal to A's, and the backward runs as one
+    pass over A with the mirrored entries' values taken from A^T.  The values here are NOT symmetric, so a
+    wrong pairing of (i, j) with (j, i) shows; the two-pass form (ISP_NO_MIRROR) must agree with the oracle too,
+    and a directed graph must not take the one-pass form."""
+    w = graphgen.make_config(1, shrink=128)  # symmetrised R-MAT with self-loops, rows ascending
+    rng = np.random.default_rng(d)
+    values = rng.standard_normal(w.nnz).astype(np.float32)
+    X = (0.3 * rng.standard_normal((w.n, d))).astype(np.float32)
+    G = rng.standard_normal((w.n, d)).astype(np.float32)
+    for mirror in (True, False):
+        os.environ.pop("ISP_NO_MIRROR", None)
+        if not mirror:
+            os.environ["ISP_NO_MIRROR"] = "1"
+        try:
+            for vals in (values, None):
+                A = build(w.indptr, w.indices, vals)
+                assert A.info()["symmetric_pattern"] == 0  # not known before the transpose exists
+                isp.csr_transpose_cached(A)
+                assert A.info()["symmetric_pattern"] == 1
+                for op in ("sigmoid", "dot", "one"):
+                    dX = torch.full((w.n, d), float("nan"), device="cuda")
+                    isp.fusedmm_backward(A, dev(X), dev(G), dX, op=op)
+                    assert_close(dX, *oracle.fusedmm_backward(w.indptr, w.indices, vals, X, G, op=op),
+                                 "fusedmm backward %s d=%d mirror=%s" % (op, d, mirror))
+                    dX2 = torch.empty_like(dX)
+                    isp.fusedmm_backward(A, dev(X), dev(G), dX2, op=op)
+                    assert torch.equal(dX, dX2)
+                A.destroy()
+        finally:
+            os.environ.pop("ISP_NO_MIRROR", None)
+    w0 = graphgen.make_config(0)  # directed
+    A = build(w0.indptr, w0.indices, w0.values)
+    isp.csr_transpose_cached(A)
+    assert A.info()["symmetric_pattern"] == 0
+    A.destroy()
+    # a symmetric pattern whose rows are not ascending is not recognised (and still computed correctly)
+    indptr, indices = w.indptr, w.indices.copy()
+    for i in range(w.n):
+        s, e = indptr[i], indptr[i + 1]
+        indices[s:e] = indices[s:e][::-1]
+    A = build(indptr, indices, None)
+    isp.csr_transpose_cached(A)
+    assert A.info()["symmetric_pattern"] == (1 if np.array_equal(indices, w.indices) else 0)
+    dX = torch.full((w.n, d), float("nan"), device="cuda")
+    isp.fusedmm_backward(A, dev(X), dev(G), dX)
+    assert_close(dX, *oracle.fusedmm_backward(indptr, indices, None, X, G), "fusedmm backward, descending rows")
+    A.destroy()
