@@ -53,6 +53,10 @@ def main():
     ap.add_argument("--flushed", action="store_true",
                     help="instead of the benchmark line: per-op time when a 1 GiB copy has swept L2 and the "
                          "Infinity Cache before every op (the small workloads otherwise run cache-warm)")
+    ap.add_argument("--split-rows", type=int, default=0, metavar="T",
+                    help="instead of the benchmark line: SpMM forward on the two sub-matrices made of the rows with at "
+                         "most T stored entries and of the longer rows (the other rows left empty), each timed alone: "
+                         "where a launch on the whole matrix spends its time")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="(kept for older command lines: plain device copies of X, the known-size kernel that "
                          "scales rocprofv3 FETCH_SIZE / WRITE_SIZE readings, now always run before the timed region)")
@@ -100,6 +104,9 @@ def main():
         return
     if args.sweep_d:
         print(json.dumps(sweep_d(isp, w, A)))
+        return
+    if args.split_rows > 0:
+        print(json.dumps(split_rows(isp, w, X, args.split_rows, max(3, args.steps // 4))))
         return
     if args.reductions:
         print(json.dumps(reductions(isp, w, A, X, dY)))
@@ -361,6 +368,39 @@ def sweep_d(isp, w, A, widths=SWEEP_WIDTHS):
         del X, Y
     return {"what": "SpMM forward vs feature width; requested_GBps = nnz * (8 + 4 d) bytes over time (every entry "
                     "fetching its own row)", "workload": w.name, "nnz": w.nnz, "sweep": out}
+
+
+def split_rows(isp, w, X, T, reps):
+    """SpMM forward on the rows of at most T entries and on the longer rows, each class as a matrix of its own
+    (those rows only, all columns), through the library as it is.  The launch on the whole matrix processes the
+    two classes one after the other, so the two times say where it goes."""
+    import numpy as np
+    import torch
+    deg = np.diff(w.indptr)
+    rows = np.repeat(np.arange(w.n), deg)
+    out = []
+    for name, keep_row in (("rows <= %d" % T, deg <= T), ("rows > %d" % T, deg > T)):
+        keep = keep_row[rows]
+        n_sub = int(keep_row.sum())
+        ip = np.zeros(n_sub + 1, dtype=np.int64)
+        np.cumsum(deg[keep_row], out=ip[1:])
+        vals = None if w.values is None else torch.from_numpy(w.values[keep]).cuda()
+        H = isp.csr_build(torch.from_numpy(ip).cuda(), torch.from_numpy(w.indices[keep]).cuda(), vals, n_cols=w.n)
+        Y = torch.empty(n_sub, w.d, device="cuda")
+        isp.spmm(H, X, Y)
+        isp.spmm(H, X, Y)
+        ms = _time_ms(lambda: isp.spmm(H, X, Y), reps)
+        nz = int(keep.sum())
+        info = H.info()
+        out.append({"class": name, "rows": n_sub, "entries": nz, "ms": round(ms, 4),
+                    "ps_per_entry": round(ms * 1e9 / max(nz, 1), 1), "spmm_pieces": info["spmm_pieces"],
+                    "work_items": info["spmm_row_blocks"] or info["n_row_blocks"] + info["n_segments"]})
+        torch.cuda.synchronize()
+        H.destroy()
+        del Y
+    return {"what": "SpMM forward on the short rows alone and on the long rows alone, each class as a matrix of its own "
+                    "(launch order: class 1, then class 2; two warm-up launches each, then %d timed)" % reps,
+            "workload": w.name, "d": w.d, "classes": out}
 
 
 def gcn_step(w, indptr, indices, values, X):

@@ -584,12 +584,14 @@ packed_layout make_packed_layout(int64_t n_rows, int64_t nnz, bool has_values, c
 // hub segments do.  ISP_MID_THRESHOLD overrides (0 disables).
 // The layout costs workspace - a second copy of the entries, their source positions and one partial row per
 // piece: up to about 36 bytes per stored entry - so beyond 256 Mi entries it is left out as well.
-int mid_threshold(int64_t n_cols, int64_t nnz, const partition_params& p1) {
+int mid_threshold(int64_t n_rows, int64_t n_cols, int64_t nnz, const partition_params& p1) {
   const int dflt = (nnz >= ((int64_t)8 << 20) && nnz <= ((int64_t)256 << 20) && n_cols >= (1 << 19)) ? 256 : 0;
   int t = env_int("ISP_MID_THRESHOLD", dflt, 0, 512);
   if (t > 0 && t < 8) t = 8;
   // the derived matrix's rows (short rows, pieces) must fit the grouped kernels' tables next to a block
   if (t > 0 && (p1.block_cost + (t > p1.seg_len ? t : p1.seg_len) > 768)) t = 0;
+  // ... and its rows (the matrix's rows plus one per piece) must stay countable in 32 bits
+  if (t > 0 && n_rows + make_layout(n_rows, nnz, cut_params(p1, t)).max_seg >= 2147483646) t = 0;
   return t;
 }
 
@@ -777,7 +779,7 @@ isp_status build_packed(isp_csr* A, const partition_params& p1, int mid_t, char*
 size_t isp_partition_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz) {
   const partition_params p1 = get_params(n_rows, n_cols, nnz);
   const ws_layout L = make_layout(n_rows, nnz, p1);
-  const int mid_t = mid_threshold(n_cols, nnz, p1);
+  const int mid_t = mid_threshold(n_rows, n_cols, nnz, p1);
   if (mid_t == 0) return L.total;
   return make_packed_layout(n_rows, nnz, true, p1, mid_t, L.total).total;
 }
@@ -795,7 +797,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
                             hipStream_t s, isp_csr** out) {
   const partition_params pp = get_params(n_rows, n_cols, nnz);
   const ws_layout L = make_layout(n_rows, nnz, pp);
-  const int mid_t = mid_threshold(n_cols, nnz, pp);
+  const int mid_t = mid_threshold(n_rows, n_cols, nnz, pp);
   packed_layout P{};
   size_t need = L.total;
   if (mid_t > 0) {
