@@ -57,6 +57,10 @@ def main():
                     help="instead of the benchmark line: SpMM forward on the two sub-matrices made of the rows with at "
                          "most T stored entries and of the longer rows (the other rows left empty), each timed alone: "
                          "where a launch on the whole matrix spends its time")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the benchmark line: what this box's memory system delivers to this access pattern - "
+                         "a plain device copy and the library's SpMM on uniform random graphs whose dense operand has a "
+                         "footprint of 2 MB ... 1.25 GB (requested gather bytes over time)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="(kept for older command lines: plain device copies of X, the known-size kernel that "
                          "scales rocprofv3 FETCH_SIZE / WRITE_SIZE readings, now always run before the timed region)")
@@ -73,6 +77,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     isp.load_library()  # fails loudly when the HIP library is missing
+    if args.ceilings:
+        print(json.dumps(ceilings(isp)))
+        return
     t0 = time.time()
     w = graphgen.make_config(args.config, shrink=args.shrink, relabel=not args.no_relabel)
     gen_s = time.time() - t0
@@ -368,6 +375,45 @@ def sweep_d(isp, w, A, widths=SWEEP_WIDTHS):
         del X, Y
     return {"what": "SpMM forward vs feature width; requested_GBps = nnz * (8 + 4 d) bytes over time (every entry "
                     "fetching its own row)", "workload": w.name, "nnz": w.nnz, "sweep": out}
+
+
+def ceilings(isp):
+    """Memory-system ceilings as this path sees them.  (a) A plain device copy (bytes read + written over time).
+    (b) The library's SpMM at d = 128 on uniform random graphs (every row 64 random columns, 16 Mi entries)
+    whose dense operand X has n_cols rows of 512 bytes: with no skew to exploit, the requested gather bytes
+    over time are what random 512-byte row gathers get from wherever a table of that size lives (an XCD's
+    4 MB L2, the 256 MB Infinity Cache, HBM)."""
+    import numpy as np
+    import torch
+    out = {"what": "copy and random-row-gather rates by footprint", "copy": [], "gather": []}
+    for mb in (8, 64, 256, 1280, 4096):
+        n = mb * (1 << 20) // 4
+        src = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        ms = _time_ms(lambda: dst.copy_(src), 20 if mb <= 256 else 5)
+        out["copy"].append({"MB_each_way": mb, "ms": round(ms, 4), "GBps_read_plus_written": round(2.0 * n * 4 / ms / 1e6, 1)})
+        del src, dst
+    d, deg, n_rows = 128, 64, 1 << 18
+    rng = np.random.default_rng(0)
+    for mb in (2, 8, 32, 128, 512, 1280):
+        n_cols = mb * (1 << 20) // (4 * d)
+        cols = np.sort(rng.integers(0, n_cols, size=(n_rows, deg), dtype=np.int64), axis=1).astype(np.int32).reshape(-1)
+        indptr = (np.arange(n_rows + 1, dtype=np.int64) * deg)
+        A = isp.csr_build(torch.from_numpy(indptr).cuda(), torch.from_numpy(cols).cuda(), None, n_cols=n_cols)
+        X = torch.randn(n_cols, d, device="cuda")
+        Y = torch.empty(n_rows, d, device="cuda")
+        isp.spmm(A, X, Y)
+        isp.spmm(A, X, Y)
+        ms = _time_ms(lambda: isp.spmm(A, X, Y), 10)
+        nnz = n_rows * deg
+        out["gather"].append({"X_MB": mb, "columns": n_cols, "entries": nnz, "ms": round(ms, 4),
+                              "requested_GBps": round(nnz * 4.0 * d / ms / 1e6, 1),
+                              "ps_per_entry": round(ms * 1e9 / nnz, 1)})
+        torch.cuda.synchronize()
+        A.destroy()
+        del X, Y
+    return out
 
 
 def split_rows(isp, w, X, T, reps):
