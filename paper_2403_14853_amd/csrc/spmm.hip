@@ -110,6 +110,14 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const bool pieces = !it.is_seg && (int64_t)it.row >= A.n_real_rows;
   const bool to_partial = it.is_seg || pieces;
   const int32_t* __restrict__ slot_of = A.piece_slot - (pieces ? A.n_real_rows : 0);  // indexed by the piece's row
+  // The block's partial-row numbers are fetched up front, one per lane (a block holds at most 129 pieces: each
+  // costs at least 2 of the 256 units), so that a row end does not wait for a load of its own.
+  int slot_lo = 0, slot_hi = 0;
+  if (pieces) {
+    const int n_pc = it.row_last - it.row;
+    if (lane < n_pc) slot_lo = slot_of[it.row + lane];
+    if (lane + ISP_WAVE < n_pc) slot_hi = slot_of[it.row + lane + ISP_WAVE];
+  }
   float* __restrict__ out = to_partial ? A.partials + (col - k_base) : Y + col;
   const int64_t ldo = to_partial ? (int64_t)ISP_PARTIAL_TILE : ldy;
   float acc[VEC];
@@ -129,7 +137,11 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   auto finish_row = [&]() {
     const int r_local = __builtin_amdgcn_readfirstlane(r_next);  // (wave-uniform: scalar address math)
     int row = it.row + r_local;
-    if (pieces) row = __builtin_amdgcn_readfirstlane(slot_of[row]);  // (wave-uniform address: one scalar load)
+    if (pieces) {  // the piece's partial row: from the lanes that fetched it, beyond 128 pieces by a load
+      if (r_local < ISP_WAVE) row = __builtin_amdgcn_readlane(slot_lo, r_local);
+      else if (r_local < 2 * ISP_WAVE) row = __builtin_amdgcn_readlane(slot_hi, r_local - ISP_WAVE);
+      else row = __builtin_amdgcn_readfirstlane(slot_of[row]);
+    }
     ++k_done;
     r_next = listed ? (int)L.ss[k_done] : k_done;
 #pragma unroll
