@@ -33,7 +33,8 @@
  *   - Results are run-to-run bitwise deterministic: no floating-point atomics are used.
  *   - Environment variables (tuning and tests only; none is needed).  All are read when isp_csr_build runs and
  *     are kept in the handle (a cached transpose inherits its source's); no compute call reads the environment.
- *       ISP_BLOCK_COST, ISP_HUB_THRESHOLD, ISP_SEGMENT_LEN, ISP_BANDS, ISP_MIN_PIECE, ISP_MID_THRESHOLD:
+ *       ISP_BLOCK_COST, ISP_HUB_THRESHOLD, ISP_SEGMENT_LEN, ISP_BANDS, ISP_MIN_PIECE, ISP_MID_THRESHOLD,
+ *       ISP_PACKED_BLOCK:
  *                              sizes of the work partition (clamped to what the kernels' tables hold)
  *       ISP_NO_GROUPED         run every operation on the general kernels
  *       ISP_SPMM_LPG, ISP_SPMM_TILE   lanes per group / feature columns per launch of the tuned SpMM

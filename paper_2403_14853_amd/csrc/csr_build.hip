@@ -27,6 +27,7 @@ struct build_counters {
 
 struct partition_params {
   int block_cost, hub_t, seg_len;
+  int row_cost;   // cost units of a row besides its entries (1; 2 in the derived matrix, which allows larger blocks)
   int bands;      // column bands of the finest cut (a power of two); 1 = no band cuts
   int min_piece;  // a hub row is cut into at most degree / min_piece bands
 };
@@ -44,6 +45,7 @@ int env_int(const char* name, int dflt, int lo, int hi) {
 
 partition_params get_params(int64_t n_rows, int64_t n_cols, int64_t nnz) {
   partition_params p;
+  p.row_cost = 1;
   const int64_t slots = isp_wave_slots();  // 4,096 on an MI355X (256 compute units)
   // Upper limits = what the grouped kernels' per-wave LDS tables hold (block_cost + hub_t <= 768
   // entries, block_cost <= 256 rows, seg_len <= 768 entries).  The environment overrides exist for
@@ -195,7 +197,7 @@ __global__ void __launch_bounds__(256) k_row_pass(const int64_t* __restrict__ in
       if (lane == src) ns = cnt;
     }
     if (!valid) continue;
-    cost[i] = hub ? 0 : (int32_t)deg + 1;
+    cost[i] = hub ? 0 : (int32_t)deg + pp.row_cost;
     hubflag[i] = hub ? 1 : 0;
     nseg[i] = ns;
     inv_len[i] = deg > 0 ? 1.f / (float)deg : 0.f;
@@ -491,7 +493,7 @@ ws_layout make_layout(int64_t n_rows, int64_t nnz, const partition_params& pp, s
   ws_layout L;
   size_t off = start;
   auto take = [&](size_t bytes) { size_t o = off; off += isp_align(bytes); return o; };
-  const int64_t n_bal = (nnz + n_rows) / pp.block_cost + 2;
+  const int64_t n_bal = (nnz + (int64_t)pp.row_cost * n_rows) / pp.block_cost + 2;
   int64_t max_hub = nnz / ((int64_t)pp.hub_t + 1);
   if (max_hub > n_rows) max_hub = n_rows;
   int64_t max_blocks = n_bal + 2 * max_hub + 3;
@@ -539,9 +541,26 @@ struct packed_layout {
   size_t total;
 };
 
+// Block cost of the derived matrix.  Its rows cost two units besides their entries, so a block of B units holds
+// at most B / 2 rows and B may reach twice the ordinary 256 within the kernels' 256-row tables; its entries
+// (fewer than B plus the longest row) must fit their 768-entry tables.
+// One and a half times the ordinary block where the longest row leaves room for it (config 3: 384 units next to
+// rows of up to 384 entries; measured 4.75 ms per SpMM against 4.81 at 256 and 4.76 at 512, where the segments
+// have to shrink to 256 entries): every work item starts with a chain of dependent loads before its first
+// gather, and fewer, larger items pay it less often.
+int derived_block_cost(const partition_params& p1, int mid_t) {
+  const int longest = mid_t > p1.seg_len ? mid_t : p1.seg_len;
+  int dflt = p1.block_cost * 3 / 2;
+  if (dflt > 768 - longest) dflt = 768 - longest;
+  if (dflt < 16) dflt = 16;
+  return env_int("ISP_PACKED_BLOCK", dflt, 16, 512);
+}
+
 partition_params cut_params(const partition_params& p1, int mid_t) {
   partition_params c = p1;
   c.hub_t = mid_t;
+  const int room = 768 - derived_block_cost(p1, mid_t);  // longest row the derived matrix may have
+  if (c.seg_len > room) c.seg_len = room;
   // pieces of 64 entries or more, on up to 32 bands (measured on 2.4 M columns: smaller pieces fetch less but
   // pay it back in partial rows)
   c.min_piece = env_int("ISP_MIN_PIECE", 64, c.seg_len / 8 > 4 ? c.seg_len / 8 : 4, 1 << 20);
@@ -553,6 +572,8 @@ partition_params derived_params(const partition_params& p1, const partition_para
   d.hub_t = cut.hub_t > cut.seg_len ? cut.hub_t : cut.seg_len;  // no row of the derived matrix is longer
   d.seg_len = d.hub_t;
   d.bands = 1;
+  d.row_cost = 2;
+  d.block_cost = derived_block_cost(p1, cut.hub_t);
   return d;
 }
 
@@ -589,7 +610,10 @@ int mid_threshold(int64_t n_rows, int64_t n_cols, int64_t nnz, const partition_p
   int t = env_int("ISP_MID_THRESHOLD", dflt, 0, 512);
   if (t > 0 && t < 8) t = 8;
   // the derived matrix's rows (short rows, pieces) must fit the grouped kernels' tables next to a block
-  if (t > 0 && (p1.block_cost + (t > p1.seg_len ? t : p1.seg_len) > 768)) t = 0;
+  if (t > 0) {
+    const partition_params c = cut_params(p1, t), dd = derived_params(p1, c);
+    if (c.seg_len < 8 || dd.block_cost + dd.hub_t > 768 || dd.block_cost / dd.row_cost > 256) t = 0;
+  }
   // ... and its rows (the matrix's rows plus one per piece) must stay countable in 32 bits
   if (t > 0 && n_rows + make_layout(n_rows, nnz, cut_params(p1, t)).max_seg >= 2147483646) t = 0;
   return t;
@@ -645,7 +669,7 @@ isp_status build_partition(int64_t n_rows, int64_t n_cols, int64_t nnz, const in
     k_mark_rows<<<row_grid, 256, 0, s>>>(hubflag, n_rows, force_row, mark);
     ISP_LAUNCH_CHECK();
     // total short-row cost <= nnz + n_rows, so this many targets cover it
-    const int64_t n_bal = (nnz + n_rows) / pp.block_cost + 1;
+    const int64_t n_bal = (nnz + (int64_t)pp.row_cost * n_rows) / pp.block_cost + 1;
     k_mark_balanced<<<(unsigned)((n_bal + 255) / 256), 256, 0, s>>>(cum_cost, n_rows, n_bal, pp.block_cost, mark);
     ISP_LAUNCH_CHECK();
   }
@@ -765,6 +789,8 @@ isp_status build_packed(isp_csr* A, const partition_params& p1, int mid_t, char*
   vp.n_real_rows = n;
   vp.piece_slot = cut.seg_order;
   A->has_packed = true;
+  A->packed_block_cost = pd.block_cost;
+  A->packed_row_cost = pd.row_cost;
   A->packed_values_rw = values2;
   A->packed_src_pos = src_pos;
   A->info.spmm_mid_threshold = mid_t;

@@ -66,6 +66,7 @@ struct isp_csr {
   isp_view vp;
   int64_t partial_rows;           // partial rows (ISP_PARTIAL_TILE floats each) v.partials has room for
   bool has_packed;
+  int packed_block_cost, packed_row_cost;  // of vp's partition (bounds of its blocks: see csr_build.hip)
   float* packed_values_rw;        // vp.values, writable, NULL without values
   const int32_t* packed_src_pos;  // position in v's arrays of every entry of the derived matrix
   isp_tuning tune;

@@ -220,7 +220,8 @@ isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, 
                           int64_t ldy, int mean_mode, const float* values_override, hipStream_t s) {
   // The packed layout (a derived matrix in which the pieces of long rows share work items) when the handle has
   // one; an override of the values is in the order of A's own entries and therefore runs on A's own partition.
-  const bool packed = A->has_packed && !values_override && A->info.block_cost + A->vp.hub_t <= GS_MAX_ENT;
+  const bool packed = A->has_packed && !values_override && A->packed_block_cost + A->vp.hub_t <= GS_MAX_ENT &&
+                      A->packed_block_cost / A->packed_row_cost <= GS_MAX_ROWS;
   const isp_view& v = packed ? A->vp : A->v;
   const float* vals = values_override ? values_override : v.values;  // (one value per stored entry, the view's order)
   const int n_items = v.n_blocks + v.n_seg;
