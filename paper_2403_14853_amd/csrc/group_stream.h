@@ -79,12 +79,27 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   gs_u16* __restrict__ rp = L.rp;
   gs_u16* __restrict__ ss = L.ss;
   const int n_ent = (int)(it.p_end - it.p);
-  for (int i = lane; i < n_ent; i += ISP_WAVE) {
-    int2 e;
-    e.x = __builtin_nontemporal_load(indices + it.p + i);
-    const float val = HAS_VAL ? __builtin_nontemporal_load(values + it.p + i) : 1.f;
-    e.y = __float_as_int(val);
-    ent[i] = e;
+  // Eight loads per lane are issued before the first is stored: the item's entries arrive in one or two round
+  // trips to memory instead of one per 64 entries (nothing else of the item can start before they are here).
+  constexpr int SB = 8;
+  for (int base = 0; base < n_ent; base += SB * ISP_WAVE) {
+    int c[SB];
+    float v[SB];
+#pragma unroll
+    for (int u = 0; u < SB; ++u) {
+      const int i = base + u * ISP_WAVE + lane;
+      c[u] = 0;
+      v[u] = 1.f;
+      if (i < n_ent) {
+        c[u] = __builtin_nontemporal_load(indices + it.p + i);
+        if (HAS_VAL) v[u] = __builtin_nontemporal_load(values + it.p + i);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < SB; ++u) {
+      const int i = base + u * ISP_WAVE + lane;
+      if (i < n_ent) ent[i] = make_int2(c[u], __float_as_int(v[u]));
+    }
   }
   const int n_rows = it.row_last - it.row;
   if (it.is_seg) {
