@@ -74,3 +74,14 @@ def test_traffic_comes_from_the_tracked_counter_records(repo_root):
     rec = bench.counter_record("c3-rmat2.4m-d128", "k_spmm_grouped")
     assert rec and rec["bytes"] > 0 and rec["commit"]
     assert "35.42e9" not in open(os.path.join(repo_root, "bench.py")).read()
+
+
+def test_split_rows_mode_on_a_shrunk_graph(repo_root):
+    """Where a launch spends its time: the two row classes as matrices of their own cover every row and entry."""
+    j = _bench_json(repo_root, "--config", "1", "--shrink", "4", "--split-rows", "64")
+    a, b = j["classes"]
+    assert a["class"] == "rows <= 64" and b["class"] == "rows > 64"
+    assert a["rows"] > 0 and b["rows"] > 0 and a["ms"] > 0 and b["ms"] > 0
+    import graphgen
+    w = graphgen.make_config(1, shrink=4)
+    assert a["rows"] + b["rows"] == w.n and a["entries"] + b["entries"] == w.nnz
