@@ -32,7 +32,9 @@
  *     at the same time race on the handle's scratch (hub-row partial sums); serialise them.
  *   - Results are run-to-run bitwise deterministic: no floating-point atomics are used.
  *   - Environment variables (tuning and tests only; none is needed).  All are read when isp_csr_build runs and
- *     are kept in the handle (a cached transpose inherits its source's); no compute call reads the environment.
+ *     are kept in the handle; no compute call reads the environment.  (The partition sizes of a cached transpose
+ *     are read when it is built, by the first isp_csr_transpose_cached call and its workspace query; the other
+ *     settings it inherits from its source.)
  *       ISP_BLOCK_COST, ISP_HUB_THRESHOLD, ISP_SEGMENT_LEN, ISP_BANDS, ISP_MIN_PIECE, ISP_MID_THRESHOLD,
  *       ISP_PACKED_BLOCK:
  *                              sizes of the work partition (clamped to what the kernels' tables hold)
