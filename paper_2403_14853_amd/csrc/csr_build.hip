@@ -848,7 +848,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->partial_rows = L.max_seg + 1;
   A->has_packed = false; A->packed_values_rw = nullptr; A->packed_src_pos = nullptr;
   A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false; A->mirror_aligned = false;
-  A->mean_values = nullptr; A->mean_values_valid = false; A->mean_values_used = false;
+  A->mean_values = nullptr; A->mean_values_packed = nullptr; A->mean_values_valid = false; A->mean_values_used = false;
   A->sel_flags = nullptr; A->inv_perm = nullptr; A->inv_perm_valid = false;
   isp_csr_info_t& I = A->info;
   const build_counters& h = po.h;

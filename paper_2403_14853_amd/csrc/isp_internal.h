@@ -74,6 +74,7 @@ struct isp_csr {
   float* t_values_rw;      // transposes only: the values array (in the workspace), writable
   float* mean_values;      // transposes only: nnz floats of workspace the transposition no longer needs, for
                            // value / (length of the entry's source row), filled on first use
+  float* mean_values_packed;  // the same values in the order of the packed SpMM layout's entries (NULL without it)
   bool mean_values_valid;  // false until filled
   bool mean_values_used;   // a mean backward has run on this handle: isp_csr_values_changed refills the array
   uint8_t* sel_flags;      // transposes only: nnz bytes of the same spare workspace; the min / max backward
@@ -128,7 +129,7 @@ isp_status isp_transpose_refresh_values(isp_csr* A, hipStream_t s);
 // Values of A's cached transpose divided by the lengths of their source rows of A (what the backward of the
 // mean reduction multiplies dY's rows by): computed on s at the first call and after the values changed,
 // kept in the transpose workspace afterwards.
-isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** out);
+isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** out, const float** out_packed);
 // Position q in A's cached transpose of every stored entry p of A (the inverse of perm): computed on s at the
 // first call, kept in the transpose workspace afterwards.
 isp_status isp_transpose_inverse_perm(isp_csr* A, hipStream_t s, const int32_t** out);
@@ -138,9 +139,11 @@ isp_status isp_spmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_
                            hipStream_t s);
 // Grouped fast path of SpMM; *done = false (nothing launched) when the operands do not qualify.
 // mean_mode 0: plain sum; 1: rows divided by their length.  values_override (optional): nnz values used in
-// place of A's own.
+// place of A's own, in the order of A's entries; values_override_packed: the same values in the order of the
+// packed layout's entries, without which an override keeps the launch on A's ordinary partition.
 isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                                   int mean_mode, const float* values_override, hipStream_t s, bool* done);
+                                   int mean_mode, const float* values_override, hipStream_t s, bool* done,
+                                   const float* values_override_packed = nullptr);
 isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv,
                             int32_t d, bool scale, float* out, hipStream_t s);
 isp_status isp_fusedmm_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, int op, float* Y,

@@ -217,13 +217,16 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
 
 template <int LPG, int VEC = 4>
 isp_status launch_grouped(const isp_csr* A, const float* X, int64_t ldx, int d, int k_base, int n_slices, float* Y,
-                          int64_t ldy, int mean_mode, const float* values_override, hipStream_t s) {
+                          int64_t ldy, int mean_mode, const float* values_override, hipStream_t s,
+                          const float* values_override_packed = nullptr) {
   // The packed layout (a derived matrix in which the pieces of long rows share work items) when the handle has
   // one; an override of the values is in the order of A's own entries and therefore runs on A's own partition.
-  const bool packed = A->has_packed && !values_override && A->packed_block_cost + A->vp.hub_t <= GS_MAX_ENT &&
+  const bool packed = A->has_packed && (!values_override || values_override_packed) &&
+                      A->packed_block_cost + A->vp.hub_t <= GS_MAX_ENT &&
                       A->packed_block_cost / A->packed_row_cost <= GS_MAX_ROWS;
   const isp_view& v = packed ? A->vp : A->v;
-  const float* vals = values_override ? values_override : v.values;  // (one value per stored entry, the view's order)
+  // (one value per stored entry, in the order of the view's entries)
+  const float* vals = values_override ? (packed ? values_override_packed : values_override) : v.values;
   const int n_items = v.n_blocks + v.n_seg;
   if (n_items > 0) {
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG) * (unsigned)n_slices;
@@ -267,7 +270,8 @@ bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 // mean_mode: see k_spmm_grouped.  values_override (optional): nnz values, in A's entry order, used in place of
 // A's own (the backward of the mean reduction passes the transpose's values divided by the source rows' lengths).
 isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx, int32_t d, float* Y, int64_t ldy,
-                                   int mean_mode, const float* values_override, hipStream_t s, bool* done) {
+                                   int mean_mode, const float* values_override, hipStream_t s, bool* done,
+                                   const float* values_override_packed) {
   const isp_view& av = A->v;
   // Lane width: float4 when width, pitch and pointers allow; float2 / float lanes otherwise (any d),
   // those two only with 32-bit addressing and for the plain sum.
@@ -290,13 +294,13 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
       const int lpg = w <= 16 * vec ? 16 : (w <= 32 * vec ? 32 : 64);
       const int ns = (w + lpg * vec - 1) / (lpg * vec);
       if (vec == 2) {
-        if (lpg == 16) st = launch_grouped<16, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
-        else if (lpg == 32) st = launch_grouped<32, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
-        else st = launch_grouped<64, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
+        if (lpg == 16) st = launch_grouped<16, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s, values_override_packed);
+        else if (lpg == 32) st = launch_grouped<32, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s, values_override_packed);
+        else st = launch_grouped<64, 2>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s, values_override_packed);
       } else {
-        if (lpg == 16) st = launch_grouped<16, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
-        else if (lpg == 32) st = launch_grouped<32, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
-        else st = launch_grouped<64, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s);
+        if (lpg == 16) st = launch_grouped<16, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s, values_override_packed);
+        else if (lpg == 32) st = launch_grouped<32, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s, values_override_packed);
+        else st = launch_grouped<64, 1>(A, X, ldx, d, k_base, ns, Y, ldy, 0, values_override, s, values_override_packed);
       }
     }
     return st;
@@ -323,11 +327,11 @@ isp_status isp_spmm_grouped_launch(const isp_csr* A, const float* X, int64_t ldx
     const int w = (d - k_base < tile) ? d - k_base : tile;
     const int ns = (w + 4 * lpg - 1) / (4 * lpg);
     switch (lpg) {
-      case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
-      case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
-      case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
-      case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
-      default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s); break;
+      case 4: st = launch_grouped<4>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s, values_override_packed); break;
+      case 8: st = launch_grouped<8>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s, values_override_packed); break;
+      case 16: st = launch_grouped<16>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s, values_override_packed); break;
+      case 32: st = launch_grouped<32>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s, values_override_packed); break;
+      default: st = launch_grouped<64>(A, X, ldx, d, k_base, ns, Y, ldy, mean_mode, values_override, s, values_override_packed); break;
     }
   }
   return st;

@@ -477,11 +477,11 @@ isp_status isp_spmm_reduce_bwd_launch(isp_csr* A, const float* dY, int64_t lddy,
   const isp_csr* At = A->At;
   if (reduce == R_MEAN && At->v.nnz > 0) {
     // the tuned kernels on A^T with every value divided by its source row's length (computed once per handle)
-    const float* mv = nullptr;
-    isp_status st = isp_transpose_mean_values(A, s, &mv);
+    const float *mv = nullptr, *mv_packed = nullptr;
+    isp_status st = isp_transpose_mean_values(A, s, &mv, &mv_packed);
     if (st != ISP_OK) return st;
     bool done = false;
-    st = isp_spmm_grouped_launch(At, dY, lddy, d, dX, lddx, 0, mv, s, &done);
+    st = isp_spmm_grouped_launch(At, dY, lddy, d, dX, lddx, 0, mv, s, &done, mv_packed);
     if (done || st != ISP_OK) return st;
   }
   const bool hv = At->v.values != nullptr;

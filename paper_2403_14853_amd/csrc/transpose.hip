@@ -378,6 +378,7 @@ isp_status isp_transpose_build(isp_csr* A, void* ws, size_t ws_bytes, hipStream_
   At->t_values_rw = t_values;
   // the record arrays of the sort are free from here on; one of them later holds the mean reduction's values
   At->mean_values = (float*)(base + L.set[0][1]);
+  At->mean_values_packed = At->has_packed ? (float*)(base + L.set[1][2]) : nullptr;
   At->mean_values_valid = false;
   At->mean_values_used = false;
   At->sel_flags = (uint8_t*)(base + L.set[1][1]);
@@ -404,17 +405,30 @@ bool stream_is_capturing(hipStream_t s) {
 
 }  // namespace
 
-isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** out) {
+// (and, where A^T has the packed SpMM layout, the same values in the order of that layout's entries)
+static isp_status fill_mean_values(isp_csr* A, hipStream_t s) {
+  isp_csr* At = A->At;
+  const unsigned grid = (unsigned)((A->v.nnz + 255) / 256);
+  k_mean_values<<<grid, 256, 0, s>>>(At->v.indices, At->v.values, A->v.inv_len, A->v.nnz, At->mean_values);
+  ISP_LAUNCH_CHECK();
+  if (At->mean_values_packed) {
+    k_gather_values<<<grid, 256, 0, s>>>(At->packed_src_pos, At->mean_values, A->v.nnz, At->mean_values_packed);
+    ISP_LAUNCH_CHECK();
+  }
+  return ISP_OK;
+}
+
+isp_status isp_transpose_mean_values(isp_csr* A, hipStream_t s, const float** out, const float** out_packed) {
   isp_csr* At = A->At;
   if (!At || !At->mean_values) return isp_fail(ISP_EINVAL, "no cached transpose");
   if (!At->mean_values_valid && A->v.nnz > 0) {
-    k_mean_values<<<(unsigned)((A->v.nnz + 255) / 256), 256, 0, s>>>(At->v.indices, At->v.values, A->v.inv_len, A->v.nnz,
-                                                                     At->mean_values);
-    ISP_LAUNCH_CHECK();
+    isp_status st = fill_mean_values(A, s);
+    if (st != ISP_OK) return st;
     At->mean_values_valid = !stream_is_capturing(s);
   }
   At->mean_values_used = true;
   *out = At->mean_values;
+  *out_packed = At->mean_values_packed;
   return ISP_OK;
 }
 
@@ -440,8 +454,8 @@ isp_status isp_transpose_refresh_values(isp_csr* A, hipStream_t s) {
   k_gather_values<<<grid, 256, 0, s>>>(At->perm, A->v.values, A->v.nnz, At->t_values_rw);
   ISP_LAUNCH_CHECK();
   if (At->mean_values_used) {  // a mean backward has run (or was captured): its values follow at once
-    k_mean_values<<<grid, 256, 0, s>>>(At->v.indices, At->v.values, A->v.inv_len, A->v.nnz, At->mean_values);
-    ISP_LAUNCH_CHECK();
+    isp_status st = fill_mean_values(A, s);
+    if (st != ISP_OK) return st;
     // (valid stays as it is: during a capture the refill runs with the replays, like the fill itself)
   }
   return ISP_OK;
