@@ -163,6 +163,29 @@ isp_status isp_csr_export(const isp_csr_t* A, const int64_t** indptr, const int3
 isp_status isp_csr_info(const isp_csr_t* A, isp_csr_info_t* info);
 
 /*
+ * Overlapping calls on one matrix (Section 1(b): the work partition, and Section 3.3: the cached transpose,
+ * are built once and shared).  The compute calls keep the partial sums of hub-row segments, and the min / max
+ * backward its per-entry marks, in the handle's workspace, so two calls on ONE handle must not run at the same
+ * time.  An alias is a second handle on the same matrix that keeps exactly that scratch in a workspace of its
+ * own and shares everything else - the caller's arrays, both work partitions, the packed SpMM layout, the
+ * cached transpose and its permutation: calls on A, on the alias and on other aliases may overlap freely
+ * (different streams or threads); calls on one alias must still follow each other.  Results are bit-identical
+ * to A's.
+ *   max_d: the widest feature width the alias will be used with (sizes the partial rows of FusedMM beyond 256
+ *     columns; wider calls still work, one 256-column group per launch).
+ *   workspace: device memory, 256-byte aligned, isp_csr_alias_workspace bytes, borrowed until the alias is
+ *     destroyed; it needs no clearing.  Config-3-sized graphs need about 1 KiB per row piece (under 1 GiB).
+ *   The alias takes over A's cached transpose as it is at this call: build it on A first if the alias is to
+ *     run backward calls (isp_csr_transpose_cached on the alias returns it, or ISP_EINVAL if A had none).
+ *   Destroy the alias (isp_csr_destroy) before A.  After isp_csr_values_changed(A) every alias made before is
+ *     refused with ISP_EINVAL: make a new one (host work only, nothing is copied or launched).
+ * Errors: ISP_EINVAL (NULL or unaligned arguments, workspace too small, A is a transpose or an alias).
+ */
+isp_status isp_csr_alias_workspace(const isp_csr_t* A, int32_t max_d, size_t* bytes);
+isp_status isp_csr_alias(const isp_csr_t* A, int32_t max_d, void* workspace, size_t workspace_bytes,
+                         isp_csr_t** out);
+
+/*
  * SpMM, sum reduction: Y[i, 0:d] = sum over stored entries p of row i of values[p] * X[indices[p], 0:d]
  * (abstract; Sections 1, 3.4).  X has A.n_cols rows, Y has A.n_rows rows.  Backward dX = A^T dY is the
  * same call on the handle from isp_csr_transpose_cached (Section 3.3).  X and Y must not overlap.

@@ -14,7 +14,8 @@ _lib = None
 
 EXPORTED_SYMBOLS = [
     "isp_csr_build_workspace", "isp_csr_build", "isp_csr_transpose_workspace", "isp_csr_transpose_cached",
-    "isp_csr_values_changed", "isp_csr_export", "isp_csr_info", "isp_spmm", "isp_spmm_static_scratch", "isp_sddmm", "isp_fusedmm", "isp_fusedmm_backward",
+    "isp_csr_values_changed", "isp_csr_alias_workspace", "isp_csr_alias", "isp_csr_export", "isp_csr_info", "isp_spmm",
+    "isp_spmm_static_scratch", "isp_sddmm", "isp_fusedmm", "isp_fusedmm_backward",
     "isp_spmm_reduce", "isp_spmm_reduce_backward", "isp_csr_destroy", "isp_last_error", "isp_version",
 ]
 
@@ -63,6 +64,8 @@ def load_library():
     lib.isp_csr_transpose_cached.argtypes = [vp, vp, sz, vp, P(vp), P(ctypes.c_int)]
     lib.isp_csr_export.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
     lib.isp_csr_values_changed.argtypes = [vp, vp]
+    lib.isp_csr_alias_workspace.argtypes = [vp, i32, P(sz)]
+    lib.isp_csr_alias.argtypes = [vp, i32, vp, sz, P(vp)]
     lib.isp_csr_info.argtypes = [vp, P(CsrInfo)]
     lib.isp_spmm.argtypes = [vp, vp, i64, i32, vp, i64, vp]
     lib.isp_spmm_static_scratch.argtypes = [vp, vp, i64, i32, vp, i64, vp]
@@ -237,6 +240,28 @@ def csr_transpose_cached(A: CSR, *, stream=None, workspace=None):
     A._keep.append(ws)
     A._At = CSR(At_h, A.n_cols, A.n_rows, A.nnz, [ws], owner=A)
     return A._At, bool(was.value)
+
+
+def csr_alias_workspace(A: CSR, max_d: int = 256) -> int:
+    """isp_csr_alias_workspace: bytes of device workspace an alias of A needs."""
+    need = ctypes.c_size_t()
+    _check(load_library().isp_csr_alias_workspace(A._h, int(max_d), ctypes.byref(need)))
+    return int(need.value)
+
+
+def csr_alias(A: CSR, max_d: int = 256, *, workspace=None) -> CSR:
+    """isp_csr_alias: a second handle on A's matrix with scratch of its own, whose calls may overlap A's.
+    The alias keeps A alive; destroy it (or drop it) before destroying A."""
+    lib = load_library()
+    ws = _own_workspace(workspace, csr_alias_workspace(A, max_d), A._keep[0].device)
+    h = ctypes.c_void_p()
+    _check(lib.isp_csr_alias(A._h, int(max_d), _dptr(ws), ws.numel(), ctypes.byref(h)))
+    B = CSR(h, A.n_rows, A.n_cols, A.nnz, [A._keep[0], ws, A])
+    if A._At is not None:  # the alias's own copy of the cached transpose (a cache hit: no device work)
+        At_h = ctypes.c_void_p()
+        _check(lib.isp_csr_transpose_cached(h, None, 0, None, ctypes.byref(At_h), None))
+        B._At = CSR(At_h, A.n_cols, A.n_rows, A.nnz, [ws], owner=B)
+    return B
 
 
 def csr_values_changed(A: CSR, *, stream=None):

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libisp.so")
 SOURCES = ["isp_api.hip", "scan.hip", "csr_build.hip", "transpose.hip", "spmm.hip", "sddmm.hip", "fusedmm.hip",
-           "spmm_reduce.hip", "static_scratch.hip"]
+           "spmm_reduce.hip", "static_scratch.hip", "alias.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 VALU ops out of scalar float code

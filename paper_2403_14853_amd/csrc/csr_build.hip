@@ -850,6 +850,7 @@ isp_status isp_build_handle(int64_t n_rows, int64_t n_cols, int64_t nnz, const i
   A->perm = nullptr; A->t_values_rw = nullptr; A->At = nullptr; A->is_transpose = false; A->mirror_aligned = false;
   A->mean_values = nullptr; A->mean_values_packed = nullptr; A->mean_values_valid = false; A->mean_values_used = false;
   A->sel_flags = nullptr; A->inv_perm = nullptr; A->inv_perm_valid = false;
+  A->source = nullptr; A->values_gen = 0; A->source_gen = 0;
   isp_csr_info_t& I = A->info;
   const build_counters& h = po.h;
   I.n_rows = n_rows; I.n_cols = n_cols; I.nnz = nnz; I.max_degree = (int64_t)h.max_degree;

@@ -60,6 +60,9 @@ isp_status isp_check_device(const isp_csr* A) {
   ISP_HIP(hipGetDevice(&dev));
   if (dev != A->device)
     return isp_fail(ISP_EINVAL, "the handle was built on device %d, the current device is %d", A->device, dev);
+  if (A->source && A->source_gen != A->source->values_gen)
+    return isp_fail(ISP_EINVAL, "isp_csr_values_changed ran on the source handle after this alias was made: "
+                    "destroy the alias and make a new one");
   return ISP_OK;
 }
 
@@ -88,6 +91,9 @@ isp_status isp_csr_transpose_cached(isp_csr_t* A, void* workspace, size_t worksp
     return ISP_OK;
   }
   if (was_cached) *was_cached = 0;
+  if (A->source)
+    return isp_fail(ISP_EINVAL, "an alias takes its transpose from its source handle: call isp_csr_transpose_cached "
+                    "on that handle first, then make the alias");
   isp_status st = isp_check_device(A);
   if (st != ISP_OK) return st;
   st = isp_transpose_build(A, workspace, workspace_bytes, (hipStream_t)stream);
@@ -99,8 +105,10 @@ isp_status isp_csr_transpose_cached(isp_csr_t* A, void* workspace, size_t worksp
 isp_status isp_csr_values_changed(isp_csr_t* A, void* stream) {
   if (!A) return isp_fail(ISP_EINVAL, "handle is NULL");
   if (A->is_transpose) return isp_fail(ISP_EINVAL, "pass the source handle, not its transpose");
+  if (A->source) return isp_fail(ISP_EINVAL, "pass the handle isp_csr_build returned, not an alias of it");
   isp_status st = isp_check_device(A);
   if (st != ISP_OK) return st;
+  ++A->values_gen;  // aliases made before this call are refused from now on
   // everything derived from the values, in stream order: the packed SpMM layout's copy, the transposed values
   // (and what the mean backward keeps of them), the transpose's own packed copy
   if ((st = isp_refresh_packed_values(A, (hipStream_t)stream)) != ISP_OK) return st;

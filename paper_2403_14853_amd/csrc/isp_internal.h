@@ -85,6 +85,11 @@ struct isp_csr {
   int device;
   isp_csr* At;             // cached transpose (owned), or NULL
   bool is_transpose;
+  // Alias handles (alias.hip): a copy of another handle ("the source") with scratch of its own.  source is
+  // NULL for a built handle and for its cached transpose.  values_gen counts isp_csr_values_changed calls on
+  // a built handle; an alias remembers in source_gen the count it was made at and is refused once they differ.
+  const isp_csr* source;
+  uint64_t values_gen, source_gen;
   bool mirror_aligned;     // set with the cached transpose: A^T's offsets and indices equal A's own element for
                            // element (a symmetric pattern, rows ascending), so entry p of A^T is the mirror of
                            // entry p of A and one pass over A can serve both
@@ -103,7 +108,8 @@ isp_status isp_fail(isp_status st, const char* fmt, ...);
 static inline size_t isp_align(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // ---- argument checks shared by the entry points (isp_api.hip) -----------------------------------
-isp_status isp_check_device(const isp_csr* A);  // the handle's device must be the current one
+// The handle's device must be the current one, and an alias must be as recent as its source's values.
+isp_status isp_check_device(const isp_csr* A);
 isp_status isp_check_dense(const void* p, int64_t ld, int32_t d, int64_t rows, const char* name);
 
 // ---- device scans (scan.hip) -----------------------------------------------------------------
