@@ -180,15 +180,15 @@ struct g_fwd {  // gathered x_j, row operand x_i
   static constexpr int NSRC = 1, NROW = 1, STEPS = 4;
   static constexpr bool PER_ENTRY = false, ACCUMULATE = false;
   using args = g_args1;
-  template <int LPG>
-  __device__ static inline void edge(const args&, float a, const float (&x)[1][4], const float (&r)[1][4],
-                                     float (&acc)[4], bool lane_on, bool live) {
+  template <int LPG, int W>
+  __device__ static inline void edge(const args&, float a, const float (&x)[1][W], const float (&r)[1][W],
+                                     float (&acc)[W], const lane_cols<W / 4>& lc, bool live) {
     float sg = 1.f, dsg = 0.f;
-    if (OP != ISP_OP_ONE) edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0], lane_on)), sg, dsg);
+    if (OP != ISP_OP_ONE) edge_fn(OP, group_allreduce<LPG>(dotw<W>(r[0], x[0], lc)), sg, dsg);
     const float w = a * sg;
     if (live) {
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[0][v], acc[v]);
+      for (int v = 0; v < W; ++v) acc[v] = fmaf(w, x[0][v], acc[v]);
     }
   }
 };
@@ -198,18 +198,18 @@ struct g_bwd_row {  // gathered x_j, row operands x_i and g_i:  dX_i += dz x_j
   static constexpr int NSRC = 1, NROW = 2, STEPS = 3;  // (three operand rows per step: three steps per buffer keep four waves resident)
   static constexpr bool PER_ENTRY = false, ACCUMULATE = false;
   using args = g_args12;
-  template <int LPG>
-  __device__ static inline void edge(const args&, float a, const float (&x)[1][4], const float (&r)[2][4],
-                                     float (&acc)[4], bool lane_on, bool live) {
+  template <int LPG, int W>
+  __device__ static inline void edge(const args&, float a, const float (&x)[1][W], const float (&r)[2][W],
+                                     float (&acc)[W], const lane_cols<W / 4>& lc, bool live) {
     if (OP == ISP_OP_ONE) return;  // s does not depend on x_i: nothing flows through z
-    const float z = group_allreduce<LPG>(dot4(r[0], x[0], lane_on));
-    const float gd = group_allreduce<LPG>(dot4(r[1], x[0], lane_on));
+    const float z = group_allreduce<LPG>(dotw<W>(r[0], x[0], lc));
+    const float gd = group_allreduce<LPG>(dotw<W>(r[1], x[0], lc));
     float sg, dsg;
     edge_fn(OP, z, sg, dsg);
     const float dz = a * gd * dsg;
     if (live) {
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc[v] = fmaf(dz, x[0][v], acc[v]);
+      for (int v = 0; v < W; ++v) acc[v] = fmaf(dz, x[0][v], acc[v]);
     }
   }
 };
@@ -219,19 +219,19 @@ struct g_bwd_col {  // over A^T: gathered x_i and g_i, row operand x_j:  dX_j +=
   static constexpr int NSRC = 2, NROW = 1, STEPS = 3;
   static constexpr bool PER_ENTRY = false, ACCUMULATE = true;
   using args = g_args21;
-  template <int LPG>
-  __device__ static inline void edge(const args&, float a, const float (&x)[2][4], const float (&r)[1][4],
-                                     float (&acc)[4], bool lane_on, bool live) {
+  template <int LPG, int W>
+  __device__ static inline void edge(const args&, float a, const float (&x)[2][W], const float (&r)[1][W],
+                                     float (&acc)[W], const lane_cols<W / 4>& lc, bool live) {
     float sg = 1.f, dsg = 0.f, gd = 0.f;
     if (OP != ISP_OP_ONE) {
-      edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0], lane_on)), sg, dsg);
-      gd = group_allreduce<LPG>(dot4(r[0], x[1], lane_on));
+      edge_fn(OP, group_allreduce<LPG>(dotw<W>(r[0], x[0], lc)), sg, dsg);
+      gd = group_allreduce<LPG>(dotw<W>(r[0], x[1], lc));
     }
     const float w = a * sg;
     const float dz = a * gd * dsg;
     if (live) {
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
+      for (int v = 0; v < W; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
     }
   }
 };
@@ -249,34 +249,35 @@ struct g_bwd_mirror {  // gathered x_j and g_j, row operands x_i and g_i
   static constexpr int NSRC = 2, NROW = 2, STEPS = 2;
   static constexpr bool PER_ENTRY = false, ACCUMULATE = false, HAS_VAL2 = true;
   using args = g_args22;
-  template <int LPG>
-  __device__ static inline void edge(const args&, float a, float at, const float (&x)[2][4], const float (&r)[2][4],
-                                     float (&acc)[4], bool lane_on, bool live) {
+  template <int LPG, int W>
+  __device__ static inline void edge(const args&, float a, float at, const float (&x)[2][W], const float (&r)[2][W],
+                                     float (&acc)[W], const lane_cols<W / 4>& lc, bool live) {
     float sg = 1.f, dsg = 0.f, gd_ij = 0.f, gd_ji = 0.f;
     if (OP != ISP_OP_ONE) {
-      edge_fn(OP, group_allreduce<LPG>(dot4(r[0], x[0], lane_on)), sg, dsg);
-      gd_ij = group_allreduce<LPG>(dot4(r[1], x[0], lane_on));  // <g_i, x_j>
-      gd_ji = group_allreduce<LPG>(dot4(x[1], r[0], lane_on));  // <g_j, x_i>
+      edge_fn(OP, group_allreduce<LPG>(dotw<W>(r[0], x[0], lc)), sg, dsg);
+      gd_ij = group_allreduce<LPG>(dotw<W>(r[1], x[0], lc));  // <g_i, x_j>
+      gd_ji = group_allreduce<LPG>(dotw<W>(x[1], r[0], lc));  // <g_j, x_i>
     }
     const float w = at * sg;
     const float dz = (a * gd_ij + at * gd_ji) * dsg;
     if (live) {
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
+      for (int v = 0; v < W; ++v) acc[v] = fmaf(w, x[1][v], fmaf(dz, x[0][v], acc[v]));
     }
   }
 };
 
-template <class P, int LPG, bool ADDR32>
+template <class P, int LPG, int W, bool ADDR32>
 __global__ void __launch_bounds__(ISP_WG) k_fused_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                           const int32_t* __restrict__ indices,
                                                           const float* __restrict__ values, typename P::args pa, int d,
                                                           float* __restrict__ Y, int64_t ldy) {
   __shared__ gs_lds lds;
-  fused_grouped_item<P, LPG, ADDR32>(A, indptr, indices, values, pa, d, Y, ldy, lds);
+  fused_grouped_item<P, LPG, W, ADDR32>(A, indptr, indices, values, pa, d, Y, ldy, lds);
 }
 
-template <class P, int LPG>
+// LPG lanes with W floats each span the feature width: W * LPG >= d.
+template <class P, int LPG, int W>
 isp_status run_grouped(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s) {
   const isp_view& v = A->v;
   const int n_items = v.n_blocks + v.n_seg;
@@ -284,8 +285,8 @@ isp_status run_grouped(const isp_csr* A, const typename P::args& pa, int d, floa
     const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
     bool a32 = true;
     for (int k = 0; k < P::NSRC; ++k) a32 = a32 && fused_offsets_fit_32(v.n_cols, pa.lds_[k], d);
-    if (a32) k_fused_grouped<P, LPG, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
-    else k_fused_grouped<P, LPG, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
+    if (a32) k_fused_grouped<P, LPG, W, true><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
+    else k_fused_grouped<P, LPG, W, false><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, v.values, pa, d, Y, ldy);
     ISP_LAUNCH_CHECK();
   }
   if (v.n_hub > 0) {
@@ -298,10 +299,17 @@ isp_status run_grouped(const isp_csr* A, const typename P::args& pa, int d, floa
 
 template <class P>
 isp_status run_grouped_d(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s) {
-  if (d <= 32) return run_grouped<P, 8>(A, pa, d, Y, ldy, s);
-  if (d <= 64) return run_grouped<P, 16>(A, pa, d, Y, ldy, s);
-  if (d <= 128) return run_grouped<P, 32>(A, pa, d, Y, ldy, s);
-  return run_grouped<P, 64>(A, pa, d, Y, ldy, s);
+  if (d <= 32) return run_grouped<P, 8, 4>(A, pa, d, Y, ldy, s);
+  if (A->tune.fused_w == 4) {  // one float4 per lane at every width
+    if (d <= 64) return run_grouped<P, 16, 4>(A, pa, d, Y, ldy, s);
+    if (d <= 128) return run_grouped<P, 32, 4>(A, pa, d, Y, ldy, s);
+    return run_grouped<P, 64, 4>(A, pa, d, Y, ldy, s);
+  }
+  // Two float4 per lane: half the lanes per dot product, so a step covers twice the entries with one lane
+  // reduction stage and one evaluation of the edge function less per entry.
+  if (d <= 64) return run_grouped<P, 8, 8>(A, pa, d, Y, ldy, s);
+  if (d <= 128) return run_grouped<P, 16, 8>(A, pa, d, Y, ldy, s);
+  return run_grouped<P, 32, 8>(A, pa, d, Y, ldy, s);
 }
 
 // Column groups (of 256) a hub segment may store per launch of a wide pass: as many as the partial-row scratch

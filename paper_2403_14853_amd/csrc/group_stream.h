@@ -12,8 +12,8 @@
 // loop is therefore flat: U steps are issued back to back (LDS read -> address -> gather) before
 // the first is consumed, independent of where rows begin and end, which keeps short rows from
 // serialising on memory latency.  When
-// a step ends a row the G group accumulators are summed with lane shuffles and group 0 writes
-// the row slice.  Feature columns beyond one slice are covered by further workgroups
+// a step ends a row the G group accumulators are summed with lane shuffles that leave each group
+// with a share of the finished columns (group_reduce_scatter), and every group writes its share.  Feature columns beyond one slice are covered by further workgroups
 // (blockIdx % n_slices), dealt round-robin to the XCDs.
 #pragma once
 #include "row_stream.h"
@@ -189,12 +189,42 @@ __device__ inline float group_allreduce(float v) {
   return v;
 }
 
-// Sum a value over the G groups (lanes with equal lane % LPG); result valid in group 0.
-template <int LPG>
-__device__ inline float group_sum(float v) {
+// Sum W values per lane over the G = 64 / LPG groups (lanes with equal lane % LPG), leaving the sums spread over
+// the groups instead of complete in one: a stage that pairs lanes `O` apart splits the values in two halves,
+// each lane of a pair keeps one half and receives the partner's share of it, so the stages move W/2 + W/4 + ...
+// values instead of W each.  Afterwards the lane holds, in v[0 .. R), R = max(1, W / G), the finished sums of
+// its values idx0 .. idx0 + R (idx0 is returned).  With more groups than values (G > W) the last stages add
+// single values both ways and the groups whose lane number has a bit of (64 / W - 1) & ~(LPG - 1) set hold
+// copies: group_owner<LPG, W>(lane) says which lanes hold the ones to store.  The order of the additions is
+// fixed, so results repeat bit for bit.
+template <int O, int LPG, int N, int W>
+__device__ inline void group_reduce_stage(float (&v)[W], int lane, int& idx0) {
+  if constexpr (O >= LPG) {
+    if constexpr (N > 1) {
+      const bool up = (lane & O) != 0;
 #pragma unroll
-  for (int o = LPG; o < ISP_WAVE; o <<= 1) v += __shfl_xor(v, o);
-  return v;
+      for (int c = 0; c < N / 2; ++c) {
+        const float send = up ? v[c] : v[c + N / 2];
+        const float keep = up ? v[c + N / 2] : v[c];
+        v[c] = keep + __shfl_xor(send, O);
+      }
+      idx0 += up ? N / 2 : 0;
+      group_reduce_stage<O / 2, LPG, N / 2, W>(v, lane, idx0);
+    } else {
+      v[0] += __shfl_xor(v[0], O);
+      group_reduce_stage<O / 2, LPG, 1, W>(v, lane, idx0);
+    }
+  }
+}
+template <int LPG, int W>
+__device__ inline int group_reduce_scatter(float (&v)[W], int lane) {
+  int idx0 = 0;
+  group_reduce_stage<ISP_WAVE / 2, LPG, W, W>(v, lane, idx0);
+  return idx0;
+}
+template <int LPG, int W>
+__device__ inline bool group_owner(int lane) {
+  return (lane & ((ISP_WAVE / W - 1) & ~(LPG - 1))) == 0;
 }
 
 }  // namespace isp_dev

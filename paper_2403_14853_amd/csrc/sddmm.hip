@@ -98,23 +98,23 @@ struct sddmm_policy {
   static constexpr int NSRC = 1, NROW = 1, STEPS = 4;
   static constexpr bool PER_ENTRY = true, ACCUMULATE = false, ADD = ADD_;
   struct args { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
-  template <int LPG>
-  __device__ static inline float entry(float a, const float (&x)[1][4], const float (&r)[1][4], bool lane_on) {
-    return a * group_allreduce<LPG>(dot4(r[0], x[0], lane_on));
+  template <int LPG, int W>
+  __device__ static inline float entry(float a, const float (&x)[1][W], const float (&r)[1][W], const lane_cols<W / 4>& lc) {
+    return a * group_allreduce<LPG>(dotw<W>(r[0], x[0], lc));
   }
 };
 
-template <int LPG, bool ADDR32, bool ADD>
+template <int LPG, int W, bool ADDR32, bool ADD>
 __global__ void __launch_bounds__(ISP_WG) k_sddmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                           const int32_t* __restrict__ indices,
                                                           const float* __restrict__ values,
                                                           typename sddmm_policy<ADD>::args pa, int d, int k_lo) {
   __shared__ gs_lds lds;
-  fused_grouped_item<sddmm_policy<ADD>, LPG, ADDR32>(A, indptr, indices, values, pa, d, nullptr, 0, lds, k_lo);
+  fused_grouped_item<sddmm_policy<ADD>, LPG, W, ADDR32>(A, indptr, indices, values, pa, d, nullptr, 0, lds, k_lo);
 }
 
-// One pass over the feature columns [k_lo, d_hi) (d_hi - k_lo <= 4 * LPG); add: accumulate into out.
-template <int LPG>
+// One pass over the feature columns [k_lo, d_hi) (d_hi - k_lo <= W * LPG); add: accumulate into out.
+template <int LPG, int W>
 isp_status launch_grouped(const isp_csr* A, const float* U, int64_t ldu, const float* V, int64_t ldv, int k_lo,
                           int d_hi, bool add, bool scale, float* out, hipStream_t s) {
   const isp_view& v = A->v;
@@ -127,7 +127,7 @@ isp_status launch_grouped(const isp_csr* A, const float* U, int64_t ldu, const f
 #define ISP_GO(A32, AD)                                                                                  \
   do {                                                                                                   \
     typename sddmm_policy<AD>::args pb{{pa.src[0]}, {pa.lds_[0]}, {pa.rowop[0]}, {pa.ldr[0]}, pa.out_entry}; \
-    k_sddmm_grouped<LPG, A32, AD><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, vals, pb, d_hi, k_lo); \
+    k_sddmm_grouped<LPG, W, A32, AD><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, vals, pb, d_hi, k_lo); \
   } while (0)
   if (a32) { if (add) ISP_GO(true, true); else ISP_GO(true, false); }
   else { if (add) ISP_GO(false, true); else ISP_GO(false, false); }
@@ -181,10 +181,16 @@ isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const
     for (int k_lo = 0; k_lo < d && st == ISP_OK; k_lo += wp) {
       const int k_hi = k_lo + wp < d ? k_lo + wp : d, w = k_hi - k_lo;
       const bool add = k_lo > 0;
-      if (w <= 32) st = launch_grouped<8>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
-      else if (w <= 64) st = launch_grouped<16>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
-      else if (w <= 128) st = launch_grouped<32>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
-      else st = launch_grouped<64>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+      if (w <= 32) st = launch_grouped<8, 4>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+      else if (A->tune.fused_w == 4) {  // one float4 per lane at every width
+        if (w <= 64) st = launch_grouped<16, 4>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+        else if (w <= 128) st = launch_grouped<32, 4>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+        else st = launch_grouped<64, 4>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+      }
+      // two float4 per lane: half the lanes per dot product (see run_grouped_d of the FusedMM passes)
+      else if (w <= 64) st = launch_grouped<8, 8>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+      else if (w <= 128) st = launch_grouped<16, 8>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
+      else st = launch_grouped<32, 8>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
     }
     return st;
   }

@@ -144,15 +144,21 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
     }
     ++k_done;
     r_next = listed ? (int)L.ss[k_done] : k_done;
+    // the groups' sums, spread over the groups: this lane ends up with R finished columns starting at its idx0-th
+    constexpr int R = VEC / G > 0 ? VEC / G : 1;
+    const int idx0 = group_reduce_scatter<LPG, VEC>(acc, lane);
+    if (group_owner<LPG, VEC>(lane) && lane_on) {
+      float t[R];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[v] = group_sum<LPG>(acc[v]);
-    if (mean_mode == 1 && !to_partial) {  // segments and pieces keep plain partial sums; their fix-up divides
-      const int len = (int)L.rp[r_local + 1] - (int)L.rp[r_local];
-      const float inv = len > 0 ? 1.f / (float)len : 0.f;
+      for (int c = 0; c < R; ++c) t[c] = acc[c];
+      if (mean_mode == 1 && !to_partial) {  // segments and pieces keep plain partial sums; their fix-up divides
+        const int len = (int)L.rp[r_local + 1] - (int)L.rp[r_local];
+        const float inv = len > 0 ? 1.f / (float)len : 0.f;
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[v] *= inv;
+        for (int c = 0; c < R; ++c) t[c] *= inv;
+      }
+      store_vec<R>(out + (int64_t)row * ldo + idx0, t);
     }
-    if (g == 0 && lane_on) store_vec<VEC>(out + (int64_t)row * ldo, acc);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
   };

@@ -621,3 +621,44 @@ def test_fusedmm_backward_one_pass_on_a_symmetric_pattern(small_partition, d):
     isp.fusedmm_backward(A, dev(X), dev(G), dX)
     assert_close(dX, *oracle.fusedmm_backward(indptr, indices, None, X, G), "fusedmm backward, descending rows")
     A.destroy()
+
+
+@pytest.mark.parametrize("fused_w", [0, 4])
+@pytest.mark.parametrize("d", [36, 64, 68, 100, 128, 132, 200, 256])
+def test_sddmm_and_fusedmm_lane_shapes(small_partition, d, fused_w):
+    """The grouped SDDMM / FusedMM kernels give a lane one float4 (d <= 32, or everywhere with ISP_FUSED_W=4) or
+    two (the second vector ragged or entirely past d at widths such as 36, 68, 100, 132, 200): both shapes,
+    every edge function, forward and both backward forms (directed graph: two passes; symmetric: one),
+    with and without values, against the oracle element by element."""
+    os.environ.pop("ISP_FUSED_W", None)
+    if fused_w:
+        os.environ["ISP_FUSED_W"] = str(fused_w)
+    try:
+        for w in (graphgen.make_config(1, shrink=128), graphgen.make_config(4, shrink=256)):
+            rng = np.random.default_rng(d)
+            X = (0.2 * rng.standard_normal((w.n, d))).astype(np.float32)
+            G = rng.standard_normal((w.n, d)).astype(np.float32)
+            for values in (w.values if w.values is not None else rng.standard_normal(w.nnz).astype(np.float32), None):
+                A = build(w.indptr, w.indices, values)
+                assert A.info()["n_hub_rows"] > 0
+                isp.csr_transpose_cached(A)
+                Xd, Gd = dev(X), dev(G)
+                out = torch.full((w.nnz,), float("nan"), device="cuda")
+                isp.sddmm(A, Gd, Xd, out, scale_by_a=values is not None)
+                assert_close(out, *oracle.sddmm(w.indptr, w.indices, values, G, X, scale_by_a=values is not None),
+                             "sddmm d=%d" % d)
+                for op in ("sigmoid", "dot", "one"):
+                    Y = torch.full((w.n, d), float("nan"), device="cuda")
+                    isp.fusedmm(A, Xd, Y, op=op)
+                    assert_close(Y, *oracle.fusedmm(w.indptr, w.indices, values, X, op=op), "fusedmm %s d=%d" % (op, d))
+                    dX = torch.full((w.n, d), float("nan"), device="cuda")
+                    isp.fusedmm_backward(A, Xd, Gd, dX, op=op)
+                    assert_close(dX, *oracle.fusedmm_backward(w.indptr, w.indices, values, X, G, op=op),
+                                 "fusedmm backward %s d=%d" % (op, d))
+                    Y2, dX2 = torch.empty_like(Y), torch.empty_like(dX)
+                    isp.fusedmm(A, Xd, Y2, op=op)
+                    isp.fusedmm_backward(A, Xd, Gd, dX2, op=op)
+                    assert torch.equal(Y, Y2) and torch.equal(dX, dX2)
+                A.destroy()
+    finally:
+        os.environ.pop("ISP_FUSED_W", None)
