@@ -42,7 +42,7 @@
  *       ISP_SPMM_LPG, ISP_SPMM_TILE   lanes per group / feature columns per launch of the tuned SpMM
  *       ISP_SDDMM_ONE_PASS     SDDMM keeps 128-column rows in one pass
  *       ISP_NO_MIRROR          the FusedMM backward always runs its two passes, also on symmetric patterns
- *       ISP_FUSED_W            4: the tuned SDDMM / FusedMM kernels give a lane one float4 at every width
+ *       ISP_FUSED_W            4 / 8: the tuned SDDMM / FusedMM kernels give a lane one / two float4 at every width above 32
  *       ISP_WIDE_GROUPS        most 256-column groups a split row stores per launch of a FusedMM pass wider than 256
  *     isp_csr_build_workspace reads the partition sizes too, so set them before both calls or not at all.
  */

@@ -91,7 +91,8 @@ isp_tuning isp_read_tuning() {
   t.spmm_tile = (tile == 64 || tile == 128 || tile == 256) ? tile : 0;
   t.wide_groups = env_int("ISP_WIDE_GROUPS", 0, 0, 4);
   t.no_mirror = getenv("ISP_NO_MIRROR") != nullptr;
-  t.fused_w = env_int("ISP_FUSED_W", 0, 0, 8) == 4 ? 4 : 0;
+  const int fw = env_int("ISP_FUSED_W", 0, 0, 8);
+  t.fused_w = (fw == 4 || fw == 8) ? fw : 0;
   return t;
 }
 

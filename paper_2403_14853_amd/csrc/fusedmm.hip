@@ -297,16 +297,23 @@ isp_status run_grouped(const isp_csr* A, const typename P::args& pa, int d, floa
   return ISP_OK;
 }
 
+// One or two float4 per lane.  Two halve the lanes per dot product, so a step covers twice the entries with one
+// lane-reduction stage and one evaluation of the edge function less per entry, and a step costs more
+// instructions: it pays where steps are full.  Measured on the benchmark graphs at widths 48 .. 256: two above
+// 64 columns; up to 64 columns one, except in the forward pass (one gathered row, the fewest instructions per
+// step) on graphs whose non-empty rows average 24 entries or more.  ISP_FUSED_W=4 / 8 forces either (d > 32).
 template <class P>
 isp_status run_grouped_d(const isp_csr* A, const typename P::args& pa, int d, float* Y, int64_t ldy, hipStream_t s) {
   if (d <= 32) return run_grouped<P, 8, 4>(A, pa, d, Y, ldy, s);
-  if (A->tune.fused_w == 4) {  // one float4 per lane at every width
+  const int64_t live_rows = A->info.n_rows - A->info.bin_rows[0];
+  const bool long_rows = live_rows > 0 && A->info.nnz >= 24 * live_rows;
+  const bool fwd = P::NSRC + P::NROW == 2;
+  const bool two = A->tune.fused_w ? A->tune.fused_w == 8 : (d > 64 || (fwd && long_rows));
+  if (!two) {
     if (d <= 64) return run_grouped<P, 16, 4>(A, pa, d, Y, ldy, s);
     if (d <= 128) return run_grouped<P, 32, 4>(A, pa, d, Y, ldy, s);
     return run_grouped<P, 64, 4>(A, pa, d, Y, ldy, s);
   }
-  // Two float4 per lane: half the lanes per dot product, so a step covers twice the entries with one lane
-  // reduction stage and one evaluation of the edge function less per entry.
   if (d <= 64) return run_grouped<P, 8, 8>(A, pa, d, Y, ldy, s);
   if (d <= 128) return run_grouped<P, 16, 8>(A, pa, d, Y, ldy, s);
   return run_grouped<P, 32, 8>(A, pa, d, Y, ldy, s);

@@ -51,7 +51,7 @@ struct isp_tuning {
   int spmm_lpg;         // ISP_SPMM_LPG: lanes per group of the grouped SpMM (0 = chosen by shape)
   int spmm_tile;        // ISP_SPMM_TILE: feature columns per launch of the grouped SpMM (0 = chosen by shape)
   bool no_mirror;       // ISP_NO_MIRROR: the FusedMM backward never takes the one-pass form of symmetric patterns
-  int fused_w;          // ISP_FUSED_W: 4 = the grouped SDDMM / FusedMM kernels keep one float4 per lane at every width (0 = chosen by width)
+  int fused_w;          // ISP_FUSED_W: 4 / 8 = the grouped SDDMM / FusedMM kernels give a lane one / two float4 at every width above 32 (0 = chosen by width and graph)
   int wide_groups;      // ISP_WIDE_GROUPS: most column groups a hub segment stores per launch of a wide FusedMM pass (0 = as many as fit)
 };
 isp_tuning isp_read_tuning();

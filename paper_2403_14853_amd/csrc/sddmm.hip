@@ -181,13 +181,16 @@ isp_status isp_sddmm_launch(const isp_csr* A, const float* U, int64_t ldu, const
     for (int k_lo = 0; k_lo < d && st == ISP_OK; k_lo += wp) {
       const int k_hi = k_lo + wp < d ? k_lo + wp : d, w = k_hi - k_lo;
       const bool add = k_lo > 0;
+      // one float4 per lane up to 64 columns, two above (half the lanes per dot product: fewer instructions per
+      // entry where a step's eight-plus entries are mostly live; measured on the benchmark graphs);
+      // ISP_FUSED_W=4 / 8 forces either
+      const bool two = A->tune.fused_w ? A->tune.fused_w == 8 : w > 64;
       if (w <= 32) st = launch_grouped<8, 4>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
-      else if (A->tune.fused_w == 4) {  // one float4 per lane at every width
+      else if (!two) {
         if (w <= 64) st = launch_grouped<16, 4>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
         else if (w <= 128) st = launch_grouped<32, 4>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
         else st = launch_grouped<64, 4>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
       }
-      // two float4 per lane: half the lanes per dot product (see run_grouped_d of the FusedMM passes)
       else if (w <= 64) st = launch_grouped<8, 8>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
       else if (w <= 128) st = launch_grouped<16, 8>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);
       else st = launch_grouped<32, 8>(A, U, ldu, V, ldv, k_lo, k_hi, add, scale, out, s);

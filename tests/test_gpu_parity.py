@@ -623,11 +623,12 @@ def test_fusedmm_backward_one_pass_on_a_symmetric_pattern(small_partition, d):
     A.destroy()
 
 
-@pytest.mark.parametrize("fused_w", [0, 4])
+@pytest.mark.parametrize("fused_w", [0, 4, 8])
 @pytest.mark.parametrize("d", [36, 64, 68, 100, 128, 132, 200, 256])
 def test_sddmm_and_fusedmm_lane_shapes(small_partition, d, fused_w):
-    """The grouped SDDMM / FusedMM kernels give a lane one float4 (d <= 32, or everywhere with ISP_FUSED_W=4) or
-    two (the second vector ragged or entirely past d at widths such as 36, 68, 100, 132, 200): both shapes,
+    """The grouped SDDMM / FusedMM kernels give a lane one float4 or two (chosen by width and graph; ISP_FUSED_W
+    forces either above 32 columns; with two the second vector is ragged or entirely past d at widths such as
+    36, 68, 100, 132, 200): both shapes,
     every edge function, forward and both backward forms (directed graph: two passes; symmetric: one),
     with and without values, against the oracle element by element."""
     os.environ.pop("ISP_FUSED_W", None)
