@@ -38,6 +38,11 @@ struct policy_has_val2 : std::false_type {};
 template <class P>
 struct policy_has_val2<P, std::void_t<decltype(P::HAS_VAL2)>> : std::bool_constant<P::HAS_VAL2> {};
 
+template <class P, class = void>
+struct policy_sparse_rows : std::bool_constant<!P::PER_ENTRY> {};
+template <class P>
+struct policy_sparse_rows<P, std::void_t<decltype(P::SPARSE_ROWS)>> : std::bool_constant<P::SPARSE_ROWS> {};
+
 template <class P, int LPG, int W, bool ADDR32>
 __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __restrict__ indptr,
                                           const int32_t* __restrict__ indices, const float* __restrict__ values,
@@ -61,9 +66,10 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   if (it.skip) return;
   gs_wave_lds& L = lds.w[w];
   // The policies with row results skip empty rows altogether (no step; the list of non-empty rows in L.ss
-  // says where each row end belongs): directed graphs leave many rows empty (half of them in the FusedMM
-  // benchmark graph).  The per-entry policy has no row results and keeps the plain table.
-  constexpr bool sparse_rows = !P::PER_ENTRY;
+  // says which row the steps between two row ends belong to): directed graphs leave many rows empty (half of
+  // them in the FusedMM benchmark graph).  The per-entry policy says which table it wants (SPARSE_ROWS): the
+  // list costs one LDS read per step, an empty row's step a whole step.
+  constexpr bool sparse_rows = policy_sparse_rows<P>::value;
   constexpr int PAD = W == 4 ? U : NB;  // (the ring of one-step buffers runs whole rounds only)
   const int n_steps = values ? gs_prepare<G, true, sparse_rows, PAD>(it, indptr, indices, values, L, lane)
                              : gs_prepare<G, false, sparse_rows, PAD>(it, indptr, indices, values, L, lane);

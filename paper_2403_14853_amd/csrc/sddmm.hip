@@ -93,10 +93,11 @@ __global__ void __launch_bounds__(ISP_WG) k_sddmm(isp_view A, const int64_t* __r
 // ADD: this pass covers a window of the feature columns and adds its partial dot product to out.
 // The entry's staged value multiplies the dot product; it is 1 when the kernel is given no values
 // (unscaled SDDMM, or a matrix without stored values).
-template <bool ADD_ = false>
+// SPARSE: empty rows own no step (worth it where many rows are empty).
+template <bool ADD_ = false, bool SPARSE_ = false>
 struct sddmm_policy {
   static constexpr int NSRC = 1, NROW = 1, STEPS = 4;
-  static constexpr bool PER_ENTRY = true, ACCUMULATE = false, ADD = ADD_;
+  static constexpr bool PER_ENTRY = true, ACCUMULATE = false, ADD = ADD_, SPARSE_ROWS = SPARSE_;
   struct args { const float* src[1]; int64_t lds_[1]; const float* rowop[1]; int64_t ldr[1]; float* out_entry; };
   template <int LPG, int W>
   __device__ static inline float entry(float a, const float (&x)[1][W], const float (&r)[1][W], const lane_cols<W / 4>& lc) {
@@ -104,13 +105,13 @@ struct sddmm_policy {
   }
 };
 
-template <int LPG, int W, bool ADDR32, bool ADD>
+template <int LPG, int W, bool ADDR32, bool ADD, bool SPARSE>
 __global__ void __launch_bounds__(ISP_WG) k_sddmm_grouped(isp_view A, const int64_t* __restrict__ indptr,
                                                           const int32_t* __restrict__ indices,
                                                           const float* __restrict__ values,
-                                                          typename sddmm_policy<ADD>::args pa, int d, int k_lo) {
+                                                          typename sddmm_policy<ADD, SPARSE>::args pa, int d, int k_lo) {
   __shared__ gs_lds lds;
-  fused_grouped_item<sddmm_policy<ADD>, LPG, W, ADDR32>(A, indptr, indices, values, pa, d, nullptr, 0, lds, k_lo);
+  fused_grouped_item<sddmm_policy<ADD, SPARSE>, LPG, W, ADDR32>(A, indptr, indices, values, pa, d, nullptr, 0, lds, k_lo);
 }
 
 // One pass over the feature columns [k_lo, d_hi) (d_hi - k_lo <= W * LPG); add: accumulate into out.
@@ -123,14 +124,19 @@ isp_status launch_grouped(const isp_csr* A, const float* U, int64_t ldu, const f
   const unsigned grid = (unsigned)((n_items + ISP_WAVES_PER_WG - 1) / ISP_WAVES_PER_WG);
   const float* vals = scale ? v.values : nullptr;
   const bool a32 = fused_offsets_fit_32(v.n_cols, ldv, d_hi);
-  typename sddmm_policy<false>::args pa{{V}, {ldv}, {U}, {ldu}, out};  // (the same members for either ADD)
-#define ISP_GO(A32, AD)                                                                                  \
-  do {                                                                                                   \
-    typename sddmm_policy<AD>::args pb{{pa.src[0]}, {pa.lds_[0]}, {pa.rowop[0]}, {pa.ldr[0]}, pa.out_entry}; \
-    k_sddmm_grouped<LPG, W, A32, AD><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, vals, pb, d_hi, k_lo); \
+  typename sddmm_policy<false>::args pa{{V}, {ldv}, {U}, {ldu}, out};  // (the same members in every variant)
+  // rows without entries: skipped through the list of non-empty rows when they are an eighth of all rows or more
+  // (the list costs one LDS read per step, an empty row's step a whole step)
+  const bool sparse = A->info.bin_rows[0] * 8 >= A->info.n_rows;
+#define ISP_GO(A32, AD, SP)                                                                                  \
+  do {                                                                                                       \
+    typename sddmm_policy<AD, SP>::args pb{{pa.src[0]}, {pa.lds_[0]}, {pa.rowop[0]}, {pa.ldr[0]}, pa.out_entry}; \
+    k_sddmm_grouped<LPG, W, A32, AD, SP><<<grid, ISP_WG, 0, s>>>(v, v.indptr, v.indices, vals, pb, d_hi, k_lo); \
   } while (0)
-  if (a32) { if (add) ISP_GO(true, true); else ISP_GO(true, false); }
-  else { if (add) ISP_GO(false, true); else ISP_GO(false, false); }
+#define ISP_GO2(A32, AD) do { if (sparse) ISP_GO(A32, AD, true); else ISP_GO(A32, AD, false); } while (0)
+  if (a32) { if (add) ISP_GO2(true, true); else ISP_GO2(true, false); }
+  else { if (add) ISP_GO2(false, true); else ISP_GO2(false, false); }
+#undef ISP_GO2
 #undef ISP_GO
   ISP_LAUNCH_CHECK();
   return ISP_OK;
