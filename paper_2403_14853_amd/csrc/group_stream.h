@@ -66,12 +66,13 @@ __device__ inline int wave_exclusive_scan_i(int v, int lane, int* total) {
 // a multiple of PAD (the caller's steps per issue, at most GS_U) with null steps (no live entry, not a
 // row end); 0 when the item has no entries.
 // SPARSE_ROWS: empty rows own no step, and ss ends up holding the local indices of the non-empty rows, in
-// order (the kernel zeroes the empty rows' outputs itself); otherwise an empty row owns one step without
-// entries.  rp holds the rows' start offsets.
+// order, then one spare 0, then the local indices of the empty rows (the kernel writes their outputs itself:
+// gs_empty_rows below); otherwise an empty row owns one step without entries.  rp holds the rows' start offsets.
+// *n_live (optional): the number of non-empty rows of a row block (SPARSE_ROWS only).
 template <int G, bool HAS_VAL, bool SPARSE_ROWS = false, int PAD = GS_U>
 __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict__ indptr,
                                  const int32_t* __restrict__ indices, const float* __restrict__ values,
-                                 gs_wave_lds& L, int lane) {
+                                 gs_wave_lds& L, int lane, int* n_live_out = nullptr) {
   constexpr bool sparse_rows = SPARSE_ROWS;
   static_assert(PAD >= 1 && PAD <= GS_U, "the step table has room for GS_U null steps");
   int2* __restrict__ ent = L.ent;
@@ -111,6 +112,7 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
       step[s] = s < n_steps ? gs_pack(s * G, left >= G ? G : left, s + 1 == n_steps) : (gs_u16)0;
     }
     wave_lds_sync();
+    if (n_live_out) *n_live_out = 1;
     return n_padded;
   }
   for (int r = lane; r <= n_rows; r += ISP_WAVE) rp[r] = (gs_u16)(indptr[it.row + r] - it.p);
@@ -120,7 +122,7 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   constexpr int CHUNKS = GS_MAX_ROWS / ISP_WAVE;
   int carry = 0, rank[CHUNKS];
 #pragma unroll
-  for (int ci = 0; ci < CHUNKS; ++ci) rank[ci] = -1;
+  for (int ci = 0; ci < CHUNKS; ++ci) rank[ci] = -1 - GS_MAX_ROWS - 1;  // (no row)
 #pragma unroll
   for (int ci = 0; ci < CHUNKS; ++ci) {
     if (ci * ISP_WAVE >= n_rows) break;  // (most items hold fewer than 64 rows: one scan)
@@ -134,7 +136,8 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
     int tot;
     const int ex = wave_exclusive_scan_i(v, lane, &tot);
     if (r < n_rows) ss[r] = (gs_u16)((carry + ex) & 0xffff);
-    rank[ci] = v ? (carry + ex) >> 16 : -1;
+    // non-empty rows before this one; an empty row keeps it as -1 - (that number)
+    rank[ci] = v ? (carry + ex) >> 16 : (r < n_rows ? -1 - ((carry + ex) >> 16) : -1 - GS_MAX_ROWS - 1);
     carry += tot;
   }
   const int n_steps = carry & 0xffff;
@@ -163,11 +166,16 @@ __device__ inline int gs_prepare(const item_range& it, const int64_t* __restrict
   // Without SPARSE_ROWS every row owns a step and the k-th row end belongs to row k.
   if constexpr (sparse_rows) {
 #pragma unroll
-    for (int ci = 0; ci < CHUNKS; ++ci)
-      if (rank[ci] >= 0) ss[rank[ci]] = (gs_u16)(ci * ISP_WAVE + lane);
+    for (int ci = 0; ci < CHUNKS; ++ci) {
+      const int r = ci * ISP_WAVE + lane;
+      if (rank[ci] >= 0) ss[rank[ci]] = (gs_u16)r;
+      // the empty rows behind the spare entry: row r has r - (non-empty rows before it) empty rows before it
+      else if (rank[ci] >= -1 - GS_MAX_ROWS) ss[n_live + 1 + r - (-1 - rank[ci])] = (gs_u16)r;
+    }
     if (lane == 0) ss[n_live] = 0;
     wave_lds_sync();
   }
+  if (n_live_out) *n_live_out = n_live;
   return n_padded;
 }
 

@@ -71,8 +71,9 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
   // list costs one LDS read per step, an empty row's step a whole step.
   constexpr bool sparse_rows = policy_sparse_rows<P>::value;
   constexpr int PAD = W == 4 ? U : NB;  // (the ring of one-step buffers runs whole rounds only)
-  const int n_steps = values ? gs_prepare<G, true, sparse_rows, PAD>(it, indptr, indices, values, L, lane)
-                             : gs_prepare<G, false, sparse_rows, PAD>(it, indptr, indices, values, L, lane);
+  int n_live = 0;  // non-empty rows of a row block
+  const int n_steps = values ? gs_prepare<G, true, sparse_rows, PAD>(it, indptr, indices, values, L, lane, &n_live)
+                             : gs_prepare<G, false, sparse_rows, PAD>(it, indptr, indices, values, L, lane, &n_live);
 
   const int g = lane / LPG, q = lane % LPG;
   lane_cols<NV> lc;  // this lane's columns: in range?  offset of the first (0 when out of range)
@@ -107,10 +108,9 @@ __device__ inline void fused_grouped_item(const isp_view& A, const int64_t* __re
         store_vec<4>(o + lc.off[v], t);
       }
   };
-  if (!P::PER_ENTRY && !P::ACCUMULATE && listed) {  // outputs of the empty rows
-    const int n_rows = it.row_last - it.row;
-    for (int r = g; r < n_rows; r += G)
-      if (L.rp[r + 1] == L.rp[r]) store_row(it.row + r);
+  if (!P::PER_ENTRY && !P::ACCUMULATE && listed) {  // outputs of the empty rows, listed behind the non-empty ones
+    const int n_empty = it.row_last - it.row - n_live;
+    for (int i = g; i < n_empty; i += G) store_row(it.row + (int)L.ss[n_live + 1 + i]);
   }
 
   auto finish_row = [&]() {

@@ -94,7 +94,8 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   const item_range it = locate_item(A, indptr, item);
   if (it.skip) return;
   gs_wave_lds& L = lds.w[w];
-  const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane);  // multiple of U
+  int n_live = 0;  // non-empty rows of a row block
+  const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane, &n_live);  // multiple of U
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_base + (slice * LPG + q) * VEC;
@@ -125,9 +126,8 @@ __global__ void __launch_bounds__(ISP_WG) __attribute__((amdgpu_waves_per_eu(4, 
   for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
   const bool listed = SPARSE_ROWS && !it.is_seg;  // else every row owns a step and the k-th row end is row k's
   if (listed && lane_on && !pieces) {  // the empty rows' outputs (also their mean); a piece is never empty
-    const int n_rows = it.row_last - it.row;
-    for (int r = g; r < n_rows; r += G)
-      if (L.rp[r + 1] == L.rp[r]) store_vec<VEC>(out + (int64_t)(it.row + r) * ldo, acc);
+    const int n_empty = it.row_last - it.row - n_live;  // they are listed behind the non-empty rows
+    for (int i = g; i < n_empty; i += G) store_vec<VEC>(out + (int64_t)(it.row + (int)L.ss[n_live + 1 + i]) * ldo, acc);
   }
   // local index of the row the next row end belongs to; with the list it is read one row ahead so that a
   // row's store does not wait for it (the list ends with a spare entry)

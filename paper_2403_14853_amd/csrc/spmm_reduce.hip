@@ -110,7 +110,8 @@ __global__ void __launch_bounds__(ISP_WG) k_minmax_grouped(isp_view A, const int
   const item_range it = locate_item(A, indptr, item);
   if (it.skip) return;
   gs_wave_lds& L = lds.w[w];
-  const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane);  // multiple of U
+  int n_live = 0;  // non-empty rows of a row block
+  const int n_steps = gs_prepare<G, HAS_VAL, SPARSE_ROWS>(it, indptr, indices, values, L, lane, &n_live);  // multiple of U
 
   const int g = lane / LPG, q = lane % LPG;
   const int col = k_base + (slice * LPG + q) * 4;
@@ -137,10 +138,9 @@ __global__ void __launch_bounds__(ISP_WG) k_minmax_grouped(isp_view A, const int
       *reinterpret_cast<int4*>(arg + (int64_t)row * d + col) = make_int4(where[0], where[1], where[2], where[3]);
     }
   };
-  if (listed && lane_on) {  // empty rows: value 0, position -1
-    const int n_rows = it.row_last - it.row;
-    for (int r = g; r < n_rows; r += G)
-      if (L.rp[r + 1] == L.rp[r]) store_row(it.row + r);
+  if (listed && lane_on) {  // empty rows (listed behind the non-empty ones): value 0, position -1
+    const int n_empty = it.row_last - it.row - n_live;
+    for (int i = g; i < n_empty; i += G) store_row(it.row + (int)L.ss[n_live + 1 + i]);
   }
   int k_done = 0;
   int r_next = listed ? (int)L.ss[0] : 0;
