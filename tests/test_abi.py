@@ -73,3 +73,23 @@ def test_header_is_plain_c(repo_root, tmp_path):
                    "}\n")
     subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only",
                            "-I", os.path.join(repo_root, "include"), str(src)])
+
+
+def test_counter_records_parse_with_their_calibration():
+    """profiles/counter_records.txt, which bench.py reads for roofline.traffic: the calibration lines are really
+    lines of their own (FETCH_SIZE counts half the bytes on this part, so its factor is 2), every benchmark
+    configuration has a record, and a record's bytes are at least the operands of its workload moved once."""
+    import bench
+    path = os.path.join(os.path.dirname(os.path.abspath(bench.__file__)), "profiles", "counter_records.txt")
+    lines = [l.split("#")[0].split() for l in open(path)]
+    factors = {f[0]: float(f[1]) for f in lines if len(f) == 2}
+    assert factors == {"fetch_factor": 2.0, "write_factor": 1.0}
+    shapes = {"c1-rmat169k-d128": (169343, 128), "c2-rmat233k-dense-d128": (232965, 128),
+              "c3-rmat2.4m-d128": (2449029, 128), "c4-rmat1m-d64-fusedmm": (1 << 20, 64)}
+    for workload, (n, d) in shapes.items():
+        kernel = "k_fused_grouped<g_fwd>" if workload.startswith("c4") else "k_spmm_grouped"
+        rec = bench.counter_record(workload, kernel)
+        assert rec is not None and rec["commit"], workload
+        assert rec["bytes"] == (2.0 * rec["fetch_kib"] + rec["write_kib"]) * 1024.0
+        assert rec["bytes"] > 2 * 4.0 * n * d, (workload, rec["bytes"])  # X read and Y written at least once
+        assert rec["write_kib"] * 1024.0 >= 4.0 * n * d * 0.95, workload   # Y is written whole
