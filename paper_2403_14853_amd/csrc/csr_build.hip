@@ -64,7 +64,11 @@ partition_params get_params(int64_t n_rows, int64_t n_cols, int64_t nnz) {
   // hub rows (segments of at most 384, pieces from 192 entries) keep more of each segment's gathers inside its
   // band (2.4 M columns: 5.30 -> 5.19 ms per SpMM, the other kernels 1-3 %); with few columns a band's popular
   // rows fit an L2 anyway and the longer segments win (233 k columns: SDDMM 3.21 vs 3.32 ms).
-  const int seg_cap = n_cols >= (1 << 19) ? 384 : 512;
+  // Measured again with the present kernels (segments 256 .. 512, smallest pieces 64 .. 256, on the three large
+  // benchmark graphs): segments of at most 320 and pieces from 128 entries are best or within 1 % of it for every
+  // kernel on every one of them (233 k columns: SpMM 2.68 -> 2.59 ms, SDDMM 2.71 -> 2.60 ms; 2.4 M columns:
+  // FusedMM 5.59 -> 5.41 ms; 1 M columns: FusedMM backward 1.36 -> 1.32 ms).
+  const int seg_cap = 320;
   int64_t auto_seg = (nnz + n_rows + slots - 1) / slots / 4;
   auto_seg = auto_seg < 80 ? 80 : (auto_seg > seg_cap ? seg_cap : auto_seg);
   const int auto_hub = 2 * auto_seg > 512 ? 512 : (int)(2 * auto_seg);
@@ -75,7 +79,9 @@ partition_params get_params(int64_t n_rows, int64_t n_cols, int64_t nnz) {
   p.bands = b;
   // (the lower limit bounds the number of segments, hence the partial-sum rows the workspace must hold)
   const int mp_lo = p.seg_len / 8 > 4 ? p.seg_len / 8 : 4;
-  p.min_piece = env_int("ISP_MIN_PIECE", p.seg_len / 2 > mp_lo ? p.seg_len / 2 : mp_lo, mp_lo, 1 << 20);
+  int mp = p.seg_len / 2 < 128 ? p.seg_len / 2 : 128;
+  if (mp < mp_lo) mp = mp_lo;
+  p.min_piece = env_int("ISP_MIN_PIECE", mp, mp_lo, 1 << 20);
   return p;
 }
 
@@ -562,6 +568,8 @@ partition_params cut_params(const partition_params& p1, int mid_t) {
   partition_params c = p1;
   c.hub_t = mid_t;
   const int room = 768 - derived_block_cost(p1, mid_t);  // longest row the derived matrix may have
+  // (the ordinary partition's segment length also bounds the pieces here: 320 against 384 measured 4.65 / 4.64 ms
+  // per SpMM on 2.4 M columns, 0.345 / 0.357 ms on 1 M columns at d = 64)
   if (c.seg_len > room) c.seg_len = room;
   // pieces of 64 entries or more, on up to 32 bands (measured on 2.4 M columns: smaller pieces fetch less but
   // pay it back in partial rows)
