@@ -32,7 +32,7 @@ struct partition_params {
   int min_piece;  // a hub row is cut into at most degree / min_piece bands
 };
 
-constexpr int MAX_BANDS = 32;
+constexpr int MAX_BANDS = 64;  // one piece per lane
 
 int env_int(const char* name, int dflt, int lo, int hi) {
   const char* s = getenv(name);
@@ -156,7 +156,8 @@ __device__ inline void wave_hub_pieces(const int32_t* __restrict__ indices, int6
     const int64_t t = __shfl_up(cut, o);
     if (lane >= o && t > cut) cut = t;
   }
-  const int64_t next = __shfl_down(cut, 1);
+  int64_t next = __shfl_down(cut, 1);
+  if (lane == ISP_WAVE - 1) next = b;  // (the last lane has no neighbour; it holds a piece only with 64 bands)
   *first = lane < br ? cut : b;
   *last = lane < br ? next : b;
 }
