@@ -109,7 +109,7 @@ isp_status isp_csr_build_workspace(int64_t n_rows, int64_t n_cols, int64_t nnz, 
  * degree; short rows are grouped into contiguous row blocks of about equal (nnz + rows); hub rows
  * (degree > hub threshold) are cut into segments of bounded length, at column-band boundaries first,
  * which are scheduled in column order (Section 1(b): balanced scheduling; Section 3.5: CSR operand).
- * For large matrices with many columns (8 Mi .. 256 Mi entries, >= 512 Ki columns) the tuned SpMM also gets a packed
+ * For large matrices with many columns (8 Mi .. 256 Mi entries, >= 64 Ki columns) the tuned SpMM also gets a packed
  * layout of its own: rows longer than 256 entries are cut into column-band pieces of 64 entries or more, and
  * the pieces, scheduled in column order, share work items with each other; that layout keeps a reordered copy
  * of the index and value arrays in the workspace (isp_csr_values_changed refreshes the values).

@@ -611,13 +611,15 @@ packed_layout make_packed_layout(int64_t n_rows, int64_t nnz, bool has_values, c
 }
 
 // Rows above this length are cut for the packed SpMM layout; 0 = no packed layout.  Chosen for large
-// matrices with many columns, where a column band of the dense operand is far larger than an L2: there the
-// pieces of mid-sized rows (too short to be work items, hence packed) gather from one band at a time like the
-// hub segments do.  ISP_MID_THRESHOLD overrides (0 disables).
+// matrices whose dense operand is far larger than an L2 (64 Ki columns or more): there the pieces of
+// mid-sized rows (too short to be work items, hence packed) gather from one band at a time like the hub
+// segments do.  Measured on 233 k columns / 115 M entries: 2.50 against 2.60 ms per SpMM; on 169 k columns /
+// 2.4 M entries it loses (0.125 against 0.113 ms: too few items per band), hence the lower size limit.
+// ISP_MID_THRESHOLD overrides (0 disables).
 // The layout costs workspace - a second copy of the entries, their source positions and one partial row per
 // piece: up to about 36 bytes per stored entry - so beyond 256 Mi entries it is left out as well.
 int mid_threshold(int64_t n_rows, int64_t n_cols, int64_t nnz, const partition_params& p1) {
-  const int dflt = (nnz >= ((int64_t)8 << 20) && nnz <= ((int64_t)256 << 20) && n_cols >= (1 << 19)) ? 256 : 0;
+  const int dflt = (nnz >= ((int64_t)8 << 20) && nnz <= ((int64_t)256 << 20) && n_cols >= (1 << 16)) ? 256 : 0;
   int t = env_int("ISP_MID_THRESHOLD", dflt, 0, 512);
   if (t > 0 && t < 8) t = 8;
   // the derived matrix's rows (short rows, pieces) must fit the grouped kernels' tables next to a block
