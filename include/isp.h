@@ -175,7 +175,9 @@ isp_status isp_csr_info(const isp_csr_t* A, isp_csr_info_t* info);
  *   max_d: the widest feature width the alias will be used with (sizes the partial rows of FusedMM beyond 256
  *     columns; wider calls still work, one 256-column group per launch).
  *   workspace: device memory, 256-byte aligned, isp_csr_alias_workspace bytes, borrowed until the alias is
- *     destroyed; it needs no clearing.  Config-3-sized graphs need about 1 KiB per row piece (under 1 GiB).
+ *     destroyed; it needs no clearing.  Size: 1 KiB per hub-row segment or row piece (isp_csr_info: n_segments,
+ *     spmm_pieces) of A and as much again for its cached transpose, plus one byte per stored entry when the
+ *     transpose exists - about 2 GiB for 124 M entries in 2.4 M rows.
  *   The alias takes over A's cached transpose as it is at this call: build it on A first if the alias is to
  *     run backward calls (isp_csr_transpose_cached on the alias returns it, or ISP_EINVAL if A had none).
  *   Destroy the alias (isp_csr_destroy) before A.  After isp_csr_values_changed(A) every alias made before is
